@@ -1,0 +1,121 @@
+/*
+ * CPU oracle, integer/index part (TEST INFRASTRUCTURE ONLY; never linked into
+ * or called by the product library).
+ *
+ * Explicit index loops, one statement per definition:
+ *   - the Ulysses all-to-all that turns the sequence-parallel layout (each rank
+ *     holds N/P tokens, all H heads) into the head-parallel layout (each rank
+ *     holds all N tokens, H/P heads) -- Section II-A -- written as its three
+ *     literal steps: build the send chunks, exchange them, lay the received
+ *     chunks out head-major;
+ *   - the V-Major active-projection selection of Section III-D in the
+ *     threshold-per-tile form this build measures: a tile of `T` consecutive
+ *     tokens is active when any element of the current value vectors differs
+ *     from the cached one by more than tau; active tiles are listed in
+ *     ascending order and their current values are gathered densely.
+ *
+ * All data are 16-bit patterns (bf16) copied without interpretation, except
+ * the selection's comparison, which widens bf16 to fp32 exactly and takes the
+ * decision in fp32 (the precision the GPU kernel decides in).
+ *
+ * Outer loops carry an OpenMP pragma; nothing is blocked, fused or reordered.
+ */
+#include <stdint.h>
+#include <string.h>
+#include <math.h>
+
+#define SLOT_SEND_MAJOR 0
+#define SLOT_RECV_MAJOR 1
+
+static inline int64_t slot_of(int r, int p, int P, int slot_order) {
+    /* chunk(r -> p): in rank r's send buffer (SEND_MAJOR) or rank p's receive buffer (RECV_MAJOR) */
+    return slot_order == SLOT_SEND_MAJOR ? (int64_t)r * P + p : (int64_t)p * P + r;
+}
+
+/* chunk(r->p)[n][hl][i] = X[r*Ns + n][p*Hp + hl][i], for source ranks r in the range */
+void oracle_a2a_pack(const uint16_t* x, uint16_t* xbuf, int N, int H, int d, int P,
+                     int rank_begin, int rank_count, int slot_order) {
+    const int Ns = N / P, Hp = H / P;
+    const int64_t chunk = (int64_t)Ns * Hp * d;
+#pragma omp parallel for schedule(static)
+    for (int r = rank_begin; r < rank_begin + rank_count; ++r)
+        for (int p = 0; p < P; ++p) {
+            uint16_t* c = xbuf + slot_of(r, p, P, slot_order) * chunk;
+            for (int n = 0; n < Ns; ++n)
+                for (int hl = 0; hl < Hp; ++hl)
+                    for (int i = 0; i < d; ++i)
+                        c[((int64_t)n * Hp + hl) * d + i] =
+                            x[((int64_t)(r * Ns + n) * H + (p * Hp + hl)) * d + i];
+        }
+}
+
+/* The exchange itself: what rank r sent to p becomes the r-th block rank p received. */
+void oracle_a2a_exchange(const uint16_t* send_major, uint16_t* recv_major, int N, int H, int d, int P) {
+    const int64_t chunk = (int64_t)(N / P) * (H / P) * d;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < P; ++r)
+        for (int p = 0; p < P; ++p)
+            memcpy(recv_major + ((int64_t)p * P + r) * chunk,
+                   send_major + ((int64_t)r * P + p) * chunk, (size_t)chunk * sizeof(uint16_t));
+}
+
+/* Y[p*Hp + hl][r*Ns + n][i] = chunk(r->p)[n][hl][i], for destination ranks p in the range */
+void oracle_a2a_unpack(const uint16_t* xbuf, uint16_t* y, int N, int H, int d, int P,
+                       int rank_begin, int rank_count, int slot_order) {
+    const int Ns = N / P, Hp = H / P;
+    const int64_t chunk = (int64_t)Ns * Hp * d;
+#pragma omp parallel for schedule(static)
+    for (int p = rank_begin; p < rank_begin + rank_count; ++p)
+        for (int r = 0; r < P; ++r) {
+            const uint16_t* c = xbuf + slot_of(r, p, P, slot_order) * chunk;
+            for (int n = 0; n < Ns; ++n)
+                for (int hl = 0; hl < Hp; ++hl)
+                    for (int i = 0; i < d; ++i)
+                        y[((int64_t)(p * Hp + hl) * N + (r * Ns + n)) * d + i] =
+                            c[((int64_t)n * Hp + hl) * d + i];
+        }
+}
+
+static inline float bf16_to_f32(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/*
+ * cur, prev: [S][N][W].  Tile t = tokens [t*T, (t+1)*T) of every slab s.
+ * flag[t] = 1 iff some element has NOT(|cur - prev| <= tau)   (so NaN counts as changed).
+ * idx: ascending active tile ids; compact[s][j*T + (n - t*T)][w] = cur[s][n][w] for the j-th
+ * active tile t, for j < cap_tiles; the compact buffer is [S][cap_tiles*T][W].
+ * Returns the number of active tiles (also beyond cap_tiles).
+ */
+int oracle_vmajor_select(int S, int N, int W, int T, const uint16_t* cur, const uint16_t* prev,
+                         float tau, int32_t* flags, int32_t* idx, uint16_t* compact, int cap_tiles) {
+    const int NT = N / T;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < NT; ++t) {
+        int active = 0;
+        for (int s = 0; s < S; ++s)
+            for (int n = t * T; n < (t + 1) * T; ++n)
+                for (int w = 0; w < W; ++w) {
+                    const int64_t e = ((int64_t)s * N + n) * W + w;
+                    const float diff = fabsf(bf16_to_f32(cur[e]) - bf16_to_f32(prev[e]));
+                    if (!(diff <= tau)) active = 1;
+                }
+        flags[t] = active;
+    }
+    int n_active = 0;
+    for (int t = 0; t < NT; ++t) {
+        if (!flags[t]) continue;
+        const int j = n_active++;
+        idx[j] = t;
+        if (compact && j < cap_tiles)
+            for (int s = 0; s < S; ++s)
+                for (int n = 0; n < T; ++n)
+                    for (int w = 0; w < W; ++w)
+                        compact[((int64_t)s * cap_tiles * T + (int64_t)j * T + n) * W + w] =
+                            cur[((int64_t)s * N + (int64_t)t * T + n) * W + w];
+    }
+    return n_active;
+}
