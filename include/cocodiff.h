@@ -1,0 +1,178 @@
+/*
+ * cocodiff.h -- C ABI of the MI355X (gfx950) library for the per-rank Ulysses
+ * attention-input path that CoCoDiff reorganises.
+ *
+ * The path, per transformer layer (paper Sections II-A, II-B, III-C, III-D):
+ *   1. project a shard of hidden states to Q, K, V (V can be computed alone,
+ *      first: the V-First schedule),
+ *   2. RMS-normalise Q and K per (token, head) and rotate them by the token's
+ *      grid position (axial RoPE); V gets neither,
+ *   3. build the all-to-all send chunks ("pack"), and lay the received chunks
+ *      out head-major ("unpack"): sequence-parallel -> head-parallel layout,
+ *   4. V-Major selection: find the 16-token tiles of V that changed since the
+ *      cached previous denoising step, list them in ascending order and gather
+ *      their current values densely.
+ *
+ * One GPU runs all P logical ranks' shares; `rank_begin`/`rank_count` choose
+ * which ranks' shares one call covers, so a caller can run one rank alone or
+ * all P at once.  With all ranks in one HBM the exchange between pack and
+ * unpack is a re-indexing of the same buffer (see `slot_order`).
+ *
+ * Conventions for every entry point
+ *   - returns 0 (COCODIFF_OK) or a negative COCODIFF_ERR_* code; on error nothing
+ *     has been enqueued and cocodiff_last_error() holds a message (thread-local);
+ *   - every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned,
+ *     unless the comment says "host"; `shape`/`rope` structs are HOST pointers read
+ *     during the call;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream); the call does not synchronise and does not allocate;
+ *   - inputs are not modified; outputs must not alias inputs unless "in place" is stated;
+ *   - bf16 values are raw 16-bit patterns (cocodiff_bf16); float arithmetic is fp32
+ *     inside the kernels with one round-to-nearest-even to bf16 at each kernel's output.
+ */
+#ifndef COCODIFF_H
+#define COCODIFF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COCODIFF_API __attribute__((visibility("default")))
+
+typedef uint16_t cocodiff_bf16;
+
+enum {
+    COCODIFF_OK = 0,
+    COCODIFF_ERR_NULL = -1,     /* a required pointer is NULL */
+    COCODIFF_ERR_SHAPE = -2,    /* shape rule violated (see cocodiff_shape) */
+    COCODIFF_ERR_ALIGN = -3,    /* a data pointer is not 16-byte aligned */
+    COCODIFF_ERR_CAPACITY = -4, /* workspace too small or cap_tiles < 1 */
+    COCODIFF_ERR_HIP = -5       /* a launch failed; the message holds the HIP error string */
+};
+
+/* Where chunk(r -> p), the block rank r sends to rank p, lives in the exchange buffer. */
+enum {
+    COCODIFF_SEND_MAJOR = 0, /* slot r*P + p: rank r's contiguous send buffer (state before the exchange) */
+    COCODIFF_RECV_MAJOR = 1  /* slot p*P + r: rank p's contiguous receive buffer (pack does a one-sided put) */
+};
+
+/*
+ * Problem shape (Section II-A notation: N tokens, H heads of d, P ranks).
+ * Rules (else COCODIFF_ERR_SHAPE): all > 0; D == H*d; d % 8 == 0; N % P == 0; H % P == 0;
+ * (N/P) % 16 == 0 (the paper's even-split rule, plus whole 16-token tiles per rank);
+ * 0 <= rank_begin, rank_count >= 1, rank_begin + rank_count <= P.
+ * Rank r owns tokens [r*N/P, (r+1)*N/P) in the sequence-parallel layout and heads
+ * [r*H/P, (r+1)*H/P) in the head-parallel layout.
+ */
+typedef struct cocodiff_shape {
+    int32_t N, D, H, d, P;
+    int32_t rank_begin, rank_count;
+} cocodiff_shape;
+
+/*
+ * Axial rotary embedding (Section II-B).  Token n has grid coordinates in row-major order,
+ * last axis fastest.  Adjacent elements (2j, 2j+1) of a head form pair j; the first pairs[0]
+ * pairs rotate with axis 0, the next pairs[1] with axis 1, ...; pair j' (local index) of axis a
+ * turns by coord_a * theta^(-j'/pairs[a]).
+ * Rules: n_axes in {1,2,3}; product of grid[0..n_axes) == N; sum of pairs == d/2.
+ * `cs` is a DEVICE table: for axis a at float offset 2 * sum_{b<a} grid[b]*pairs[b],
+ * [grid[a]][pairs[a]][2] = (cos, sin) in fp32 -- exactly what cocodiff_rope_table_fill writes.
+ */
+typedef struct cocodiff_rope {
+    int32_t n_axes;
+    int32_t grid[3];
+    int32_t pairs[3];
+    float theta;
+    const float* cs;
+} cocodiff_rope;
+
+/*
+ * Step 1 -- projection (Section II-B: q_i = h_i W_Q, k_i = h_i W_K, v_i = h_i W_V; no bias).
+ * x [N][D]; w* [D_out = D][D_in = D] (output-major: y[n][o] = sum_k x[n][k] * w[o][k]);
+ * q, k, v [N][D] = [N][H][d].  Rows of the ranks in the range are computed; other rows untouched.
+ * Any of the pairs (wq,q), (wk,k), (wv,v) may be NULL/NULL = skip that tensor, so V alone first
+ * and then Q,K is the V-First order of Section III-C; at least one pair must be given, and a
+ * pair given half (weight without output or the reverse) is COCODIFF_ERR_NULL.
+ * bf16 inputs, fp32 accumulation on the matrix cores, one RNE rounding to bf16.
+ */
+COCODIFF_API int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                      const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                      cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, void* stream);
+
+/*
+ * Step 2 -- Q/K normalisation + RoPE (Section II-B; RMSNorm as in Section III-C), IN PLACE.
+ * For each given tensor t in {q, k} ([N][H][d]), each token of the rank range, each head:
+ * y = x / sqrt(mean(x^2) + eps) * gamma_t, then the rotation of cocodiff_rope at the token's
+ * GLOBAL index.  gamma_q, gamma_k: [d] bf16, shared by all heads.  q or k may be NULL (skipped,
+ * its gamma is then ignored); both NULL is COCODIFF_ERR_NULL.  V is never touched.
+ * Extra shape rule: d/8 must be a power of two (d in 8..512) and D/8 a divisor or multiple of 64.
+ */
+COCODIFF_API int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf16* q, cocodiff_bf16* k,
+                          const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                          const cocodiff_rope* rope, void* stream);
+
+/*
+ * Step 3a -- pack (Section II-A all-to-all, sender side; Section III-B "tensor preparation").
+ * x_seq [N][H][d] -> xbuf, P*P chunks of [N/P][H/P][d]:
+ *   chunk(r->p)[n][hl][i] = x_seq[r*N/P + n][p*H/P + hl][i]   for SOURCE ranks r in the range.
+ * xbuf holds N*D elements; chunks of other source ranks are not written.
+ */
+COCODIFF_API int cocodiff_a2a_pack(const cocodiff_shape* shape, const cocodiff_bf16* x_seq, cocodiff_bf16* xbuf,
+                      int slot_order, void* stream);
+
+/*
+ * Step 3b -- unpack (receiver side): xbuf -> x_hs [H][N][d] (head-parallel, head-major):
+ *   x_hs[p*H/P + hl][r*N/P + n][i] = chunk(r->p)[n][hl][i]   for DESTINATION ranks p in the range.
+ * With the same slot_order as the pack, pack + unpack is the whole all-to-all:
+ * x_hs[h][n][i] == x_seq[n][h][i].
+ */
+COCODIFF_API int cocodiff_a2a_unpack(const cocodiff_shape* shape, const cocodiff_bf16* xbuf, cocodiff_bf16* x_hs,
+                        int slot_order, void* stream);
+
+/*
+ * Step 4 -- V-Major active-tile selection (Section III-D, threshold-per-tile form).
+ * v_cur, v_prev: [S][N][W] bf16 (head-parallel: S = H, W = d; sequence layout: S = 1, W = D).
+ * Tile t = tokens [t*tile_tokens, (t+1)*tile_tokens) of every slab s; NT = N / tile_tokens.
+ *   flags[t]      = 1 if some element of the tile has NOT(|v_cur - v_prev| <= tau) in fp32, else 0
+ *                   (NaN counts as changed; |diff| == tau does not).  [NT] int32, may be NULL.
+ *   active_idx[j] = id of the j-th active tile, ascending, j < n_active.  [NT] int32.
+ *   *n_active     = number of active tiles (device int32), also when it exceeds cap_tiles.
+ *   compact[s][j*tile_tokens + m][w] = v_cur[s][active_idx[j]*tile_tokens + m][w] for
+ *                   j < min(n_active, cap_tiles); [S][cap_tiles*tile_tokens][W]; NULL = indices only.
+ * Entries of active_idx and compact beyond n_active are unspecified.  v_prev is read-only.
+ * Rules: S, N, W, tile_tokens > 0; W % 8 == 0; N % tile_tokens == 0 (else COCODIFF_ERR_SHAPE);
+ * cap_tiles >= 1 when compact != NULL (else COCODIFF_ERR_CAPACITY).
+ * workspace: device scratch of at least cocodiff_vmajor_select_workspace_bytes(...) bytes.
+ */
+COCODIFF_API int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
+                           const cocodiff_bf16* v_cur, const cocodiff_bf16* v_prev, float tau,
+                           int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                           cocodiff_bf16* compact, int32_t cap_tiles,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of device scratch cocodiff_vmajor_select needs for this shape (0 on a bad shape). */
+COCODIFF_API size_t cocodiff_vmajor_select_workspace_bytes(int32_t S, int32_t N, int32_t W, int32_t tile_tokens);
+
+/* Host helpers (not on the hot path). */
+
+/* Bytes of the cos/sin table described at cocodiff_rope (0 on a bad description; `cs` is ignored). */
+COCODIFF_API size_t cocodiff_rope_table_bytes(const cocodiff_rope* rope);
+
+/* Fill a HOST buffer of cocodiff_rope_table_bytes(rope) bytes; angles and cos/sin are computed in
+ * fp64 and stored as fp32.  The caller uploads it and points rope->cs at the device copy. */
+COCODIFF_API int cocodiff_rope_table_fill(const cocodiff_rope* rope, float* host_out);
+
+/* Plain 128-bit copy kernel (dst[i] = src[i], `bytes` a multiple of 16): the calibration kernel the
+ * HBM-bound steps are priced against; used by the benchmark and the profiler-counter scaling. */
+COCODIFF_API int cocodiff_util_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+COCODIFF_API const char* cocodiff_version(void);
+COCODIFF_API const char* cocodiff_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COCODIFF_H */

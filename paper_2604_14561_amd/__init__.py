@@ -1,0 +1,22 @@
+"""MI355X-native per-rank Ulysses attention-input path (QKV projection, Q/K RMSNorm + RoPE,
+all-to-all pack/unpack, V-Major tile selection) as hand-written HIP behind a C ABI.
+
+``binding`` marshals arguments to ``libcocodiff.so``; ``build`` compiles it in-tree.
+"""
+from . import binding  # noqa: F401
+from .binding import (  # noqa: F401
+    RECV_MAJOR,
+    SEND_MAJOR,
+    CocodiffError,
+    Rope,
+    Shape,
+    a2a_pack,
+    a2a_unpack,
+    qk_norm_rope,
+    qkv_proj,
+    rope_table,
+    util_copy,
+    version,
+    vmajor_select,
+    vmajor_select_workspace_bytes,
+)

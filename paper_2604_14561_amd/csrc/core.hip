@@ -1,0 +1,120 @@
+// Error channel, shape validation, host helpers (RoPE table) and the calibration copy kernel.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "internal.h"
+
+namespace cocodiff {
+
+static thread_local char g_last_error[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_last_error, sizeof g_last_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_shape(const cocodiff_shape* s) {
+    if (!s) return fail(COCODIFF_ERR_NULL, "shape is NULL");
+    if (s->N <= 0 || s->D <= 0 || s->H <= 0 || s->d <= 0 || s->P <= 0)
+        return fail(COCODIFF_ERR_SHAPE, "N, D, H, d, P must be positive (N=%d D=%d H=%d d=%d P=%d)",
+                    s->N, s->D, s->H, s->d, s->P);
+    if ((int64_t)s->H * s->d != s->D)
+        return fail(COCODIFF_ERR_SHAPE, "D (%d) != H*d (%d*%d)", s->D, s->H, s->d);
+    if (s->d % 8) return fail(COCODIFF_ERR_SHAPE, "d (%d) must be a multiple of 8", s->d);
+    if (s->N % s->P) return fail(COCODIFF_ERR_SHAPE, "N (%d) must divide evenly over P (%d) ranks", s->N, s->P);
+    if (s->H % s->P) return fail(COCODIFF_ERR_SHAPE, "H (%d) must divide evenly over P (%d) ranks", s->H, s->P);
+    if ((s->N / s->P) % 16)
+        return fail(COCODIFF_ERR_SHAPE, "tokens per rank (%d) must be a multiple of 16", s->N / s->P);
+    if (s->rank_begin < 0 || s->rank_count < 1 || (int64_t)s->rank_begin + s->rank_count > s->P)
+        return fail(COCODIFF_ERR_SHAPE, "rank range [%d, %d+%d) outside [0, %d)", s->rank_begin,
+                    s->rank_begin, s->rank_count, s->P);
+    return COCODIFF_OK;
+}
+
+int check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return COCODIFF_OK;
+}
+
+static int check_rope_desc(const cocodiff_rope* r) {
+    if (!r) return fail(COCODIFF_ERR_NULL, "rope is NULL");
+    if (r->n_axes < 1 || r->n_axes > 3) return fail(COCODIFF_ERR_SHAPE, "rope n_axes (%d) must be 1..3", r->n_axes);
+    for (int a = 0; a < r->n_axes; ++a)
+        if (r->grid[a] <= 0 || r->pairs[a] <= 0)
+            return fail(COCODIFF_ERR_SHAPE, "rope axis %d: grid (%d) and pairs (%d) must be positive", a,
+                        r->grid[a], r->pairs[a]);
+    if (!(r->theta > 0.f)) return fail(COCODIFF_ERR_SHAPE, "rope theta must be positive");
+    return COCODIFF_OK;
+}
+
+// 16-byte vectors, grid-stride; the loop is unrolled by four so each lane keeps four loads in flight.
+__global__ void __launch_bounds__(256) copy_kernel(const vec16* __restrict__ src, vec16* __restrict__ dst, size_t n_vec) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        vec16 a = ld_nt(src + i);
+        vec16 b = ld_nt(src + i + stride);
+        vec16 c = ld_nt(src + i + 2 * stride);
+        vec16 d = ld_nt(src + i + 3 * stride);
+        st_nt(dst + i, a);
+        st_nt(dst + i + stride, b);
+        st_nt(dst + i + 2 * stride, c);
+        st_nt(dst + i + 3 * stride, d);
+    }
+    for (; i < n_vec; i += stride) dst[i] = src[i];
+}
+
+}  // namespace cocodiff
+
+using namespace cocodiff;
+
+extern "C" {
+
+const char* cocodiff_version(void) { return "cocodiff-mi355x 0.1 (gfx950)"; }
+
+const char* cocodiff_last_error(void) { return g_last_error; }
+
+size_t cocodiff_rope_table_bytes(const cocodiff_rope* rope) {
+    if (check_rope_desc(rope) != COCODIFF_OK) return 0;
+    size_t n = 0;
+    for (int a = 0; a < rope->n_axes; ++a) n += (size_t)rope->grid[a] * rope->pairs[a] * 2;
+    return n * sizeof(float);
+}
+
+int cocodiff_rope_table_fill(const cocodiff_rope* rope, float* host_out) {
+    int rc = check_rope_desc(rope);
+    if (rc != COCODIFF_OK) return rc;
+    if (!host_out) return fail(COCODIFF_ERR_NULL, "host_out is NULL");
+    float* out = host_out;
+    for (int a = 0; a < rope->n_axes; ++a) {
+        const int pa = rope->pairs[a];
+        for (int c = 0; c < rope->grid[a]; ++c)
+            for (int j = 0; j < pa; ++j) {
+                const double omega = std::pow((double)rope->theta, -(double)j / (double)pa);
+                const double phi = (double)c * omega;
+                *out++ = (float)std::cos(phi);
+                *out++ = (float)std::sin(phi);
+            }
+    }
+    return COCODIFF_OK;
+}
+
+int cocodiff_util_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst) return fail(COCODIFF_ERR_NULL, "copy: NULL pointer");
+    if (!aligned16(src) || !aligned16(dst)) return fail(COCODIFF_ERR_ALIGN, "copy: pointers must be 16-byte aligned");
+    if (bytes % 16) return fail(COCODIFF_ERR_SHAPE, "copy: bytes (%zu) must be a multiple of 16", bytes);
+    if (bytes == 0) return COCODIFF_OK;
+    const size_t n_vec = bytes / 16;
+    size_t blocks = (n_vec + 256 * 4 - 1) / (256 * 4);
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream),
+                       (const vec16*)src, (vec16*)dst, n_vec);
+    return check_launch("copy_kernel");
+}
+
+}  // extern "C"

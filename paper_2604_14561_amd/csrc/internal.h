@@ -1,0 +1,49 @@
+// Internal helpers shared by the HIP sources of libcocodiff (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/cocodiff.h"
+
+namespace cocodiff {
+
+// Record a message for cocodiff_last_error() on this thread and return `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
+// Shape rules of cocodiff_shape; returns COCODIFF_OK or records the violated rule.
+int check_shape(const cocodiff_shape* s);
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Check the launch that was just issued.
+int check_launch(const char* what);
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// ---- device helpers -------------------------------------------------------
+
+// One 16-byte vector (8 bf16), the unit every kernel moves; a native vector type, so the
+// non-temporal load/store builtins accept it.
+typedef uint32_t __attribute__((ext_vector_type(4))) vec16;
+
+__device__ __forceinline__ vec16 ld_nt(const vec16* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void st_nt(vec16* p, vec16 v) { __builtin_nontemporal_store(v, p); }
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// Two bf16 packed in a 32-bit word: element 0 in the low half.
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Round two floats to bf16 (nearest even; gfx950 has a packed convert) and pack them, a in the low half.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+    f32x2_t f = {a, b};
+    bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+}  // namespace cocodiff

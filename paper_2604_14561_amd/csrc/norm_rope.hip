@@ -1,0 +1,200 @@
+// Q/K RMSNorm fused with axial RoPE, in place (paper Section II-B; RMSNorm per Section III-C).
+//
+// One 16-byte vector (8 bf16 = 4 rotary pairs) per lane per step.  A head row of d elements is
+// d8 = d/8 adjacent lanes; its sum of squares is reduced with cross-lane moves inside the wavefront.
+// A wavefront owns a run of whole token rows: one token (D8 = D/8 vectors, a multiple of 64) walked in
+// D8/64 steps, or 64/D8 short tokens in one step.  In both cases a lane keeps the same position inside
+// its head and the same token for every step, so gamma and the token's cos/sin values are fetched
+// once per lane and reused for every head.  HBM traffic: each element read once and written once.
+#include "internal.h"
+
+namespace cocodiff {
+
+struct RopeDev {
+    int32_t n_axes;
+    int32_t grid[3];
+    int32_t pairs[3];
+    int32_t offset[3];   // float offset of each axis' [grid][pairs][2] table
+    const float* cs;
+};
+
+struct NormRopeArgs {
+    uint16_t* tensor[2];
+    const uint16_t* gamma[2];
+    uint32_t D8, d8;
+    uint32_t first_token, n_tokens;   // token range of this launch
+    uint32_t steps;                   // D8/64 when D8 >= 64, else 1
+    float inv_d, eps;
+    RopeDev rope;
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over groups of `width` adjacent lanes (width a power of two, 1..64); every lane gets its group's sum.
+__device__ __forceinline__ float group_sum(float v, uint32_t width) {
+    if (width > 1) v += dpp<0xB1>(v);    // quad_perm [1,0,3,2]
+    if (width > 2) v += dpp<0x4E>(v);    // quad_perm [2,3,0,1]
+    if (width > 4) v += dpp<0x141>(v);   // row_half_mirror: the other quad of the 8-lane half row
+    if (width > 8) v += dpp<0x140>(v);   // row_mirror: the other half of the 16-lane row
+    if (width > 16) v += __shfl_xor(v, 16, 64);
+    if (width > 32) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+constexpr int kMaxSteps = 8;
+
+template <int STEPS>   // 0 = any number of steps, taken kMaxSteps at a time
+__global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t run = blockIdx.x * 4 + (threadIdx.x >> 6);
+    uint16_t* __restrict__ base = a.tensor[blockIdx.y];
+    const uint16_t* __restrict__ gamma = a.gamma[blockIdx.y];
+
+    // which token this lane works on, and where in its row the lane starts
+    uint32_t tok_local, v_first;
+    if (a.D8 >= 64) {
+        tok_local = run;
+        v_first = lane;
+    } else {
+        const uint32_t per_wave = 64 / a.D8;
+        tok_local = run * per_wave + lane / a.D8;
+        v_first = lane % a.D8;
+    }
+    if (tok_local >= a.n_tokens) return;   // whole groups of d8 lanes leave together (d8 divides D8)
+    const uint32_t n = a.first_token + tok_local;
+    const uint32_t l = lane % a.d8;        // vector index inside the head row; pairs 4l .. 4l+3
+
+    // gamma for this lane's 8 elements
+    const vec16 gv = *reinterpret_cast<const vec16*>(gamma + l * 8);
+    const float g[8] = {bf16_lo(gv.x), bf16_hi(gv.x), bf16_lo(gv.y), bf16_hi(gv.y),
+                        bf16_lo(gv.z), bf16_hi(gv.z), bf16_lo(gv.w), bf16_hi(gv.w)};
+
+    // grid coordinates of the token (last axis fastest) and the (cos, sin) of this lane's 4 pairs
+    uint32_t coord[3] = {0, 0, 0};
+    {
+        uint32_t rem = n;
+        for (int ax = a.rope.n_axes - 1; ax >= 0; --ax) {
+            const uint32_t gsz = (uint32_t)a.rope.grid[ax];
+            coord[ax] = rem % gsz;
+            rem /= gsz;
+        }
+    }
+    float cs_c[4], cs_s[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        uint32_t j = l * 4 + jj;
+        int ax = 0;
+        while (ax < a.rope.n_axes - 1 && j >= (uint32_t)a.rope.pairs[ax]) {
+            j -= (uint32_t)a.rope.pairs[ax];
+            ++ax;
+        }
+        const float2 v = *reinterpret_cast<const float2*>(
+            a.rope.cs + a.rope.offset[ax] + ((size_t)coord[ax] * a.rope.pairs[ax] + j) * 2);
+        cs_c[jj] = v.x;
+        cs_s[jj] = v.y;
+    }
+
+    vec16* row = reinterpret_cast<vec16*>(base) + (size_t)n * a.D8 + v_first;
+    const uint32_t total_steps = STEPS ? (uint32_t)STEPS : a.steps;
+    for (uint32_t s0 = 0; s0 < total_steps; s0 += kMaxSteps) {
+        constexpr int UN = STEPS ? (STEPS < kMaxSteps ? STEPS : kMaxSteps) : kMaxSteps;
+        vec16 in[UN];
+#pragma unroll
+        for (int k = 0; k < UN; ++k)
+            if (STEPS || s0 + k < total_steps) in[k] = row[(size_t)(s0 + k) * 64];
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            if (!(STEPS || s0 + k < total_steps)) continue;
+            const uint32_t w[4] = {in[k].x, in[k].y, in[k].z, in[k].w};
+            float x[8];
+            float ss = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[2 * i] = bf16_lo(w[i]);
+                x[2 * i + 1] = bf16_hi(w[i]);
+                ss += x[2 * i] * x[2 * i] + x[2 * i + 1] * x[2 * i + 1];
+            }
+            ss = group_sum(ss, a.d8);
+            const float rinv = 1.0f / sqrtf(ss * a.inv_d + a.eps);
+            uint32_t o[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float e = x[2 * i] * rinv * g[2 * i];
+                const float od = x[2 * i + 1] * rinv * g[2 * i + 1];
+                o[i] = pack_bf16x2(e * cs_c[i] - od * cs_s[i], e * cs_s[i] + od * cs_c[i]);
+            }
+            row[(size_t)(s0 + k) * 64] = vec16{o[0], o[1], o[2], o[3]};
+        }
+    }
+}
+
+}  // namespace cocodiff
+
+using namespace cocodiff;
+
+extern "C" int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf16* q, cocodiff_bf16* k,
+                                     const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                     const cocodiff_rope* rope, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != COCODIFF_OK) return rc;
+    if (!q && !k) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: q and k are both NULL");
+    if ((q && !gamma_q) || (k && !gamma_k)) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: gamma missing for a given tensor");
+    if (!rope || !rope->cs) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: rope description or its table is NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(gamma_q) || !aligned16(gamma_k) || !aligned16(rope->cs))
+        return fail(COCODIFF_ERR_ALIGN, "qk_norm_rope: pointers must be 16-byte aligned");
+    const uint32_t d8 = shape->d / 8, D8 = shape->D / 8;
+    if ((d8 & (d8 - 1)) || d8 > 64)
+        return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: d (%d) must be 8 times a power of two, at most 512", shape->d);
+    if (!(D8 % 64 == 0 || 64 % D8 == 0))
+        return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: D/8 (%u) must divide 64 or be a multiple of 64", D8);
+    if (rope->n_axes < 1 || rope->n_axes > 3) return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: rope n_axes (%d) must be 1..3", rope->n_axes);
+    int64_t cells = 1, npairs = 0;
+    for (int ax = 0; ax < rope->n_axes; ++ax) {
+        if (rope->grid[ax] <= 0 || rope->pairs[ax] <= 0)
+            return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: rope axis %d needs positive grid and pairs", ax);
+        cells *= rope->grid[ax];
+        npairs += rope->pairs[ax];
+    }
+    if (cells != shape->N) return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: grid has %lld cells, N is %d", (long long)cells, shape->N);
+    if (npairs * 2 != shape->d) return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: rope pairs sum to %lld, d/2 is %d", (long long)npairs, shape->d / 2);
+
+    NormRopeArgs a;
+    int nt = 0;
+    if (q) { a.tensor[nt] = q; a.gamma[nt] = gamma_q; ++nt; }
+    if (k) { a.tensor[nt] = k; a.gamma[nt] = gamma_k; ++nt; }
+    if (nt == 1) { a.tensor[1] = a.tensor[0]; a.gamma[1] = a.gamma[0]; }
+    const uint32_t Ns = shape->N / shape->P;
+    a.D8 = D8;
+    a.d8 = d8;
+    a.first_token = shape->rank_begin * Ns;
+    a.n_tokens = shape->rank_count * Ns;
+    a.steps = D8 >= 64 ? D8 / 64 : 1;
+    a.inv_d = 1.0f / (float)shape->d;
+    a.eps = eps;
+    a.rope.n_axes = rope->n_axes;
+    int32_t off = 0;
+    for (int ax = 0; ax < 3; ++ax) {
+        a.rope.grid[ax] = ax < rope->n_axes ? rope->grid[ax] : 1;
+        a.rope.pairs[ax] = ax < rope->n_axes ? rope->pairs[ax] : 0;
+        a.rope.offset[ax] = off;
+        if (ax < rope->n_axes) off += rope->grid[ax] * rope->pairs[ax] * 2;
+    }
+    a.rope.cs = rope->cs;
+
+    const uint32_t tokens_per_wave = D8 >= 64 ? 1 : 64 / D8;
+    const uint32_t runs = (a.n_tokens + tokens_per_wave - 1) / tokens_per_wave;
+    const dim3 grid((runs + 3) / 4, nt), block(256);
+    hipStream_t st = as_stream(stream);
+    switch (a.steps) {
+        case 1: hipLaunchKernelGGL(norm_rope_kernel<1>, grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL(norm_rope_kernel<2>, grid, block, 0, st, a); break;
+        case 4: hipLaunchKernelGGL(norm_rope_kernel<4>, grid, block, 0, st, a); break;
+        case 6: hipLaunchKernelGGL(norm_rope_kernel<6>, grid, block, 0, st, a); break;
+        case 8: hipLaunchKernelGGL(norm_rope_kernel<8>, grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL(norm_rope_kernel<0>, grid, block, 0, st, a); break;
+    }
+    return check_launch("norm_rope_kernel");
+}

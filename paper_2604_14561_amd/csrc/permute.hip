@@ -1,0 +1,140 @@
+// Ulysses all-to-all #1 on one GPU (paper Section II-A): pack the send chunks, unpack the received
+// chunks head-major.  Pure 128-bit permutation copies; HBM-bound.
+//
+// Units below are 16-byte vectors (8 bf16).  d8 = d/8 vectors per head row, D8 = D/8 per token row,
+// row8 = Hp*d8 per chunk row, chunk8 = Ns*row8 per chunk.
+#include "internal.h"
+
+namespace cocodiff {
+
+constexpr int kThreads = 256;
+constexpr int kVecPerThread = 4;
+
+struct PermuteArgs {
+    uint32_t Ns, P, D8, d8, row8, chunk8;
+    uint32_t N;           // tokens in total
+    uint32_t first;       // pack: first token of the range; unpack: first head of the range
+    uint32_t n_vec;       // vectors this launch moves
+    int recv_major;
+};
+
+__device__ __forceinline__ uint32_t slot_of(uint32_t r, uint32_t p, uint32_t P, int recv_major) {
+    return recv_major ? p * P + r : r * P + p;
+}
+
+// One thread moves kVecPerThread vectors, kThreads apart, all loads issued before the stores.
+// Source is walked linearly: token-major rows of the sequence-parallel tensor.
+__global__ void __launch_bounds__(kThreads) pack_kernel(const vec16* __restrict__ x, vec16* __restrict__ xbuf, PermuteArgs a) {
+    const uint32_t base = blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
+    vec16 val[kVecPerThread];
+    uint32_t dst[kVecPerThread];
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; ++k) {
+        const uint32_t g = base + k * kThreads;
+        if (g < a.n_vec) {
+            const uint32_t tl = g / a.D8;            // token within the range
+            const uint32_t v = g - tl * a.D8;        // vector within the token row
+            const uint32_t n = a.first + tl;         // global token
+            const uint32_t r = n / a.Ns;             // source rank
+            const uint32_t m = n - r * a.Ns;         // token within the rank
+            const uint32_t p = v / a.row8;           // destination rank (owner of this head)
+            const uint32_t c = v - p * a.row8;       // (hl, i) within the chunk row
+            dst[k] = slot_of(r, p, a.P, a.recv_major) * a.chunk8 + m * a.row8 + c;
+            val[k] = x[(size_t)n * a.D8 + v];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; ++k) {
+        const uint32_t g = base + k * kThreads;
+        if (g < a.n_vec) xbuf[dst[k]] = val[k];
+    }
+}
+
+// Destination is walked linearly: head-major rows of the head-parallel tensor.
+__global__ void __launch_bounds__(kThreads) unpack_kernel(const vec16* __restrict__ xbuf, vec16* __restrict__ y, PermuteArgs a) {
+    const uint32_t base = blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
+    const uint32_t head8 = a.N * a.d8;               // vectors per head slab
+    const uint32_t Hp = a.row8 / a.d8;
+    vec16 val[kVecPerThread];
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; ++k) {
+        const uint32_t g = base + k * kThreads;
+        if (g < a.n_vec) {
+            const uint32_t hl_range = g / head8;
+            const uint32_t rem = g - hl_range * head8;
+            const uint32_t h = a.first + hl_range;   // global head
+            const uint32_t n = rem / a.d8;           // global token
+            const uint32_t i8 = rem - n * a.d8;
+            const uint32_t p = h / Hp;               // destination rank
+            const uint32_t hl = h - p * Hp;
+            const uint32_t r = n / a.Ns;             // source rank
+            const uint32_t m = n - r * a.Ns;
+            val[k] = xbuf[(size_t)slot_of(r, p, a.P, a.recv_major) * a.chunk8 + m * a.row8 + hl * a.d8 + i8];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; ++k) {
+        const uint32_t g = base + k * kThreads;
+        if (g < a.n_vec) y[(size_t)a.first * head8 + g] = val[k];
+    }
+}
+
+static int check_permute(const cocodiff_shape* s, const void* in, const void* out, int slot_order, const char* who) {
+    int rc = check_shape(s);
+    if (rc != COCODIFF_OK) return rc;
+    if (!in || !out) return fail(COCODIFF_ERR_NULL, "%s: NULL tensor pointer", who);
+    if (!aligned16(in) || !aligned16(out)) return fail(COCODIFF_ERR_ALIGN, "%s: pointers must be 16-byte aligned", who);
+    if (slot_order != COCODIFF_SEND_MAJOR && slot_order != COCODIFF_RECV_MAJOR)
+        return fail(COCODIFF_ERR_SHAPE, "%s: slot_order (%d) must be SEND_MAJOR or RECV_MAJOR", who, slot_order);
+    if ((int64_t)s->N * s->D / 8 >= (int64_t)1 << 31)
+        return fail(COCODIFF_ERR_SHAPE, "%s: N*D/8 must be below 2^31", who);
+    return COCODIFF_OK;
+}
+
+static PermuteArgs make_args(const cocodiff_shape* s, int slot_order) {
+    PermuteArgs a;
+    a.Ns = s->N / s->P;
+    a.P = s->P;
+    a.D8 = s->D / 8;
+    a.d8 = s->d / 8;
+    a.row8 = (s->H / s->P) * a.d8;
+    a.chunk8 = a.Ns * a.row8;
+    a.N = s->N;
+    a.first = 0;
+    a.n_vec = 0;
+    a.recv_major = slot_order == COCODIFF_RECV_MAJOR;
+    return a;
+}
+
+}  // namespace cocodiff
+
+using namespace cocodiff;
+
+extern "C" int cocodiff_a2a_pack(const cocodiff_shape* shape, const cocodiff_bf16* x_seq, cocodiff_bf16* xbuf,
+                                 int slot_order, void* stream) {
+    int rc = check_permute(shape, x_seq, xbuf, slot_order, "a2a_pack");
+    if (rc != COCODIFF_OK) return rc;
+    PermuteArgs a = make_args(shape, slot_order);
+    a.first = shape->rank_begin * a.Ns;
+    a.n_vec = (uint32_t)shape->rank_count * a.Ns * a.D8;
+    const uint32_t per_block = kThreads * kVecPerThread;
+    const uint32_t blocks = (a.n_vec + per_block - 1) / per_block;
+    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(kThreads), 0, as_stream(stream),
+                       (const vec16*)x_seq, (vec16*)xbuf, a);
+    return check_launch("a2a_pack");
+}
+
+extern "C" int cocodiff_a2a_unpack(const cocodiff_shape* shape, const cocodiff_bf16* xbuf, cocodiff_bf16* x_hs,
+                                   int slot_order, void* stream) {
+    int rc = check_permute(shape, xbuf, x_hs, slot_order, "a2a_unpack");
+    if (rc != COCODIFF_OK) return rc;
+    PermuteArgs a = make_args(shape, slot_order);
+    const uint32_t Hp = shape->H / shape->P;
+    a.first = shape->rank_begin * Hp;
+    a.n_vec = (uint32_t)shape->rank_count * Hp * a.N * a.d8;
+    const uint32_t per_block = kThreads * kVecPerThread;
+    const uint32_t blocks = (a.n_vec + per_block - 1) / per_block;
+    hipLaunchKernelGGL(unpack_kernel, dim3(blocks), dim3(kThreads), 0, as_stream(stream),
+                       (const vec16*)xbuf, (vec16*)x_hs, a);
+    return check_launch("a2a_unpack");
+}
