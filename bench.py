@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the Ulysses attention-input path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic layer input, all P logical ranks:
+  stream V : qkv_proj(V) -> a2a_pack(V) -> a2a_unpack(V) -> vmajor_select(V, V_prev)
+  stream QK: [after V's projection] qkv_proj(Q, K) -> qk_norm_rope(Q, K) -> a2a_pack(Q), (K) -> a2a_unpack(Q), (K)
+(the V-First order of the paper's Section III-C; --schedule serial runs the same calls on one stream).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line on stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "tokens/s per layer (QKV+norm+RoPE+pack); pack/select GB/s vs HBM peak"
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--schedule", default="vfirst", choices=["vfirst", "serial"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-breakdown", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs all P logical ranks of the path on ONE GPU; "
+            "there is no multi-GPU path to time (--gpus must be 1).")
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2604_14561_amd as cd
+    from synth import CONFIGS, make_layer_inputs, perturb_tiles
+
+    if not os.path.exists(cd.binding.LIB_PATH):
+        from paper_2604_14561_amd import build as _build
+        _build.build()
+
+    cfg = CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    N, D, H, d, P, T = cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, cfg.tile_tokens
+    log(f"bench: {cfg.name} N={N} D={D} H={H}x{d} P={P}; generating inputs")
+
+    def up(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+
+    def bits(t):
+        return t.cpu().numpy().view(np.uint16)
+
+    inp = make_layer_inputs(cfg)
+    X, Wq, Wk, Wv = up(inp["X"]), up(inp["Wq"]), up(inp["Wk"]), up(inp["Wv"])
+    gq, gk = up(inp["gamma_q"]), up(inp["gamma_k"])
+    table = up(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta))
+    rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, table.data_ptr())
+    sh = cd.Shape.make(N, D, H, d, P)
+
+    def bf(shape):
+        return torch.empty(shape, dtype=torch.int16, device=dev)
+
+    q, k, v = bf((N, D)), bf((N, D)), bf((N, D))
+    bq, bk, bv = bf((N * D,)), bf((N * D,)), bf((N * D,))
+    hq, hk, hv = bf((H, N, d)), bf((H, N, d)), bf((H, N, d))
+    NT = cfg.NT
+    cap = NT
+    ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device=dev)
+    flags = torch.empty(NT, dtype=torch.int32, device=dev)
+    idx = torch.empty(NT, dtype=torch.int32, device=dev)
+    n_act = torch.zeros(1, dtype=torch.int32, device=dev)
+    compact = bf((H, cap * T, d))
+
+    s_v, s_qk = torch.cuda.Stream(), torch.cuda.Stream()
+    ORDER = cd.RECV_MAJOR
+
+    # previous-step V: this layer's own head-parallel V with a seeded fraction of 16-token tiles perturbed
+    cd.qkv_proj(sh, X, None, None, Wv, None, None, v)
+    cd.a2a_pack(sh, v, bv, ORDER)
+    cd.a2a_unpack(sh, bv, hv, ORDER)
+    torch.cuda.synchronize()
+    v_prev_host, changed = perturb_tiles(bits(hv), 1, T, cfg.n_changed, np.random.default_rng(cfg.index), cfg.noise_sigma)
+    hv_prev = up(v_prev_host)
+    del v_prev_host
+
+    def step_vfirst(ev=None):
+        """ev: optional (v0, v1, qk0, qk1) timing events bracketing the two projection launches."""
+        if ev:
+            ev[0].record(s_v)
+        cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=s_v)
+        if ev:
+            ev[1].record(s_v)
+        v_ready = torch.cuda.Event()
+        v_ready.record(s_v)
+        cd.a2a_pack(sh, v, bv, ORDER, stream=s_v)
+        cd.a2a_unpack(sh, bv, hv, ORDER, stream=s_v)
+        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
+        s_qk.wait_event(v_ready)            # V's projection goes first; its layout change overlaps what follows
+        if ev:
+            ev[2].record(s_qk)
+        cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=s_qk)
+        if ev:
+            ev[3].record(s_qk)
+        cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=s_qk)
+        cd.a2a_pack(sh, q, bq, ORDER, stream=s_qk)
+        cd.a2a_pack(sh, k, bk, ORDER, stream=s_qk)
+        cd.a2a_unpack(sh, bq, hq, ORDER, stream=s_qk)
+        cd.a2a_unpack(sh, bk, hk, ORDER, stream=s_qk)
+        done = torch.cuda.Event()
+        done.record(s_qk)
+        s_v.wait_event(done)                # join: the next layer cannot start before Q and K are laid out
+
+    def step_serial(ev=None):
+        st = s_v
+        if ev:
+            ev[0].record(st)
+        cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=st)
+        if ev:
+            ev[1].record(st)
+            ev[2].record(st)
+        cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=st)
+        if ev:
+            ev[3].record(st)
+        cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=st)
+        for src, buf, dst in ((v, bv, hv), (q, bq, hq), (k, bk, hk)):
+            cd.a2a_pack(sh, src, buf, ORDER, stream=st)
+            cd.a2a_unpack(sh, buf, dst, ORDER, stream=st)
+        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=st)
+
+    step = step_vfirst if args.schedule == "vfirst" else step_serial
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert int(n_act.cpu()[0]) == cfg.n_changed, "selection did not find the perturbed tiles"
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = N / (ms_per_step * 1e-3)
+
+    # dominant kernel: the projection GEMM (two launches per step: V, then Q+K)
+    gemm_ms = [(e[0].elapsed_time(e[1]), e[2].elapsed_time(e[3])) for e in events]
+    gemm_ms_per_launch = float(np.mean([a + b for a, b in gemm_ms])) / 2.0
+    flops_per_launch = 2.0 * N * (3 * D) * D / 2.0
+    achieved_tflops = flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12
+    roofline = {"kernel": "qkv_gemm_kernel", "bound": "mfma", "achieved": round(achieved_tflops, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
+                "traffic": None, "avg_launch_us": round(gemm_ms_per_launch * 1e3, 2), "launches_per_step": 2}
+
+    # ---- per-kernel times, each launched alone on one stream (not part of `value`) ----
+    kernels = {}
+    if not args.no_breakdown:
+        st = torch.cuda.current_stream()
+        tensor_bytes = N * D * 2
+
+        def timed(fn, iters=20):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(st)
+            for _ in range(iters):
+                fn()
+            e1.record(st)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / iters * 1e3   # us
+
+        def add(name, us, flops=None, nbytes=None):
+            ent = {"us": round(us, 2)}
+            if flops:
+                ent["TFLOP/s"] = round(flops / us / 1e6, 1)
+                ent["frac_mfma_peak"] = round(flops / us / 1e6 / PEAK_BF16_TFLOPS, 4)
+            if nbytes:
+                ent["GB/s"] = round(nbytes / us / 1e3, 1)
+                ent["frac_hbm_peak"] = round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4)
+            kernels[name] = ent
+
+        g1 = 2.0 * N * D * D
+        add("qkv_proj_v", timed(lambda: cd.qkv_proj(sh, X, None, None, Wv, None, None, v)), flops=g1)
+        add("qkv_proj_qk", timed(lambda: cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None)), flops=2 * g1)
+        add("qkv_proj_qkv", timed(lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v)), flops=3 * g1)
+        add("qk_norm_rope", timed(lambda: cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope)), nbytes=4 * tensor_bytes)
+        add("a2a_pack", timed(lambda: cd.a2a_pack(sh, v, bv, ORDER)), nbytes=2 * tensor_bytes)
+        add("a2a_unpack", timed(lambda: cd.a2a_unpack(sh, bv, hv, ORDER)), nbytes=2 * tensor_bytes)
+        f_act = cfg.n_changed / NT
+        add("vmajor_select", timed(lambda: cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act,
+                                                            compact, cap, ws)), nbytes=(2 + f_act) * tensor_bytes)
+        add("copy_same_bytes", timed(lambda: cd.util_copy(v, bv, tensor_bytes)), nbytes=2 * tensor_bytes)
+        big = 1 << 30
+        src_big = torch.empty(big, dtype=torch.uint8, device=dev)
+        dst_big = torch.empty(big, dtype=torch.uint8, device=dev)
+        add("copy_1GiB", timed(lambda: cd.util_copy(src_big, dst_big, big), iters=10), nbytes=2 * big)
+        del src_big, dst_big
+        for name, ent in kernels.items():
+            log(f"  {name:18s} {ent}")
+
+    # ---- the CPU oracle on the host cores, on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build_c()
+        n_ranks = min(P, max(1, int(round(3072 / cfg.Ns)))) if cfg.Ns < 3072 else 1
+        S_tok = n_ranks * cfg.Ns
+        ids = np.arange(S_tok)
+        t_a = time.perf_counter()
+        o = {}
+        for name, w in (("q", "Wq"), ("k", "Wk"), ("v", "Wv")):
+            o[name] = oracle.qkv_proj(inp["X"][:S_tok], inp[w])
+        for name, g in (("q", "gamma_q"), ("k", "gamma_k")):
+            o[name] = oracle.rope_rotate(oracle.rms_norm(o[name].reshape(S_tok, H, d), oracle.widen(inp[g]), cfg.eps),
+                                         ids, cfg.grid, cfg.pairs, cfg.theta)
+        t_b = time.perf_counter()
+        host_seq = bits(v).reshape(N, H, d)
+        host_prev = bits(hv_prev)
+        t_c = time.perf_counter()
+        for _ in range(3):                                   # Q, K and V each go through pack + unpack
+            buf = oracle.a2a_pack(host_seq, P, oracle.ref.RECV_MAJOR)
+            hs_host = oracle.a2a_unpack(buf, N, H, d, P, oracle.ref.RECV_MAJOR)
+        o_sel = oracle.vmajor_select(hs_host, host_prev, cfg.tau, T)
+        t_d = time.perf_counter()
+        assert o_sel[2] == cfg.n_changed
+        per_token = (t_b - t_a) / S_tok + (t_d - t_c) / N
+        try:
+            from threadpoolctl import threadpool_info
+            blas_threads = max([p_.get("num_threads", 1) for p_ in threadpool_info()] or [1])
+        except Exception:
+            blas_threads = os.cpu_count() or 1
+        cpu = {"value": round(1.0 / per_token, 1), "unit": "tokens/s", "cores": int(blas_threads), "kind": "oracle",
+               "sample": f"fp64 projection+norm+RoPE on the first {S_tok} of {N} tokens ({n_ranks} ranks' shares), "
+                         f"pack/unpack x3 and select on the full tensors; {t_b - t_a + t_d - t_c:.1f} s of CPU work"}
+        log(f"  cpu oracle: {cpu}")
+
+    out = {
+        "metric": METRIC, "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: N={N} tokens ({'x'.join(map(str, cfg.grid))} grid), D={D}, {H} heads x {d}, "
+                               f"P={P} logical ranks on one GPU, {cfg.n_changed}/{NT} 16-token V tiles changed",
+                   "schedule": args.schedule, "global_batch": 1, "seq_len": N},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

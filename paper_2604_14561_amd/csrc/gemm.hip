@@ -1,13 +1,21 @@
 // QKV projection (paper Section II-B): Y[n][o] = sum_k X[n][k] * W[o][k], bf16 in, fp32 accumulate on the
 // gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), one RNE rounding to bf16.
 //
-// Both operands are K-contiguous, so a tile of either is a set of 128-byte row segments.
-// Workgroup = 256 lanes = 4 wavefronts (2 x 2), output tile 256 tokens x 256 features, K step 64,
-// two LDS stages of (32 KB of X + 32 KB of W).  A wavefront owns 128 x 128 outputs = 4 x 4 MFMA tiles
-// (256 accumulator registers per lane).  W rides the MFMA "A" side, so an accumulator lane holds four
-// consecutive features of one token.  LDS rows are 128 B = eight 16-byte columns; column c of row r
-// is stored at column c ^ swz(r), which makes the 128-bit fragment reads bank-conflict free.
+// Workgroup = 256 lanes = 4 wavefronts (2 x 2), output tile 256 tokens x 256 features.  A wavefront owns
+// 128 x 128 outputs = 4 x 4 MFMA tiles (256 accumulator registers per lane).  W rides the MFMA "A" side,
+// so an accumulator lane holds four consecutive features of one token.  Both operands are K-contiguous,
+// so a tile of either is a set of row segments; LDS tiles keep rows contiguous and store 16-byte column
+// c of row r at column c ^ swizzle(r), which makes the 128-bit fragment reads bank-conflict free.
+//
+// Main kernel (K a multiple of 64): global -> LDS directly (no staging registers), K step 64 so every row
+// segment is a whole 128-byte line (half lines halve the L1 fill rate).  A step's X tile and W tile are
+// 32 KB each and travel separately through a ring of five 32 KB slots: two are being multiplied, three
+// are in flight or landed, so half of each step's data has two steps to arrive and half has one.
+// Fallback kernel (any K that is a multiple of 8): global -> registers -> LDS, two 64 KB stages, zero-filled
+// K tail.
 // The epilogue rounds to bf16, transposes through the (now idle) LDS and writes whole 256-byte rows.
+#include <type_traits>
+
 #include "internal.h"
 
 namespace cocodiff {
@@ -17,9 +25,15 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int BM = 256;          // tokens per workgroup tile
 constexpr int BN = 256;          // features per workgroup tile
-constexpr int BK = 64;           // K elements per stage
 constexpr int kGemmThreads = 256;
-constexpr int kStageBytes = (BM + BN) * BK * 2;   // 64 KB
+constexpr int BK = 64;                                   // K elements per step
+// main kernel: ring of direct-to-LDS slots, one operand tile of one K step per slot
+constexpr int kRingSlots = 5;
+constexpr int kSlotBytes = BM * BK * 2;                  // 32 KB (BM == BN)
+constexpr int kPipeLdsBytes = kRingSlots * kSlotBytes;   // 160 KB
+constexpr int kLoadsPerSlot = BM * (BK / 8) / kGemmThreads;   // global->LDS instructions per lane per slot: 8
+// fallback kernel: register-staged double buffer
+constexpr int kStageBytes = (BM + BN) * BK * 2;          // 64 KB
 constexpr int kVecPerOperand = BM * (BK / 8) / kGemmThreads;   // 16-byte vectors per lane per operand per stage: 8
 
 struct GemmArgs {
@@ -32,25 +46,30 @@ struct GemmArgs {
     int32_t tiles_m, tiles_n_per_tensor;
 };
 
+// [rows][64] bf16 tiles (128-byte rows): any 16 consecutive rows of one column land in 16
+// different 16-byte slots of the 256-byte bank span.
 __device__ __forceinline__ uint32_t swz(uint32_t row) { return (row & 7u) ^ ((row >> 3) & 1u); }
 
 // Byte offset of 16-byte column c of row r inside a [rows][64] bf16 LDS tile.
 __device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t c) { return row * 128u + ((c ^ swz(row)) << 4); }
 
-__global__ void __launch_bounds__(kGemmThreads) qkv_gemm_kernel(GemmArgs a) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
-    // ---- which tile: blocks are dealt round-robin to the 8 XCDs, so give each XCD a contiguous run
-    //      of tiles, ordered so that tiles running together share rows of X and W in that XCD's L2.
+template <int V> using template_int = std::integral_constant<int, V>;
+
+struct TileCoord {
+    uint32_t tensor, m0, f0;
+};
+
+// Blocks are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of tiles, ordered in groups
+// of 8 tile rows walked column by column, so tiles running together share rows of X and W in that XCD's L2.
+__device__ __forceinline__ TileCoord tile_of_block(const GemmArgs& a) {
     const uint32_t n_tiles = gridDim.x;
     const uint32_t tiles_n = (uint32_t)a.tiles_n_per_tensor * a.n_tensors;
-    uint32_t vt;
-    {
-        const uint32_t xcd = blockIdx.x & 7u, li = blockIdx.x >> 3;
-        const uint32_t per = n_tiles >> 3, rem = n_tiles & 7u;   // XCD x gets per + (x < rem) tiles
-        vt = xcd * per + (xcd < rem ? xcd : rem) + li;
-    }
-    // groups of 8 tile rows, walked column by column
+    const uint32_t xcd = blockIdx.x & 7u, li = blockIdx.x >> 3;
+    const uint32_t per = n_tiles >> 3, rem = n_tiles & 7u;   // XCD x gets per + (x < rem) tiles
+    const uint32_t vt = xcd * per + (xcd < rem ? xcd : rem) + li;
     constexpr uint32_t GROUP = 8;
     const uint32_t per_group = GROUP * tiles_n;
     const uint32_t grp = vt / per_group;
@@ -59,99 +78,29 @@ __global__ void __launch_bounds__(kGemmThreads) qkv_gemm_kernel(GemmArgs a) {
     const uint32_t in_grp = vt - grp * per_group;
     const uint32_t tm = first_m + in_grp % rows_here;
     const uint32_t tn = in_grp / rows_here;
+    TileCoord t;
+    t.tensor = tn / a.tiles_n_per_tensor;
+    t.m0 = tm * BM;
+    t.f0 = (tn - t.tensor * a.tiles_n_per_tensor) * BN;
+    return t;
+}
 
-    const uint32_t tensor = tn / a.tiles_n_per_tensor;
-    const uint32_t tn_local = tn - tensor * a.tiles_n_per_tensor;
-    const uint16_t* __restrict__ W = a.w[tensor];
-    uint16_t* __restrict__ Y = a.y[tensor];
-    const uint32_t K = (uint32_t)a.D;
-    const uint32_t m0 = tm * BM;          // first token of the tile, relative to row_begin
-    const uint32_t f0 = tn_local * BN;    // first feature of the tile
-
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const uint32_t wave_f = (wave & 1u) * 128u;    // wavefront's feature offset in the tile
-    const uint32_t wave_t = (wave >> 1) * 128u;    // wavefront's token offset in the tile
-
-    // ---- global -> register staging: lane moves vectors v = tid + 256*i, row = v/8, column = v%8
-    const uint32_t ld_c = tid & 7u;
-    const uint32_t ld_r = tid >> 3;       // + 32*i
-    const uint16_t* xg[kVecPerOperand];
-    const uint16_t* wg[kVecPerOperand];
-#pragma unroll
-    for (int i = 0; i < kVecPerOperand; ++i) {
-        const uint32_t r = ld_r + 32u * i;
-        const uint32_t xr = min(m0 + r, (uint32_t)a.M - 1u);       // rows past the end re-read the last row; never stored
-        const uint32_t wr = min(f0 + r, (uint32_t)a.D - 1u);
-        xg[i] = a.x + ((size_t)a.row_begin + xr) * K + ld_c * 8u;
-        wg[i] = W + (size_t)wr * K + ld_c * 8u;
-    }
-    const bool k_tail = (K % BK) != 0;    // last stage partly beyond K: those vectors are zero
-
-    vec16 xs[kVecPerOperand], ws[kVecPerOperand];
-    auto load_stage = [&](uint32_t k0) {
-#pragma unroll
-        for (int i = 0; i < kVecPerOperand; ++i) {
-            if (k_tail && k0 + ld_c * 8u >= K) {
-                xs[i] = vec16{0u, 0u, 0u, 0u};
-                ws[i] = vec16{0u, 0u, 0u, 0u};
-            } else {
-                xs[i] = *reinterpret_cast<const vec16*>(xg[i] + k0);
-                ws[i] = *reinterpret_cast<const vec16*>(wg[i] + k0);
-            }
-        }
-    };
-    auto store_stage = [&](uint32_t stage) {
-        unsigned char* xb = smem + stage * kStageBytes;
-        unsigned char* wb = xb + BM * BK * 2;
-#pragma unroll
-        for (int i = 0; i < kVecPerOperand; ++i) {
-            const uint32_t r = ld_r + 32u * i;
-            *reinterpret_cast<vec16*>(xb + lds_off(r, ld_c)) = xs[i];
-            *reinterpret_cast<vec16*>(wb + lds_off(r, ld_c)) = ws[i];
-        }
-    };
-
-    f32x16 acc[4][4];   // [feature tile][token tile]
+__device__ __forceinline__ void mfma_slice(f32x16 (&acc)[4][4], const bf16x8 (&wf)[4], const bf16x8 (&xf)[4]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
+}
 
-    const uint32_t n_k = (K + BK - 1) / BK;
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
-
-    const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
-    for (uint32_t kt = 0; kt < n_k; ++kt) {
-        const uint32_t cur = kt & 1u;
-        if (kt + 1 < n_k) load_stage((kt + 1) * BK);
-        const unsigned char* xb = smem + cur * kStageBytes;
-        const unsigned char* wb = xb + BM * BK * 2;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 wf[4], xf[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                wf[i] = *reinterpret_cast<const bf16x8*>(wb + lds_off(wave_f + 32u * i + frag_row, 2u * kk + frag_half));
-                xf[i] = *reinterpret_cast<const bf16x8*>(xb + lds_off(wave_t + 32u * i + frag_row, 2u * kk + frag_half));
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < n_k) store_stage(cur ^ 1u);
-        __syncthreads();
-    }
-
-    // ---- epilogue: bf16, transpose through this wavefront's private 32 KB of LDS, 256-byte row stores.
-    // Accumulator element e of lane l in MFMA tile (i, j): feature 32i + 8*(e/4) + 4*(l/32) + e%4,
-    // token 32j + l%32.  LDS row = token (256 B = sixteen 16-byte columns, column c stored at c ^ (row & 15)).
+// Round to bf16, transpose through this wavefront's private 32 KB of LDS, write whole 256-byte rows.
+// Accumulator element e of lane l in MFMA tile (i, j): feature 32i + 8*(e/4) + 4*(l/32) + e%4,
+// token 32j + l%32.  LDS row = token (256 B = sixteen 16-byte columns, column c stored at c ^ (row & 15)).
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], unsigned char* smem, uint32_t wave, uint32_t lane,
+                                           uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
+                                           uint32_t M, uint32_t D) {
     unsigned char* ep = smem + wave * (128 * 256);
+    const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -173,11 +122,241 @@ __global__ void __launch_bounds__(kGemmThreads) qkv_gemm_kernel(GemmArgs a) {
     for (int it = 0; it < 32; ++it) {
         const uint32_t row = 4u * it + rsub;
         const vec16 v = *reinterpret_cast<const vec16*>(ep + row * 256u + ((c16 ^ (row & 15u)) << 4));
-        const uint32_t tok = m0 + wave_t + row;
-        const uint32_t feat = f0 + wave_f + c16 * 8u;
-        if (tok < (uint32_t)a.M && feat < (uint32_t)a.D)
-            *reinterpret_cast<vec16*>(Y + ((size_t)a.row_begin + tok) * K + feat) = v;
+        const uint32_t tok = tok0 + row;
+        const uint32_t feat = feat0 + c16 * 8u;
+        if (tok < M && feat < D) *reinterpret_cast<vec16*>(Y + (row0 + tok) * D + feat) = v;
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Main kernel.  X tile of K step kt lives in ring slot (2kt) % 5, W tile in slot (2kt + 1) % 5.
+// In step kt a wavefront multiplies slices 0..2 (each while reading the next slice's fragments), waits
+// until step kt+1 has landed (its own loads; the barrier covers the other wavefronts'), then multiplies
+// slice 3 while reading slice 0 of step kt+1 and issuing W of step kt+2 into the slot X of step kt
+// used and X of step kt+3 into the slot W of step kt used (every wavefront is past its last read of them).
+// Instruction order inside a slice is pinned with scheduling groups (0x008 MFMA, 0x100 LDS read,
+// 0x020 VMEM read): 16 MFMAs, the 8 fragment reads slotted after the first 8 of them.
+// ---------------------------------------------------------------------------------------------
+template <int WAIT>   // s_waitcnt: at most WAIT global->LDS loads still in flight (LDS-read counter untouched)
+__device__ __forceinline__ void wait_loads() {
+    static_assert(WAIT >= 0 && WAIT < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (WAIT & 15) | ((WAIT >> 4) << 14));
+}
+
+__device__ __forceinline__ uint32_t ring_add(uint32_t slot, uint32_t n) {   // (slot + n) % 5 for n <= 5
+    const uint32_t t = slot + n;
+    return t >= kRingSlots ? t - kRingSlots : t;
+}
+
+__global__ void __launch_bounds__(kGemmThreads) qkv_gemm_pipe_kernel(GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const TileCoord tc = tile_of_block(a);
+    const uint16_t* __restrict__ W = a.w[tc.tensor];
+    const uint32_t K = (uint32_t)a.D;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t wave_f = (wave & 1u) * 128u, wave_t = (wave >> 1) * 128u;
+
+    // load i of this wavefront fills LDS rows (4i + wave)*8 .. +8 of a tile: lane -> row lane>>3, stored column lane&7
+    const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x + ((size_t)a.row_begin + tc.m0) * K);
+    const unsigned char* wbase = reinterpret_cast<const unsigned char*>(W + (size_t)tc.f0 * K);
+    uint32_t xoff[kLoadsPerSlot], woff[kLoadsPerSlot];
+#pragma unroll
+    for (int i = 0; i < kLoadsPerSlot; ++i) {
+        const uint32_t r = (4u * i + wave) * 8u + (lane >> 3);
+        const uint32_t c = (lane & 7u) ^ swz(r);
+        const uint32_t xr = min(r, (uint32_t)a.M - 1u - tc.m0);     // rows past the end re-read the last row; never stored
+        const uint32_t wr = min(r, (uint32_t)a.D - 1u - tc.f0);
+        xoff[i] = xr * K * 2u + c * 16u;
+        woff[i] = wr * K * 2u + c * 16u;
+    }
+    auto issue_tile = [&](const unsigned char* base, const uint32_t (&off)[kLoadsPerSlot], uint32_t kt, uint32_t slot) {
+        const unsigned char* g = base + (size_t)kt * (BK * 2);
+        unsigned char* l = smem + slot * kSlotBytes + wave * 1024u;
+#pragma unroll
+        for (int i = 0; i < kLoadsPerSlot; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(g + off[i]), (lptr_t)(l + i * 4096), 16, 0, 0);
+    };
+
+    // fragment addresses: row = wave offset + 32i + (lane & 31); the swizzle depends on the lane only
+    const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
+    const uint32_t sw = swz(frag_row);
+    const uint32_t x_frag = (wave_t + frag_row) * 128u;
+    const uint32_t w_frag = (wave_f + frag_row) * 128u;
+    auto read_frags = [&](uint32_t slot_x, uint32_t kk, bf16x8 (&wf)[4], bf16x8 (&xf)[4]) {
+        const uint32_t col = ((2u * kk + frag_half) ^ sw) << 4;
+        const unsigned char* xb = smem + slot_x * kSlotBytes + x_frag + col;
+        const unsigned char* wb = smem + ring_add(slot_x, 1) * kSlotBytes + w_frag + col;
+        wf[0] = *reinterpret_cast<const bf16x8*>(wb);     // in the order the MFMAs consume them
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xf[i] = *reinterpret_cast<const bf16x8*>(xb + i * 4096);
+#pragma unroll
+        for (int i = 1; i < 4; ++i) wf[i] = *reinterpret_cast<const bf16x8*>(wb + i * 4096);
+    };
+
+    f32x16 acc[4][4];   // [feature tile][token tile]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const uint32_t n_k = K / BK;   // >= 3 (the host sends shorter K to the fallback kernel)
+    issue_tile(xbase, xoff, 0, 0);
+    issue_tile(wbase, woff, 0, 1);
+    issue_tile(xbase, xoff, 1, 2);
+    issue_tile(wbase, woff, 1, 3);
+    issue_tile(xbase, xoff, 2, 4);
+    wait_loads<3 * kLoadsPerSlot>();   // step 0 has landed; X1, W1, X2 may still be in flight
+    __syncthreads();
+
+    bf16x8 wf0[4], xf0[4], wf1[4], xf1[4];
+    read_frags(0, 0, wf0, xf0);
+
+    // `slot` is the ring slot of X of step kt; W of step kt sits in the next slot
+    auto k_step = [&](uint32_t kt, uint32_t slot, auto load_w, auto load_x, auto wait, auto next) {
+        constexpr bool LOAD_W = decltype(load_w)::value, LOAD_X = decltype(load_x)::value, NEXT = decltype(next)::value;
+        constexpr int WAIT = decltype(wait)::value;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk & 1) {
+                read_frags(slot, kk + 1, wf0, xf0);
+                mfma_slice(acc, wf1, xf1);
+            } else {
+                read_frags(slot, kk + 1, wf1, xf1);
+                mfma_slice(acc, wf0, xf0);
+            }
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (NEXT) {
+            wait_loads<WAIT>();
+            __syncthreads();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (NEXT) read_frags(ring_add(slot, 2), 0, wf0, xf0);
+        if constexpr (LOAD_W) issue_tile(wbase, woff, kt + 2, slot);
+        if constexpr (LOAD_X) issue_tile(xbase, xoff, kt + 3, ring_add(slot, 1));
+        mfma_slice(acc, wf1, xf1);
+        if constexpr (NEXT) {
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            if constexpr (LOAD_W) {
+#pragma unroll
+                for (int g = 0; g < 8; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, LOAD_X ? 2 : 1, 0);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using yes = std::true_type;
+    using no = std::false_type;
+    const template_int<0> w0;
+    const template_int<kLoadsPerSlot> w1;
+    uint32_t kt = 0, slot = 0;
+    auto advance = [&]() {
+        ++kt;
+        slot = ring_add(slot, 2);
+    };
+    for (; kt + 3 < n_k; advance()) k_step(kt, slot, yes{}, yes{}, w1, yes{});   // X of step kt+2 may still be in flight
+    k_step(kt, slot, yes{}, no{}, w1, yes{});    // step n_k-3: only W of the last step is left to issue
+    advance();
+    k_step(kt, slot, no{}, no{}, w0, yes{});     // step n_k-2: the last step must have landed completely
+    advance();
+    k_step(kt, slot, no{}, no{}, w0, no{});      // step n_k-1
+    __syncthreads();
+    store_tile(acc, smem, wave, lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t, tc.f0 + wave_f,
+               (uint32_t)a.M, (uint32_t)a.D);
+}
+
+// ---------------------------------------------------------------------------------------------
+// General path, any K that is a multiple of 8: global -> registers -> LDS, vectors beyond K are zero.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kGemmThreads) qkv_gemm_staged_kernel(GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const TileCoord tc = tile_of_block(a);
+    const uint16_t* __restrict__ W = a.w[tc.tensor];
+    const uint32_t K = (uint32_t)a.D;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t wave_f = (wave & 1u) * 128u, wave_t = (wave >> 1) * 128u;
+
+    // lane moves vectors v = tid + 256*i of a tile: row = v/8, column = v%8
+    const uint32_t ld_c = tid & 7u, ld_r = tid >> 3;
+    const uint16_t* xg[kVecPerOperand];
+    const uint16_t* wg[kVecPerOperand];
+#pragma unroll
+    for (int i = 0; i < kVecPerOperand; ++i) {
+        const uint32_t r = ld_r + 32u * i;
+        const uint32_t xr = min(tc.m0 + r, (uint32_t)a.M - 1u);
+        const uint32_t wr = min(tc.f0 + r, (uint32_t)a.D - 1u);
+        xg[i] = a.x + ((size_t)a.row_begin + xr) * K + ld_c * 8u;
+        wg[i] = W + (size_t)wr * K + ld_c * 8u;
+    }
+    vec16 xs[kVecPerOperand], ws[kVecPerOperand];
+    auto load_stage = [&](uint32_t k0) {
+        const bool inside = k0 + ld_c * 8u < K;
+#pragma unroll
+        for (int i = 0; i < kVecPerOperand; ++i) {
+            xs[i] = inside ? *reinterpret_cast<const vec16*>(xg[i] + k0) : vec16{0u, 0u, 0u, 0u};
+            ws[i] = inside ? *reinterpret_cast<const vec16*>(wg[i] + k0) : vec16{0u, 0u, 0u, 0u};
+        }
+    };
+    auto store_stage = [&](uint32_t stage) {
+        unsigned char* xb = smem + stage * kStageBytes;
+        unsigned char* wb = xb + BM * BK * 2;
+#pragma unroll
+        for (int i = 0; i < kVecPerOperand; ++i) {
+            const uint32_t r = ld_r + 32u * i;
+            *reinterpret_cast<vec16*>(xb + lds_off(r, ld_c)) = xs[i];
+            *reinterpret_cast<vec16*>(wb + lds_off(r, ld_c)) = ws[i];
+        }
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const uint32_t n_k = (K + BK - 1) / BK;
+    load_stage(0);
+    store_stage(0);
+    __syncthreads();
+    const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
+    for (uint32_t kt = 0; kt < n_k; ++kt) {
+        const uint32_t cur = kt & 1u;
+        if (kt + 1 < n_k) load_stage((kt + 1) * BK);
+        const unsigned char* xb = smem + cur * kStageBytes;
+        const unsigned char* wb = xb + BM * BK * 2;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 wf[4], xf[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                wf[i] = *reinterpret_cast<const bf16x8*>(wb + lds_off(wave_f + 32u * i + frag_row, 2u * kk + frag_half));
+                xf[i] = *reinterpret_cast<const bf16x8*>(xb + lds_off(wave_t + 32u * i + frag_row, 2u * kk + frag_half));
+            }
+            mfma_slice(acc, wf, xf);
+        }
+        if (kt + 1 < n_k) store_stage(cur ^ 1u);
+        __syncthreads();
+    }
+    store_tile(acc, smem, wave, lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t, tc.f0 + wave_f,
+               (uint32_t)a.M, (uint32_t)a.D);
 }
 
 }  // namespace cocodiff
@@ -221,10 +400,16 @@ extern "C" int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf1
 
     static bool attr_set = false;   // dynamic LDS above 64 KB needs the attribute once per process
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)qkv_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-        if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve %d bytes of LDS: %s", 2 * kStageBytes, hipGetErrorString(e));
+        hipError_t e = hipFuncSetAttribute((const void*)qkv_gemm_pipe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kPipeLdsBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)qkv_gemm_staged_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+        if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(e));
         attr_set = true;
     }
-    hipLaunchKernelGGL(qkv_gemm_kernel, dim3(n_tiles), dim3(kGemmThreads), 2 * kStageBytes, as_stream(stream), a);
+    if ((int64_t)BM * a.D * 2 >= ((int64_t)1 << 32)) return fail(COCODIFF_ERR_SHAPE, "qkv_proj: D (%d) too large", a.D);
+    if (a.D % BK == 0 && a.D >= 3 * BK)
+        hipLaunchKernelGGL(qkv_gemm_pipe_kernel, dim3(n_tiles), dim3(kGemmThreads), kPipeLdsBytes, as_stream(stream), a);
+    else
+        hipLaunchKernelGGL(qkv_gemm_staged_kernel, dim3(n_tiles), dim3(kGemmThreads), 2 * kStageBytes, as_stream(stream), a);
     return check_launch("qkv_gemm_kernel");
 }
