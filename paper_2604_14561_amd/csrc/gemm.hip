@@ -1,19 +1,17 @@
 // QKV projection (paper Section II-B): Y[n][o] = sum_k X[n][k] * W[o][k], bf16 in, fp32 accumulate on the
 // gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), one RNE rounding to bf16.
 //
-// Workgroup = 256 lanes = 4 wavefronts (2 x 2), output tile 256 tokens x 256 features.  A wavefront owns
-// 128 x 128 outputs = 4 x 4 MFMA tiles (256 accumulator registers per lane).  W rides the MFMA "A" side,
-// so an accumulator lane holds four consecutive features of one token.  Both operands are K-contiguous,
-// so a tile of either is a set of row segments; LDS tiles keep rows contiguous and store 16-byte column
-// c of row r at column c ^ swizzle(r), which makes the 128-bit fragment reads bank-conflict free.
+// Workgroup tile: 256 tokens x 256 features, K step 64 (a row segment of either operand is one whole
+// 128-byte line; half lines halve the L1 fill rate).  W rides the MFMA "A" side, so an accumulator lane
+// holds four consecutive features of one token.  Both operands are K-contiguous; LDS tiles keep rows
+// contiguous and store 16-byte column c of row r at column c ^ swz(r), which makes the 128-bit fragment
+// reads bank-conflict free.
 //
-// Main kernel (K a multiple of 64): global -> LDS directly (no staging registers), K step 64 so every row
-// segment is a whole 128-byte line (half lines halve the L1 fill rate).  A step's X tile and W tile are
-// 32 KB each and travel separately through a ring of five 32 KB slots: two are being multiplied, three
-// are in flight or landed, so half of each step's data has two steps to arrive and half has one.
-// Fallback kernel (any K that is a multiple of 8): global -> registers -> LDS, two 64 KB stages, zero-filled
-// K tail.
-// The epilogue rounds to bf16, transposes through the (now idle) LDS and writes whole 256-byte rows.
+// Main kernel (K a multiple of 64): global -> LDS directly (no staging registers), two 64 KB stages.
+// WN wavefronts along the features x 2 along the tokens: WN = 4 gives 8 wavefronts of 128 x 64 outputs,
+// two per SIMD, so one can multiply while the other waits for LDS, memory or the barrier.
+// Fallback kernel (any K that is a multiple of 8): global -> registers -> LDS, zero-filled K tail.
+// The epilogue rounds to bf16, transposes through the (now idle) LDS and writes whole rows.
 #include <type_traits>
 
 #include "internal.h"
@@ -25,16 +23,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int BM = 256;          // tokens per workgroup tile
 constexpr int BN = 256;          // features per workgroup tile
-constexpr int kGemmThreads = 256;
-constexpr int BK = 64;                                   // K elements per step
-// main kernel: ring of direct-to-LDS slots, one operand tile of one K step per slot
-constexpr int kRingSlots = 5;
-constexpr int kSlotBytes = BM * BK * 2;                  // 32 KB (BM == BN)
-constexpr int kPipeLdsBytes = kRingSlots * kSlotBytes;   // 160 KB
-constexpr int kLoadsPerSlot = BM * (BK / 8) / kGemmThreads;   // global->LDS instructions per lane per slot: 8
-// fallback kernel: register-staged double buffer
-constexpr int kStageBytes = (BM + BN) * BK * 2;          // 64 KB
-constexpr int kVecPerOperand = BM * (BK / 8) / kGemmThreads;   // 16-byte vectors per lane per operand per stage: 8
+constexpr int BK = 64;           // K elements per step
+constexpr int kTileBytes = BM * BK * 2;                  // one operand tile of one K step: 32 KB (BM == BN)
+constexpr int kStageBytes = 2 * kTileBytes;              // 64 KB
+constexpr int kLdsBytes = 2 * kStageBytes;               // 128 KB
 
 struct GemmArgs {
     const uint16_t* x;
@@ -46,8 +38,8 @@ struct GemmArgs {
     int32_t tiles_m, tiles_n_per_tensor;
 };
 
-// [rows][64] bf16 tiles (128-byte rows): any 16 consecutive rows of one column land in 16
-// different 16-byte slots of the 256-byte bank span.
+// [rows][64] bf16 tiles (128-byte rows): any 16 consecutive rows of one column land in 16 different
+// 16-byte slots of the 256-byte bank span.
 __device__ __forceinline__ uint32_t swz(uint32_t row) { return (row & 7u) ^ ((row >> 3) & 1u); }
 
 // Byte offset of 16-byte column c of row r inside a [rows][64] bf16 LDS tile.
@@ -55,8 +47,6 @@ __device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t c) { return r
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
-
-template <int V> using template_int = std::integral_constant<int, V>;
 
 struct TileCoord {
     uint32_t tensor, m0, f0;
@@ -85,24 +75,28 @@ __device__ __forceinline__ TileCoord tile_of_block(const GemmArgs& a) {
     return t;
 }
 
-__device__ __forceinline__ void mfma_slice(f32x16 (&acc)[4][4], const bf16x8 (&wf)[4], const bf16x8 (&xf)[4]) {
+// A wavefront's accumulators: NI feature tiles x 4 token tiles of 32 x 32.
+template <int NI>
+__device__ __forceinline__ void mfma_slice(f32x16 (&acc)[NI][4], const bf16x8 (&wf)[NI], const bf16x8 (&xf)[4]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
 }
 
-// Round to bf16, transpose through this wavefront's private 32 KB of LDS, write whole 256-byte rows.
-// Accumulator element e of lane l in MFMA tile (i, j): feature 32i + 8*(e/4) + 4*(l/32) + e%4,
-// token 32j + l%32.  LDS row = token (256 B = sixteen 16-byte columns, column c stored at c ^ (row & 15)).
-__device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], unsigned char* smem, uint32_t wave, uint32_t lane,
+// Round to bf16, transpose through this wavefront's private LDS region (128 token rows of NI*32 features),
+// write whole rows.  Accumulator element e of lane l in MFMA tile (i, j): feature 32i + 8*(e/4) + 4*(l/32)
+// + e%4, token 32j + l%32.  16-byte column c of LDS row r is stored at column c ^ (r & (columns - 1)).
+template <int NI>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][4], unsigned char* ep, uint32_t lane,
                                            uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
                                            uint32_t M, uint32_t D) {
-    unsigned char* ep = smem + wave * (128 * 256);
+    constexpr uint32_t COLS = NI * 4;            // 16-byte columns per row
+    constexpr uint32_t ROWB = COLS * 16;         // bytes per row
     const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -113,149 +107,150 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[4][4], unsigned c
                 uint2 v;
                 v.x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
                 v.y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-                *reinterpret_cast<uint2*>(ep + row * 256u + (((c16 ^ (row & 15u)) << 4) | (half8 << 3))) = v;
+                *reinterpret_cast<uint2*>(ep + row * ROWB + (((c16 ^ (row & (COLS - 1u))) << 4) | (half8 << 3))) = v;
             }
     // the same wavefront reads back what it wrote, and a wavefront's LDS accesses complete in order:
     // no workgroup barrier is needed
-    const uint32_t c16 = lane & 15u, rsub = lane >> 4;
+    constexpr uint32_t RPI = 64 / COLS;          // rows per read instruction
+    const uint32_t c16 = lane % COLS, rsub = lane / COLS;
 #pragma unroll 8
-    for (int it = 0; it < 32; ++it) {
-        const uint32_t row = 4u * it + rsub;
-        const vec16 v = *reinterpret_cast<const vec16*>(ep + row * 256u + ((c16 ^ (row & 15u)) << 4));
+    for (uint32_t it = 0; it < 128 / RPI; ++it) {
+        const uint32_t row = RPI * it + rsub;
+        const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & (COLS - 1u))) << 4));
         const uint32_t tok = tok0 + row;
         const uint32_t feat = feat0 + c16 * 8u;
         if (tok < M && feat < D) *reinterpret_cast<vec16*>(Y + (row0 + tok) * D + feat) = v;
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Main kernel.  X tile of K step kt lives in ring slot (2kt) % 5, W tile in slot (2kt + 1) % 5.
-// In step kt a wavefront multiplies slices 0..2 (each while reading the next slice's fragments), waits
-// until step kt+1 has landed (its own loads; the barrier covers the other wavefronts'), then multiplies
-// slice 3 while reading slice 0 of step kt+1 and issuing W of step kt+2 into the slot X of step kt
-// used and X of step kt+3 into the slot W of step kt used (every wavefront is past its last read of them).
-// Instruction order inside a slice is pinned with scheduling groups (0x008 MFMA, 0x100 LDS read,
-// 0x020 VMEM read): 16 MFMAs, the 8 fragment reads slotted after the first 8 of them.
-// ---------------------------------------------------------------------------------------------
-template <int WAIT>   // s_waitcnt: at most WAIT global->LDS loads still in flight (LDS-read counter untouched)
+// s_waitcnt: at most WAIT global->LDS loads of this wavefront still in flight (LDS-read counter untouched)
+template <int WAIT>
 __device__ __forceinline__ void wait_loads() {
     static_assert(WAIT >= 0 && WAIT < 64, "vmcnt is a 6-bit counter");
     __builtin_amdgcn_s_waitcnt(0x0F70 | (WAIT & 15) | ((WAIT >> 4) << 14));
 }
 
-__device__ __forceinline__ uint32_t ring_add(uint32_t slot, uint32_t n) {   // (slot + n) % 5 for n <= 5
-    const uint32_t t = slot + n;
-    return t >= kRingSlots ? t - kRingSlots : t;
-}
-
-__global__ void __launch_bounds__(kGemmThreads) qkv_gemm_pipe_kernel(GemmArgs a) {
+// ---------------------------------------------------------------------------------------------
+// Main kernel.  K step kt lives in LDS stage kt & 1.  In step kt a wavefront multiplies slices 0..2 (each
+// while reading the next slice's fragments), waits until step kt+1 has landed (its own loads; the barrier
+// covers the other wavefronts'), then multiplies slice 3 while reading slice 0 of step kt+1 and issuing
+// the loads of step kt+2 into the stage step kt used (every wavefront is past its last read of it).
+// Instruction order inside a slice is pinned with scheduling groups (0x008 MFMA, 0x100 LDS read,
+// 0x020 VMEM read): the fragment reads of the next slice are slotted one per MFMA from the start.
+// ---------------------------------------------------------------------------------------------
+template <int WN>
+__global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
+    constexpr int WAVES = 2 * WN;
+    constexpr int NI = BN / WN / 32;               // feature tiles per wavefront: 4 or 2
+    constexpr int NMFMA = NI * 4, NREAD = NI + 4;
+    constexpr int LOADS = 32 / WAVES;              // global->LDS instructions per lane per operand per step
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const TileCoord tc = tile_of_block(a);
     const uint16_t* __restrict__ W = a.w[tc.tensor];
     const uint32_t K = (uint32_t)a.D;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t wave_f = (wave & 1u) * 128u, wave_t = (wave >> 1) * 128u;
+    const uint32_t wave_f = (wave % WN) * (NI * 32u), wave_t = (wave / WN) * 128u;
 
-    // load i of this wavefront fills LDS rows (4i + wave)*8 .. +8 of a tile: lane -> row lane>>3, stored column lane&7
+    // load i of this wavefront fills LDS rows (WAVES*i + wave)*8 .. +8 of a tile: lane -> row lane>>3, stored column lane&7
     const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x + ((size_t)a.row_begin + tc.m0) * K);
     const unsigned char* wbase = reinterpret_cast<const unsigned char*>(W + (size_t)tc.f0 * K);
-    uint32_t xoff[kLoadsPerSlot], woff[kLoadsPerSlot];
+    uint32_t xoff[LOADS], woff[LOADS];
 #pragma unroll
-    for (int i = 0; i < kLoadsPerSlot; ++i) {
-        const uint32_t r = (4u * i + wave) * 8u + (lane >> 3);
+    for (int i = 0; i < LOADS; ++i) {
+        const uint32_t r = (WAVES * i + wave) * 8u + (lane >> 3);
         const uint32_t c = (lane & 7u) ^ swz(r);
         const uint32_t xr = min(r, (uint32_t)a.M - 1u - tc.m0);     // rows past the end re-read the last row; never stored
         const uint32_t wr = min(r, (uint32_t)a.D - 1u - tc.f0);
         xoff[i] = xr * K * 2u + c * 16u;
         woff[i] = wr * K * 2u + c * 16u;
     }
-    auto issue_tile = [&](const unsigned char* base, const uint32_t (&off)[kLoadsPerSlot], uint32_t kt, uint32_t slot) {
-        const unsigned char* g = base + (size_t)kt * (BK * 2);
-        unsigned char* l = smem + slot * kSlotBytes + wave * 1024u;
+    auto issue_loads = [&](uint32_t kt) {
+        const unsigned char* xk = xbase + (size_t)kt * (BK * 2);
+        const unsigned char* wk = wbase + (size_t)kt * (BK * 2);
+        unsigned char* xl = smem + (kt & 1u) * kStageBytes + wave * 1024u;
+        unsigned char* wl = xl + kTileBytes;
 #pragma unroll
-        for (int i = 0; i < kLoadsPerSlot; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t)(g + off[i]), (lptr_t)(l + i * 4096), 16, 0, 0);
+        for (int i = 0; i < LOADS; ++i) {
+            __builtin_amdgcn_global_load_lds((gptr_t)(xk + xoff[i]), (lptr_t)(xl + i * (WAVES * 1024)), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(wk + woff[i]), (lptr_t)(wl + i * (WAVES * 1024)), 16, 0, 0);
+        }
     };
 
     // fragment addresses: row = wave offset + 32i + (lane & 31); the swizzle depends on the lane only
     const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
     const uint32_t sw = swz(frag_row);
     const uint32_t x_frag = (wave_t + frag_row) * 128u;
-    const uint32_t w_frag = (wave_f + frag_row) * 128u;
-    auto read_frags = [&](uint32_t slot_x, uint32_t kk, bf16x8 (&wf)[4], bf16x8 (&xf)[4]) {
-        const uint32_t col = ((2u * kk + frag_half) ^ sw) << 4;
-        const unsigned char* xb = smem + slot_x * kSlotBytes + x_frag + col;
-        const unsigned char* wb = smem + ring_add(slot_x, 1) * kSlotBytes + w_frag + col;
-        wf[0] = *reinterpret_cast<const bf16x8*>(wb);     // in the order the MFMAs consume them
+    const uint32_t w_frag = kTileBytes + (wave_f + frag_row) * 128u;
+    auto read_frags = [&](uint32_t stage, uint32_t kk, bf16x8 (&wf)[NI], bf16x8 (&xf)[4]) {
+        const unsigned char* sb = smem + stage * kStageBytes + (((2u * kk + frag_half) ^ sw) << 4);
+        wf[0] = *reinterpret_cast<const bf16x8*>(sb + w_frag);     // in the order the MFMAs consume them
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xf[i] = *reinterpret_cast<const bf16x8*>(xb + i * 4096);
+        for (int i = 0; i < 4; ++i) xf[i] = *reinterpret_cast<const bf16x8*>(sb + x_frag + i * 4096);
 #pragma unroll
-        for (int i = 1; i < 4; ++i) wf[i] = *reinterpret_cast<const bf16x8*>(wb + i * 4096);
+        for (int i = 1; i < NI; ++i) wf[i] = *reinterpret_cast<const bf16x8*>(sb + w_frag + i * 4096);
     };
 
-    f32x16 acc[4][4];   // [feature tile][token tile]
+    f32x16 acc[NI][4];   // [feature tile][token tile]
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const uint32_t n_k = K / BK;   // >= 3 (the host sends shorter K to the fallback kernel)
-    issue_tile(xbase, xoff, 0, 0);
-    issue_tile(wbase, woff, 0, 1);
-    issue_tile(xbase, xoff, 1, 2);
-    issue_tile(wbase, woff, 1, 3);
-    issue_tile(xbase, xoff, 2, 4);
-    wait_loads<3 * kLoadsPerSlot>();   // step 0 has landed; X1, W1, X2 may still be in flight
+    const uint32_t n_k = K / BK;   // >= 2 (the host sends shorter K to the fallback kernel)
+    issue_loads(0);
+    issue_loads(1);
+    wait_loads<2 * LOADS>();       // step 0 has landed; step 1 may still be in flight
     __syncthreads();
 
-    bf16x8 wf0[4], xf0[4], wf1[4], xf1[4];
+    bf16x8 wf0[NI], xf0[4], wf1[NI], xf1[4];
     read_frags(0, 0, wf0, xf0);
 
-    // `slot` is the ring slot of X of step kt; W of step kt sits in the next slot
-    auto k_step = [&](uint32_t kt, uint32_t slot, auto load_w, auto load_x, auto wait, auto next) {
-        constexpr bool LOAD_W = decltype(load_w)::value, LOAD_X = decltype(load_x)::value, NEXT = decltype(next)::value;
-        constexpr int WAIT = decltype(wait)::value;
+    auto pin_slice = [&]() {       // NMFMA MFMAs with the NREAD fragment reads slotted after the first ones
+#pragma unroll
+        for (int g = 0; g < NREAD; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NREAD, 0);
+    };
+    auto k_step = [&](uint32_t kt, auto next_frags, auto next_loads) {
+        constexpr bool NEXT = decltype(next_frags)::value, LOAD = decltype(next_loads)::value;
+        const uint32_t cur = kt & 1u;
 #pragma unroll
         for (int kk = 0; kk < 3; ++kk) {
             __builtin_amdgcn_sched_barrier(0);
             if (kk & 1) {
-                read_frags(slot, kk + 1, wf0, xf0);
-                mfma_slice(acc, wf1, xf1);
+                read_frags(cur, kk + 1, wf0, xf0);
+                mfma_slice<NI>(acc, wf1, xf1);
             } else {
-                read_frags(slot, kk + 1, wf1, xf1);
-                mfma_slice(acc, wf0, xf0);
+                read_frags(cur, kk + 1, wf1, xf1);
+                mfma_slice<NI>(acc, wf0, xf0);
             }
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+            pin_slice();
         }
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (NEXT) {
-            wait_loads<WAIT>();
+            wait_loads<0>();
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (NEXT) read_frags(ring_add(slot, 2), 0, wf0, xf0);
-        if constexpr (LOAD_W) issue_tile(wbase, woff, kt + 2, slot);
-        if constexpr (LOAD_X) issue_tile(xbase, xoff, kt + 3, ring_add(slot, 1));
-        mfma_slice(acc, wf1, xf1);
+        if constexpr (NEXT) read_frags(cur ^ 1u, 0, wf0, xf0);
+        if constexpr (LOAD) issue_loads(kt + 2);
+        mfma_slice<NI>(acc, wf1, xf1);
         if constexpr (NEXT) {
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {
+            for (int g = 0; g < NREAD; ++g) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
-            if constexpr (LOAD_W) {
+            if constexpr (LOAD) {
 #pragma unroll
-                for (int g = 0; g < 8; ++g) {
+                for (int g = 0; g < NMFMA - NREAD; ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x020, LOAD_X ? 2 : 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x020, (2 * LOADS + NMFMA - NREAD - 1) / (NMFMA - NREAD), 0);
                 }
             }
         }
@@ -263,28 +258,23 @@ __global__ void __launch_bounds__(kGemmThreads) qkv_gemm_pipe_kernel(GemmArgs a)
     };
     using yes = std::true_type;
     using no = std::false_type;
-    const template_int<0> w0;
-    const template_int<kLoadsPerSlot> w1;
-    uint32_t kt = 0, slot = 0;
-    auto advance = [&]() {
-        ++kt;
-        slot = ring_add(slot, 2);
-    };
-    for (; kt + 3 < n_k; advance()) k_step(kt, slot, yes{}, yes{}, w1, yes{});   // X of step kt+2 may still be in flight
-    k_step(kt, slot, yes{}, no{}, w1, yes{});    // step n_k-3: only W of the last step is left to issue
-    advance();
-    k_step(kt, slot, no{}, no{}, w0, yes{});     // step n_k-2: the last step must have landed completely
-    advance();
-    k_step(kt, slot, no{}, no{}, w0, no{});      // step n_k-1
+    uint32_t kt = 0;
+    for (; kt + 2 < n_k; ++kt) k_step(kt, yes{}, yes{});
+    k_step(kt, yes{}, no{});       // step n_k-2: nothing left to issue
+    k_step(kt + 1, no{}, no{});    // step n_k-1
     __syncthreads();
-    store_tile(acc, smem, wave, lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t, tc.f0 + wave_f,
-               (uint32_t)a.M, (uint32_t)a.D);
+    store_tile<NI>(acc, smem + wave * (128 * NI * 64), lane, a.y[tc.tensor], (size_t)a.row_begin,
+                   tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D);
 }
 
 // ---------------------------------------------------------------------------------------------
 // General path, any K that is a multiple of 8: global -> registers -> LDS, vectors beyond K are zero.
+// Four wavefronts (2 x 2) of 128 x 128 outputs.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kGemmThreads) qkv_gemm_staged_kernel(GemmArgs a) {
+constexpr int kStagedThreads = 256;
+constexpr int kVecPerOperand = BM * (BK / 8) / kStagedThreads;   // 16-byte vectors per lane per operand per stage: 8
+
+__global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const TileCoord tc = tile_of_block(a);
     const uint16_t* __restrict__ W = a.w[tc.tensor];
@@ -315,7 +305,7 @@ __global__ void __launch_bounds__(kGemmThreads) qkv_gemm_staged_kernel(GemmArgs 
     };
     auto store_stage = [&](uint32_t stage) {
         unsigned char* xb = smem + stage * kStageBytes;
-        unsigned char* wb = xb + BM * BK * 2;
+        unsigned char* wb = xb + kTileBytes;
 #pragma unroll
         for (int i = 0; i < kVecPerOperand; ++i) {
             const uint32_t r = ld_r + 32u * i;
@@ -341,7 +331,7 @@ __global__ void __launch_bounds__(kGemmThreads) qkv_gemm_staged_kernel(GemmArgs 
         const uint32_t cur = kt & 1u;
         if (kt + 1 < n_k) load_stage((kt + 1) * BK);
         const unsigned char* xb = smem + cur * kStageBytes;
-        const unsigned char* wb = xb + BM * BK * 2;
+        const unsigned char* wb = xb + kTileBytes;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 wf[4], xf[4];
@@ -350,14 +340,16 @@ __global__ void __launch_bounds__(kGemmThreads) qkv_gemm_staged_kernel(GemmArgs 
                 wf[i] = *reinterpret_cast<const bf16x8*>(wb + lds_off(wave_f + 32u * i + frag_row, 2u * kk + frag_half));
                 xf[i] = *reinterpret_cast<const bf16x8*>(xb + lds_off(wave_t + 32u * i + frag_row, 2u * kk + frag_half));
             }
-            mfma_slice(acc, wf, xf);
+            mfma_slice<4>(acc, wf, xf);
         }
         if (kt + 1 < n_k) store_stage(cur ^ 1u);
         __syncthreads();
     }
-    store_tile(acc, smem, wave, lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t, tc.f0 + wave_f,
-               (uint32_t)a.M, (uint32_t)a.D);
+    store_tile<4>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t,
+                  tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D);
 }
+
+constexpr int kMainWN = 4;   // 8 wavefronts per workgroup in the main kernel
 
 }  // namespace cocodiff
 
@@ -397,19 +389,20 @@ extern "C" int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf1
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n_per_tensor = (a.D + BN - 1) / BN;
     const uint32_t n_tiles = (uint32_t)a.tiles_m * a.tiles_n_per_tensor * a.n_tensors;
+    if ((int64_t)BM * a.D * 2 >= ((int64_t)1 << 32)) return fail(COCODIFF_ERR_SHAPE, "qkv_proj: D (%d) too large", a.D);
 
     static bool attr_set = false;   // dynamic LDS above 64 KB needs the attribute once per process
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)qkv_gemm_pipe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kPipeLdsBytes);
+        hipError_t e = hipFuncSetAttribute((const void*)qkv_gemm_direct_kernel<kMainWN>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)qkv_gemm_staged_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+            e = hipFuncSetAttribute((const void*)qkv_gemm_staged_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(e));
         attr_set = true;
     }
-    if ((int64_t)BM * a.D * 2 >= ((int64_t)1 << 32)) return fail(COCODIFF_ERR_SHAPE, "qkv_proj: D (%d) too large", a.D);
-    if (a.D % BK == 0 && a.D >= 3 * BK)
-        hipLaunchKernelGGL(qkv_gemm_pipe_kernel, dim3(n_tiles), dim3(kGemmThreads), kPipeLdsBytes, as_stream(stream), a);
+    if (a.D % BK == 0 && a.D >= 2 * BK)
+        hipLaunchKernelGGL(qkv_gemm_direct_kernel<kMainWN>, dim3(n_tiles), dim3(128 * kMainWN), kLdsBytes, as_stream(stream), a);
     else
-        hipLaunchKernelGGL(qkv_gemm_staged_kernel, dim3(n_tiles), dim3(kGemmThreads), 2 * kStageBytes, as_stream(stream), a);
+        hipLaunchKernelGGL(qkv_gemm_staged_kernel, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, as_stream(stream), a);
     return check_launch("qkv_gemm_kernel");
 }
