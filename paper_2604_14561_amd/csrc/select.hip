@@ -3,24 +3,23 @@
 //   idx     = ascending list of flagged tiles, n_active = its length
 //   compact = v_cur of the flagged tiles gathered densely in list order.
 //
-// Three launches on the caller's stream:
-//   1. flag pass   -- one wavefront per piece (<= 256 16-byte vectors) of a (tile, slab) segment,
-//                     streams v_cur and v_prev once, writes one partial flag per piece;
-//   2. scan        -- one workgroup ORs the partials of each tile, ballot/prefix-scans the flags
-//                     and writes flags, idx and n_active;
-//   3. gather      -- one wavefront per (active tile, slab, piece) copies v_cur into `compact`;
-//                     wavefronts beyond n_active exit at once.
-// HBM traffic: 2 tensors read once + the active fraction read once more and written once.
+// Two launches on the caller's stream, one workgroup per tile in both:
+//   1. flag pass -- streams the tile's S segments of v_cur and v_prev once and writes the tile's flag;
+//   2. gather    -- a flagged tile's workgroup counts the flags before it (its slot in the list), writes its
+//                   id there and copies its v_cur segments into `compact`; unflagged tiles leave at once;
+//                   the last tile's workgroup also writes n_active.
+// HBM traffic: 2 tensors read once + the active fraction read once more and written once (the flags,
+// 4 bytes per tile, are re-read by the flagged workgroups out of L2).
 #include "internal.h"
 
 namespace cocodiff {
 
-constexpr int kPieceVec = 256;   // 16-byte vectors per piece: 64 lanes x 4
-constexpr int kWavesPerBlock = 4;
+constexpr int kSelThreads = 256;
+constexpr int kSelUnroll = 6;     // 16-byte vectors per tensor a lane keeps in flight
 
 struct SelectShape {
-    uint32_t S, NT, seg8, pieces;   // seg8: vectors per (tile, slab) segment; pieces per segment
-    uint64_t slab8;                 // vectors per slab = N*W/8
+    uint32_t S, NT, seg8;   // seg8: 16-byte vectors per (tile, slab) segment
+    uint64_t slab8;         // vectors per slab = N*W/8
 };
 
 __device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, float tau) {
@@ -37,101 +36,82 @@ __device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, floa
     return changed;
 }
 
-// partial[(t*S + s)*pieces + q] = 1 if piece q of segment (t, s) holds a changed element.
-__global__ void __launch_bounds__(64 * kWavesPerBlock) select_flag_kernel(
-    const vec16* __restrict__ cur, const vec16* __restrict__ prev, float tau, int32_t* __restrict__ partial,
-    SelectShape sh, uint32_t n_items) {
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t item = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    if (item >= n_items) return;
-    const uint32_t q = item % sh.pieces;
-    const uint32_t ts = item / sh.pieces;
-    const uint32_t s = ts % sh.S;
-    const uint32_t t = ts / sh.S;
-    const uint64_t seg = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8;
-    const uint32_t v0 = q * kPieceVec + lane;
-    vec16 c[4], p[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t v = v0 + k * 64;
-        if (v < sh.seg8) {
-            c[k] = ld_nt(cur + seg + v);
-            p[k] = ld_nt(prev + seg + v);
-        }
-    }
+// Workgroup t: flag of tile t.
+__global__ void __launch_bounds__(kSelThreads) select_flag_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
+                                                                  float tau, int32_t* __restrict__ tile_flag,
+                                                                  int32_t* __restrict__ user_flags, SelectShape sh) {
+    const uint32_t t = blockIdx.x;
     bool changed = false;
+    // the tile's S segments form one index space g = s*seg8 + v; a lane keeps kSelUnroll vectors of each tensor in flight
+    const uint32_t total = sh.S * sh.seg8;
+    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * kSelThreads) {
+        vec16 c[kSelUnroll], p[kSelUnroll];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t v = v0 + k * 64;
-        if (v < sh.seg8) changed |= vec_changed(c[k], p[k], tau);
+        for (int k = 0; k < kSelUnroll; ++k) {
+            const uint32_t g = g0 + k * kSelThreads;
+            if (g < total) {
+                const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
+                const uint64_t at = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v;
+                c[k] = ld_nt(cur + at);
+                p[k] = ld_nt(prev + at);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kSelUnroll; ++k)
+            if (g0 + k * kSelThreads < total) changed |= vec_changed(c[k], p[k], tau);
     }
-    const bool any = __ballot(changed) != 0ull;
-    if (lane == 0) partial[item] = any ? 1 : 0;
+    const int any = __syncthreads_or(changed ? 1 : 0) ? 1 : 0;
+    if (threadIdx.x == 0) {
+        tile_flag[t] = any;
+        if (user_flags) user_flags[t] = any;
+    }
 }
 
-// One workgroup of 1024 lanes walks the tiles in order, 1024 at a time.
-__global__ void __launch_bounds__(1024) select_scan_kernel(const int32_t* __restrict__ partial, int32_t* __restrict__ flags,
-                                                           int32_t* __restrict__ idx, int32_t* __restrict__ n_active,
-                                                           uint32_t NT, uint32_t per_tile) {
-    __shared__ uint32_t wave_count[16];
-    __shared__ uint32_t running;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) running = 0;
+// Sum over the workgroup of one count per lane; every lane gets the total.
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* wave_tot) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if ((threadIdx.x & 63) == 0) wave_tot[threadIdx.x >> 6] = v;
     __syncthreads();
-    for (uint32_t t0 = 0; t0 < NT; t0 += 1024) {
-        const uint32_t t = t0 + threadIdx.x;
-        bool f = false;
-        if (t < NT) {
-            const int32_t* pt = partial + (size_t)t * per_tile;
-            int32_t acc = 0;
-            for (uint32_t i = 0; i < per_tile; ++i) acc |= pt[i];
-            f = acc != 0;
-            if (flags) flags[t] = f ? 1 : 0;
-        }
-        const uint64_t ball = __ballot(f);
-        const uint32_t below = __popcll(ball & ((1ull << lane) - 1ull));
-        if (lane == 0) wave_count[wave] = __popcll(ball);
-        __syncthreads();
-        uint32_t before = running;
-        for (uint32_t w = 0; w < wave; ++w) before += wave_count[w];
-        if (f) idx[before + below] = (int32_t)t;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t tot = running;
-            for (uint32_t w = 0; w < 16; ++w) tot += wave_count[w];
-            running = tot;
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *n_active = (int32_t)running;
+    uint32_t tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSelThreads / 64; ++w) tot += wave_tot[w];
+    return tot;
 }
 
-// item = (j*S + s)*pieces + q over j < cap_tiles; wavefronts with j >= n_active leave at once.
-__global__ void __launch_bounds__(64 * kWavesPerBlock) select_gather_kernel(
-    const vec16* __restrict__ cur, const int32_t* __restrict__ idx, const int32_t* __restrict__ n_active,
-    vec16* __restrict__ compact, SelectShape sh, uint32_t cap_tiles, uint32_t n_items) {
-    const uint32_t lane = threadIdx.x & 63;
-    const uint32_t item = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    if (item >= n_items) return;
-    const uint32_t q = item % sh.pieces;
-    const uint32_t js = item / sh.pieces;
-    const uint32_t s = js % sh.S;
-    const uint32_t j = js / sh.S;
-    if ((int32_t)j >= *n_active) return;
-    const uint32_t t = (uint32_t)idx[j];
-    const uint64_t src = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8;
-    const uint64_t dst = ((uint64_t)s * cap_tiles + j) * sh.seg8;
-    const uint32_t v0 = q * kPieceVec + lane;
-    vec16 c[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t v = v0 + k * 64;
-        if (v < sh.seg8) c[k] = cur[src + v];
+// Workgroup t: if tile t is flagged, its list slot is the number of flagged tiles before it.
+__global__ void __launch_bounds__(kSelThreads) select_gather_kernel(const vec16* __restrict__ cur, const int32_t* __restrict__ tile_flag,
+                                                                    int32_t* __restrict__ idx, int32_t* __restrict__ n_active,
+                                                                    vec16* __restrict__ compact, SelectShape sh, uint32_t cap_tiles) {
+    __shared__ uint32_t wave_tot[kSelThreads / 64];
+    const uint32_t t = blockIdx.x;
+    const bool mine = tile_flag[t] != 0;
+    const bool last = t + 1 == sh.NT;
+    if (!mine && !last) return;
+    uint32_t before = 0;
+    for (uint32_t u = threadIdx.x; u < t; u += kSelThreads) before += tile_flag[u] != 0 ? 1u : 0u;
+    const uint32_t slot = block_sum(before, wave_tot);
+    if (threadIdx.x == 0) {
+        if (mine) idx[slot] = (int32_t)t;
+        if (last) *n_active = (int32_t)(slot + (mine ? 1u : 0u));
     }
+    if (!mine || !compact || slot >= cap_tiles) return;
+    const uint32_t total = sh.S * sh.seg8;
+    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * kSelThreads) {
+        vec16 c[kSelUnroll];
+        uint64_t dst[kSelUnroll];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t v = v0 + k * 64;
-        if (v < sh.seg8) st_nt(compact + dst + v, c[k]);
+        for (int k = 0; k < kSelUnroll; ++k) {
+            const uint32_t g = g0 + k * kSelThreads;
+            if (g < total) {
+                const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
+                c[k] = cur[(uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v];
+                dst[k] = ((uint64_t)s * cap_tiles + slot) * sh.seg8 + v;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kSelUnroll; ++k)
+            if (g0 + k * kSelThreads < total) st_nt(compact + dst[k], c[k]);
     }
 }
 
@@ -140,14 +120,10 @@ static int select_shape(int32_t S, int32_t N, int32_t W, int32_t T, SelectShape*
     if (W % 8) return fail(COCODIFF_ERR_SHAPE, "select: W (%d) must be a multiple of 8", W);
     if (N % T) return fail(COCODIFF_ERR_SHAPE, "select: N (%d) must be a multiple of tile_tokens (%d)", N, T);
     const int64_t seg8 = (int64_t)T * W / 8;
-    const int64_t pieces = (seg8 + kPieceVec - 1) / kPieceVec;
-    const int64_t NT = N / T;
-    if (NT * S * pieces >= ((int64_t)1 << 31) || seg8 >= ((int64_t)1 << 31))
-        return fail(COCODIFF_ERR_SHAPE, "select: too many (tile, slab, piece) work items");
+    if (seg8 * S >= ((int64_t)1 << 31)) return fail(COCODIFF_ERR_SHAPE, "select: a tile of %lld vectors is too large", (long long)(seg8 * S));
     out->S = (uint32_t)S;
-    out->NT = (uint32_t)NT;
+    out->NT = (uint32_t)(N / T);
     out->seg8 = (uint32_t)seg8;
-    out->pieces = (uint32_t)pieces;
     out->slab8 = (uint64_t)N * W / 8;
     return COCODIFF_OK;
 }
@@ -159,7 +135,7 @@ using namespace cocodiff;
 extern "C" size_t cocodiff_vmajor_select_workspace_bytes(int32_t S, int32_t N, int32_t W, int32_t tile_tokens) {
     SelectShape sh;
     if (select_shape(S, N, W, tile_tokens, &sh) != COCODIFF_OK) return 0;
-    return (size_t)sh.NT * sh.S * sh.pieces * sizeof(int32_t);
+    return (size_t)sh.NT * sizeof(int32_t);   // one flag per tile
 }
 
 extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
@@ -175,29 +151,18 @@ extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t t
     if (!aligned16(v_cur) || !aligned16(v_prev) || !aligned16(workspace) || (compact && !aligned16(compact)))
         return fail(COCODIFF_ERR_ALIGN, "select: tensors and workspace must be 16-byte aligned");
     if (compact && cap_tiles < 1) return fail(COCODIFF_ERR_CAPACITY, "select: cap_tiles (%d) must be >= 1", cap_tiles);
-    const size_t need = (size_t)sh.NT * sh.S * sh.pieces * sizeof(int32_t);
+    const size_t need = (size_t)sh.NT * sizeof(int32_t);
     if (workspace_bytes < need)
         return fail(COCODIFF_ERR_CAPACITY, "select: workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
     hipStream_t st = as_stream(stream);
-    int32_t* partial = (int32_t*)workspace;
+    int32_t* tile_flag = (int32_t*)workspace;
 
-    const uint32_t n_items = sh.NT * sh.S * sh.pieces;
-    hipLaunchKernelGGL(select_flag_kernel, dim3((n_items + kWavesPerBlock - 1) / kWavesPerBlock), dim3(64 * kWavesPerBlock),
-                       0, st, (const vec16*)v_cur, (const vec16*)v_prev, tau, partial, sh, n_items);
+    hipLaunchKernelGGL(select_flag_kernel, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur, (const vec16*)v_prev,
+                       tau, tile_flag, flags, sh);
     rc = check_launch("select_flag_kernel");
     if (rc != COCODIFF_OK) return rc;
-    hipLaunchKernelGGL(select_scan_kernel, dim3(1), dim3(1024), 0, st, (const int32_t*)partial, flags, active_idx,
-                       n_active, sh.NT, sh.S * sh.pieces);
-    rc = check_launch("select_scan_kernel");
-    if (rc != COCODIFF_OK) return rc;
-    if (compact) {
-        const uint32_t cap = (uint32_t)cap_tiles < sh.NT ? (uint32_t)cap_tiles : sh.NT;
-        const uint64_t items64 = (uint64_t)cap * sh.S * sh.pieces;
-        const uint32_t g_items = (uint32_t)items64;
-        hipLaunchKernelGGL(select_gather_kernel, dim3((g_items + kWavesPerBlock - 1) / kWavesPerBlock),
-                           dim3(64 * kWavesPerBlock), 0, st, (const vec16*)v_cur, (const int32_t*)active_idx,
-                           (const int32_t*)n_active, (vec16*)compact, sh, (uint32_t)cap_tiles, g_items);
-        rc = check_launch("select_gather_kernel");
-    }
-    return rc;
+    hipLaunchKernelGGL(select_gather_kernel, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
+                       (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh,
+                       compact ? (uint32_t)cap_tiles : 0u);
+    return check_launch("select_gather_kernel");
 }
