@@ -206,10 +206,10 @@ def main() -> int:
         add("vmajor_select", timed(lambda: cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act,
                                                             compact, cap, ws)), nbytes=(2 + f_act) * tensor_bytes)
         add("copy_same_bytes", timed(lambda: cd.util_copy(v, bv, tensor_bytes)), nbytes=2 * tensor_bytes)
-        big = 1 << 30
-        src_big = torch.empty(big, dtype=torch.uint8, device=dev)
+        big = 1000 << 20   # not a power of two: source and destination must not alias onto the same HBM banks
+        src_big = torch.empty(big + (3 << 20), dtype=torch.uint8, device=dev)
         dst_big = torch.empty(big, dtype=torch.uint8, device=dev)
-        add("copy_1GiB", timed(lambda: cd.util_copy(src_big, dst_big, big), iters=10), nbytes=2 * big)
+        add("copy_1000MiB", timed(lambda: cd.util_copy(src_big, dst_big, big), iters=10), nbytes=2 * big)
         del src_big, dst_big
         for name, ent in kernels.items():
             log(f"  {name:18s} {ent}")

@@ -52,21 +52,17 @@ static int check_rope_desc(const cocodiff_rope* r) {
     return COCODIFF_OK;
 }
 
-// 16-byte vectors, grid-stride; the loop is unrolled by four so each lane keeps four loads in flight.
+// Each workgroup copies 1024 consecutive 16-byte vectors, four per lane, loads before stores.
+template <bool STREAM>
 __global__ void __launch_bounds__(256) copy_kernel(const vec16* __restrict__ src, vec16* __restrict__ dst, size_t n_vec) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n_vec; i += 4 * stride) {
-        vec16 a = ld_nt(src + i);
-        vec16 b = ld_nt(src + i + stride);
-        vec16 c = ld_nt(src + i + 2 * stride);
-        vec16 d = ld_nt(src + i + 3 * stride);
-        st_nt(dst + i, a);
-        st_nt(dst + i + stride, b);
-        st_nt(dst + i + 2 * stride, c);
-        st_nt(dst + i + 3 * stride, d);
-    }
-    for (; i < n_vec; i += stride) dst[i] = src[i];
+    const size_t base = (size_t)blockIdx.x * 1024 + threadIdx.x;
+    vec16 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if (base + k * 256 < n_vec) v[k] = ld_vec<STREAM>(src + base + k * 256);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if (base + k * 256 < n_vec) st_vec<STREAM>(dst + base + k * 256, v[k]);
 }
 
 }  // namespace cocodiff
@@ -110,10 +106,12 @@ int cocodiff_util_copy(const void* src, void* dst, size_t bytes, void* stream) {
     if (bytes % 16) return fail(COCODIFF_ERR_SHAPE, "copy: bytes (%zu) must be a multiple of 16", bytes);
     if (bytes == 0) return COCODIFF_OK;
     const size_t n_vec = bytes / 16;
-    size_t blocks = (n_vec + 256 * 4 - 1) / (256 * 4);
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream),
-                       (const vec16*)src, (vec16*)dst, n_vec);
+    const size_t blocks = (n_vec + 1023) / 1024;
+    if (blocks >= ((size_t)1 << 31)) return fail(COCODIFF_ERR_SHAPE, "copy: %zu bytes is too much for one launch", bytes);
+    if (should_stream(2 * bytes))
+        hipLaunchKernelGGL(copy_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), (const vec16*)src, (vec16*)dst, n_vec);
+    else
+        hipLaunchKernelGGL(copy_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), (const vec16*)src, (vec16*)dst, n_vec);
     return check_launch("copy_kernel");
 }
 

@@ -22,6 +22,11 @@ int check_launch(const char* what);
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// HBM-bound kernels stream (non-temporal hints) once the bytes they touch are several times the 256 MB
+// last-level cache; below that, cached accesses measured faster and let a consumer kernel find its
+// producer's output on chip.
+inline bool should_stream(size_t bytes_touched) { return bytes_touched > ((size_t)768 << 20); }
+
 // ---- device helpers -------------------------------------------------------
 
 // One 16-byte vector (8 bf16), the unit every kernel moves; a native vector type, so the
@@ -30,6 +35,12 @@ typedef uint32_t __attribute__((ext_vector_type(4))) vec16;
 
 __device__ __forceinline__ vec16 ld_nt(const vec16* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void st_nt(vec16* p, vec16 v) { __builtin_nontemporal_store(v, p); }
+
+// Streaming (non-temporal) or cached access, chosen at compile time.
+template <bool STREAM> __device__ __forceinline__ vec16 ld_vec(const vec16* p) { return STREAM ? ld_nt(p) : *p; }
+template <bool STREAM> __device__ __forceinline__ void st_vec(vec16* p, vec16 v) {
+    if (STREAM) st_nt(p, v); else *p = v;
+}
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 

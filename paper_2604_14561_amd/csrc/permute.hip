@@ -24,6 +24,7 @@ __device__ __forceinline__ uint32_t slot_of(uint32_t r, uint32_t p, uint32_t P, 
 
 // One thread moves kVecPerThread vectors, kThreads apart, all loads issued before the stores.
 // Source is walked linearly: token-major rows of the sequence-parallel tensor.
+template <bool STREAM>
 __global__ void __launch_bounds__(kThreads) pack_kernel(const vec16* __restrict__ x, vec16* __restrict__ xbuf, PermuteArgs a) {
     const uint32_t base = blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
     vec16 val[kVecPerThread];
@@ -40,17 +41,18 @@ __global__ void __launch_bounds__(kThreads) pack_kernel(const vec16* __restrict_
             const uint32_t p = v / a.row8;           // destination rank (owner of this head)
             const uint32_t c = v - p * a.row8;       // (hl, i) within the chunk row
             dst[k] = slot_of(r, p, a.P, a.recv_major) * a.chunk8 + m * a.row8 + c;
-            val[k] = x[(size_t)n * a.D8 + v];
+            val[k] = ld_vec<STREAM>(x + (size_t)n * a.D8 + v);
         }
     }
 #pragma unroll
     for (int k = 0; k < kVecPerThread; ++k) {
         const uint32_t g = base + k * kThreads;
-        if (g < a.n_vec) xbuf[dst[k]] = val[k];
+        if (g < a.n_vec) st_vec<STREAM>(xbuf + dst[k], val[k]);
     }
 }
 
 // Destination is walked linearly: head-major rows of the head-parallel tensor.
+template <bool STREAM>
 __global__ void __launch_bounds__(kThreads) unpack_kernel(const vec16* __restrict__ xbuf, vec16* __restrict__ y, PermuteArgs a) {
     const uint32_t base = blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
     const uint32_t head8 = a.N * a.d8;               // vectors per head slab
@@ -69,13 +71,13 @@ __global__ void __launch_bounds__(kThreads) unpack_kernel(const vec16* __restric
             const uint32_t hl = h - p * Hp;
             const uint32_t r = n / a.Ns;             // source rank
             const uint32_t m = n - r * a.Ns;
-            val[k] = xbuf[(size_t)slot_of(r, p, a.P, a.recv_major) * a.chunk8 + m * a.row8 + hl * a.d8 + i8];
+            val[k] = ld_vec<STREAM>(xbuf + (size_t)slot_of(r, p, a.P, a.recv_major) * a.chunk8 + m * a.row8 + hl * a.d8 + i8);
         }
     }
 #pragma unroll
     for (int k = 0; k < kVecPerThread; ++k) {
         const uint32_t g = base + k * kThreads;
-        if (g < a.n_vec) y[(size_t)a.first * head8 + g] = val[k];
+        if (g < a.n_vec) st_vec<STREAM>(y + (size_t)a.first * head8 + g, val[k]);
     }
 }
 
@@ -119,8 +121,10 @@ extern "C" int cocodiff_a2a_pack(const cocodiff_shape* shape, const cocodiff_bf1
     a.n_vec = (uint32_t)shape->rank_count * a.Ns * a.D8;
     const uint32_t per_block = kThreads * kVecPerThread;
     const uint32_t blocks = (a.n_vec + per_block - 1) / per_block;
-    hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(kThreads), 0, as_stream(stream),
-                       (const vec16*)x_seq, (vec16*)xbuf, a);
+    if (should_stream((size_t)a.n_vec * 32))
+        hipLaunchKernelGGL(pack_kernel<true>, dim3(blocks), dim3(kThreads), 0, as_stream(stream), (const vec16*)x_seq, (vec16*)xbuf, a);
+    else
+        hipLaunchKernelGGL(pack_kernel<false>, dim3(blocks), dim3(kThreads), 0, as_stream(stream), (const vec16*)x_seq, (vec16*)xbuf, a);
     return check_launch("a2a_pack");
 }
 
@@ -134,7 +138,9 @@ extern "C" int cocodiff_a2a_unpack(const cocodiff_shape* shape, const cocodiff_b
     a.n_vec = (uint32_t)shape->rank_count * Hp * a.N * a.d8;
     const uint32_t per_block = kThreads * kVecPerThread;
     const uint32_t blocks = (a.n_vec + per_block - 1) / per_block;
-    hipLaunchKernelGGL(unpack_kernel, dim3(blocks), dim3(kThreads), 0, as_stream(stream),
-                       (const vec16*)xbuf, (vec16*)x_hs, a);
+    if (should_stream((size_t)a.n_vec * 32))
+        hipLaunchKernelGGL(unpack_kernel<true>, dim3(blocks), dim3(kThreads), 0, as_stream(stream), (const vec16*)xbuf, (vec16*)x_hs, a);
+    else
+        hipLaunchKernelGGL(unpack_kernel<false>, dim3(blocks), dim3(kThreads), 0, as_stream(stream), (const vec16*)xbuf, (vec16*)x_hs, a);
     return check_launch("a2a_unpack");
 }

@@ -37,6 +37,7 @@ __device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, floa
 }
 
 // Workgroup t: flag of tile t.
+template <bool STREAM>
 __global__ void __launch_bounds__(kSelThreads) select_flag_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
                                                                   float tau, int32_t* __restrict__ tile_flag,
                                                                   int32_t* __restrict__ user_flags, SelectShape sh) {
@@ -52,8 +53,8 @@ __global__ void __launch_bounds__(kSelThreads) select_flag_kernel(const vec16* _
             if (g < total) {
                 const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
                 const uint64_t at = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v;
-                c[k] = ld_nt(cur + at);
-                p[k] = ld_nt(prev + at);
+                c[k] = ld_vec<STREAM>(cur + at);
+                p[k] = ld_vec<STREAM>(prev + at);
             }
         }
 #pragma unroll
@@ -157,8 +158,12 @@ extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t t
     hipStream_t st = as_stream(stream);
     int32_t* tile_flag = (int32_t*)workspace;
 
-    hipLaunchKernelGGL(select_flag_kernel, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur, (const vec16*)v_prev,
-                       tau, tile_flag, flags, sh);
+    if (should_stream((size_t)S * sh.slab8 * 32))
+        hipLaunchKernelGGL(select_flag_kernel<true>, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
+                           (const vec16*)v_prev, tau, tile_flag, flags, sh);
+    else
+        hipLaunchKernelGGL(select_flag_kernel<false>, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
+                           (const vec16*)v_prev, tau, tile_flag, flags, sh);
     rc = check_launch("select_flag_kernel");
     if (rc != COCODIFF_OK) return rc;
     hipLaunchKernelGGL(select_gather_kernel, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
