@@ -20,6 +20,21 @@ if ROOT not in sys.path:
 METRIC = "tokens/s per layer (QKV+norm+RoPE+pack); pack/select GB/s vs HBM peak"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "qkv_gemm_hbm_traffic.txt")
+
+
+def measured_traffic(workload: str, schedule: str):
+    """Bytes per launch that crossed the L2 <-> memory-fabric boundary for the projection kernel, from the
+    committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs of this script); None if not recorded."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 4 and parts[0] == "traffic_bytes_per_launch" and parts[1] == workload and parts[2] == schedule:
+                    return int(parts[3])
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -29,7 +44,7 @@ def log(*a):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--schedule", default="vfirst", choices=["vfirst", "serial"])
@@ -165,7 +180,7 @@ def main() -> int:
     achieved_tflops = flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12
     roofline = {"kernel": "qkv_gemm_kernel", "bound": "mfma", "achieved": round(achieved_tflops, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "avg_launch_us": round(gemm_ms_per_launch * 1e3, 2), "launches_per_step": 2}
+                "traffic": measured_traffic(cfg.name, args.schedule), "avg_launch_us": round(gemm_ms_per_launch * 1e3, 2), "launches_per_step": 2}
 
     # ---- per-kernel times, each launched alone on one stream (not part of `value`) ----
     kernels = {}
@@ -219,35 +234,40 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         oracle.build_c()
-        n_ranks = min(P, max(1, int(round(3072 / cfg.Ns)))) if cfg.Ns < 3072 else 1
-        S_tok = n_ranks * cfg.Ns
+        S_tok = min(N, 24576)                                # float stages: the first S_tok tokens per pass
         ids = np.arange(S_tok)
-        t_a = time.perf_counter()
-        o = {}
-        for name, w in (("q", "Wq"), ("k", "Wk"), ("v", "Wv")):
-            o[name] = oracle.qkv_proj(inp["X"][:S_tok], inp[w])
-        for name, g in (("q", "gamma_q"), ("k", "gamma_k")):
-            o[name] = oracle.rope_rotate(oracle.rms_norm(o[name].reshape(S_tok, H, d), oracle.widen(inp[g]), cfg.eps),
-                                         ids, cfg.grid, cfg.pairs, cfg.theta)
-        t_b = time.perf_counter()
         host_seq = bits(v).reshape(N, H, d)
         host_prev = bits(hv_prev)
-        t_c = time.perf_counter()
-        for _ in range(3):                                   # Q, K and V each go through pack + unpack
-            buf = oracle.a2a_pack(host_seq, P, oracle.ref.RECV_MAJOR)
-            hs_host = oracle.a2a_unpack(buf, N, H, d, P, oracle.ref.RECV_MAJOR)
-        o_sel = oracle.vmajor_select(hs_host, host_prev, cfg.tau, T)
-        t_d = time.perf_counter()
-        assert o_sel[2] == cfg.n_changed
-        per_token = (t_b - t_a) / S_tok + (t_d - t_c) / N
+        t_float = t_perm = 0.0
+        passes = 0
+        while t_float + t_perm < 12.0 and passes < 200:      # about 10-30 s of CPU work in whole passes
+            t_a = time.perf_counter()
+            o = {}
+            for name, w in (("q", "Wq"), ("k", "Wk"), ("v", "Wv")):
+                o[name] = oracle.qkv_proj(inp["X"][:S_tok], inp[w])
+            for name, g in (("q", "gamma_q"), ("k", "gamma_k")):
+                o[name] = oracle.rope_rotate(oracle.rms_norm(o[name].reshape(S_tok, H, d), oracle.widen(inp[g]), cfg.eps),
+                                             ids, cfg.grid, cfg.pairs, cfg.theta)
+            t_b = time.perf_counter()
+            for _ in range(3):                               # Q, K and V each go through pack + unpack
+                buf = oracle.a2a_pack(host_seq, P, oracle.ref.RECV_MAJOR)
+                hs_host = oracle.a2a_unpack(buf, N, H, d, P, oracle.ref.RECV_MAJOR)
+            o_sel = oracle.vmajor_select(hs_host, host_prev, cfg.tau, T)
+            t_c = time.perf_counter()
+            assert o_sel[2] == cfg.n_changed
+            t_float += t_b - t_a
+            t_perm += t_c - t_b
+            passes += 1
+        per_token = t_float / (passes * S_tok) + t_perm / (passes * N)
         try:
             from threadpoolctl import threadpool_info
             blas_threads = max([p_.get("num_threads", 1) for p_ in threadpool_info()] or [1])
         except Exception:
             blas_threads = os.cpu_count() or 1
         cpu = {"value": round(1.0 / per_token, 1), "unit": "tokens/s", "cores": int(blas_threads), "kind": "oracle",
-               "sample": f"fp64 projection+norm+RoPE on the first {S_tok} of {N} tokens ({n_ranks} ranks' shares), "
-                         f"pack/unpack x3 and select on the full tensors; {t_b - t_a + t_d - t_c:.1f} s of CPU work"}
+               "sample": f"{passes} passes of the oracle over the workload (fp64 projection + norm + RoPE on "
+                         f"{S_tok} of {N} tokens per pass; pack/unpack x3 and select on the full tensors): "
+                         f"{t_float + t_perm:.1f} s of CPU work"}
         log(f"  cpu oracle: {cpu}")
 
     out = {
