@@ -7,9 +7,10 @@
 // contiguous and store 16-byte column c of row r at column c ^ swz(r), which makes the 128-bit fragment
 // reads bank-conflict free.
 //
-// Main kernel (K a multiple of 64): global -> LDS directly (no staging registers), two 64 KB stages.
-// WN wavefronts along the features x 2 along the tokens: WN = 4 gives 8 wavefronts of 128 x 64 outputs,
-// two per SIMD, so one can multiply while the other waits for LDS, memory or the barrier.
+// Main kernel (K a multiple of 64): global -> LDS directly (no staging registers) through a ring of five
+// 32 KB slots (X and W tiles of a step travel separately).  WN wavefronts along the features x 2 along the
+// tokens: WN = 4 gives 8 wavefronts of 128 x 64 outputs, two per SIMD, so one can multiply while the
+// other waits for LDS, memory or the barrier.
 // Fallback kernel (any K that is a multiple of 8): global -> registers -> LDS, zero-filled K tail.
 // The epilogue rounds to bf16, transposes through the (now idle) LDS and writes whole rows.
 #include <type_traits>
@@ -131,20 +132,40 @@ __device__ __forceinline__ void wait_loads() {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Main kernel.  K step kt lives in LDS stage kt & 1.  In step kt a wavefront multiplies slices 0..2 (each
-// while reading the next slice's fragments), waits until step kt+1 has landed (its own loads; the barrier
-// covers the other wavefronts'), then multiplies slice 3 while reading slice 0 of step kt+1 and issuing
-// the loads of step kt+2 into the stage step kt used (every wavefront is past its last read of it).
-// Instruction order inside a slice is pinned with scheduling groups (0x008 MFMA, 0x100 LDS read,
-// 0x020 VMEM read): the fragment reads of the next slice are slotted one per MFMA from the start.
+// Main kernel.  A step's X tile and W tile (32 KB each) travel separately through a ring of five LDS
+// slots: X of K step kt lives in slot (2kt) % 5, W in slot (2kt + 1) % 5.  In step kt a wavefront
+// multiplies slices 0..2 (each while reading the next slice's fragments), waits until step kt+1 has landed
+// (its own loads; the barrier covers the other wavefronts'), then multiplies slice 3 while reading slice 0
+// of step kt+1.  After that barrier every wavefront is past its last read of step kt, so W of step kt+2
+// goes into the slot X of step kt used (one step to land) and X of step kt+3 into the slot W of step kt
+// used (two steps to land).  The W loads are issued in slice 3 of step kt, the X loads one or two per
+// slice over step kt+1: a wavefront that issues its eight loads of a step in one burst stalls on the
+// address unit, and the MFMAs behind them in program order with it (measured: +340 cycles per step).
+// Instruction order inside a slice is pinned by a scheduling barrier after every instruction group.
 // ---------------------------------------------------------------------------------------------
+constexpr int kRingSlots = 5;
+constexpr int kRingLdsBytes = kRingSlots * kTileBytes;   // 160 KB
+
+__device__ __forceinline__ uint32_t ring_add(uint32_t slot, uint32_t n) {   // (slot + n) % 5 for n <= 5
+    const uint32_t t = slot + n;
+    return t >= kRingSlots ? t - kRingSlots : t;
+}
+
+// One global -> LDS load of 16 bytes per lane: lane l's vector lands at lds_addr + 16*l.  Written as inline
+// assembly so that the compiler does not tie later LDS reads to it with a full vmcnt wait (it cannot tell
+// that the ring slot being filled is not the one being read); completion is awaited by wait_loads().
+__device__ __forceinline__ void load_to_lds(const void* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
+}
+
 template <int WN>
 __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     constexpr int WAVES = 2 * WN;
     constexpr int NI = BN / WN / 32;               // feature tiles per wavefront: 4 or 2
     constexpr int NMFMA = NI * 4, NREAD = NI + 4;
-    constexpr int LOADS = 32 / WAVES;              // global->LDS instructions per lane per operand per step
+    constexpr int LOADS = 32 / WAVES;              // global->LDS instructions per lane per operand per step: 8 or 4
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const TileCoord tc = tile_of_block(a);
     const uint16_t* __restrict__ W = a.w[tc.tensor];
     const uint32_t K = (uint32_t)a.D;
@@ -165,30 +186,29 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
         xoff[i] = xr * K * 2u + c * 16u;
         woff[i] = wr * K * 2u + c * 16u;
     }
-    auto issue_loads = [&](uint32_t kt) {
-        const unsigned char* xk = xbase + (size_t)kt * (BK * 2);
-        const unsigned char* wk = wbase + (size_t)kt * (BK * 2);
-        unsigned char* xl = smem + (kt & 1u) * kStageBytes + wave * 1024u;
-        unsigned char* wl = xl + kTileBytes;
+    // load i of one operand tile of K step kt into ring slot `slot`
+    auto issue_one = [&](const unsigned char* base, const uint32_t (&off)[LOADS], uint32_t kt, uint32_t slot, int i) {
+        load_to_lds(base + (size_t)kt * (BK * 2) + off[i], lds0 + slot * kTileBytes + (WAVES * i + wave) * 1024u);
+    };
+    auto issue_tile = [&](const unsigned char* base, const uint32_t (&off)[LOADS], uint32_t kt, uint32_t slot) {
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            __builtin_amdgcn_global_load_lds((gptr_t)(xk + xoff[i]), (lptr_t)(xl + i * (WAVES * 1024)), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(wk + woff[i]), (lptr_t)(wl + i * (WAVES * 1024)), 16, 0, 0);
-        }
+        for (int i = 0; i < LOADS; ++i) issue_one(base, off, kt, slot, i);
     };
 
     // fragment addresses: row = wave offset + 32i + (lane & 31); the swizzle depends on the lane only
     const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
     const uint32_t sw = swz(frag_row);
     const uint32_t x_frag = (wave_t + frag_row) * 128u;
-    const uint32_t w_frag = kTileBytes + (wave_f + frag_row) * 128u;
-    auto read_frags = [&](uint32_t stage, uint32_t kk, bf16x8 (&wf)[NI], bf16x8 (&xf)[4]) {
-        const unsigned char* sb = smem + stage * kStageBytes + (((2u * kk + frag_half) ^ sw) << 4);
-        wf[0] = *reinterpret_cast<const bf16x8*>(sb + w_frag);     // in the order the MFMAs consume them
-#pragma unroll
-        for (int i = 0; i < 4; ++i) xf[i] = *reinterpret_cast<const bf16x8*>(sb + x_frag + i * 4096);
-#pragma unroll
-        for (int i = 1; i < NI; ++i) wf[i] = *reinterpret_cast<const bf16x8*>(sb + w_frag + i * 4096);
+    const uint32_t w_frag = (wave_f + frag_row) * 128u;
+    // fragment r of slice kk of the step whose X tile sits in slot_x, in the order the MFMAs consume them:
+    // r = 0: W tile 0; r = 1..4: X tiles 0..3; r = 5..: W tiles 1..
+    auto read_frag = [&](uint32_t slot_x, uint32_t kk, int r, bf16x8 (&wf)[NI], bf16x8 (&xf)[4]) {
+        const uint32_t col = ((2u * kk + frag_half) ^ sw) << 4;
+        const unsigned char* xb = smem + slot_x * kTileBytes + x_frag + col;
+        const unsigned char* wb = smem + ring_add(slot_x, 1) * kTileBytes + w_frag + col;
+        if (r == 0) wf[0] = *reinterpret_cast<const bf16x8*>(wb);
+        else if (r <= 4) xf[r - 1] = *reinterpret_cast<const bf16x8*>(xb + (r - 1) * 4096);
+        else wf[r - 4] = *reinterpret_cast<const bf16x8*>(wb + (r - 4) * 4096);
     };
 
     f32x16 acc[NI][4];   // [feature tile][token tile]
@@ -199,69 +219,86 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const uint32_t n_k = K / BK;   // >= 2 (the host sends shorter K to the fallback kernel)
-    issue_loads(0);
-    issue_loads(1);
-    wait_loads<2 * LOADS>();       // step 0 has landed; step 1 may still be in flight
+    const uint32_t n_k = K / BK;   // >= 3 (the host sends shorter K to the fallback kernel)
+    issue_tile(xbase, xoff, 0, 0);
+    issue_tile(wbase, woff, 0, 1);
+    issue_tile(xbase, xoff, 1, 2);
+    issue_tile(wbase, woff, 1, 3);
+    issue_tile(xbase, xoff, 2, 4);
+    wait_loads<3 * LOADS>();       // step 0 has landed; X1, W1, X2 may still be in flight
     __syncthreads();
 
     bf16x8 wf0[NI], xf0[4], wf1[NI], xf1[4];
-    read_frags(0, 0, wf0, xf0);
+#pragma unroll
+    for (int r = 0; r < NREAD; ++r) read_frag(0, 0, r, wf0, xf0);
 
-    auto pin_slice = [&]() {       // NMFMA MFMAs with the NREAD fragment reads slotted after the first ones
+    // One slice: NMFMA MFMAs on (wf, xf); after MFMA m < NREAD the m-th fragment of the next slice is read into
+    // (wf_n, xf_n); after MFMA NREAD + g the g-th of `n_loads` loads (first_load ...) of `base` is issued.
+    // sched_barrier(0) after every instruction group keeps this order.
+    auto slice = [&](const bf16x8 (&wf)[NI], const bf16x8 (&xf)[4], bf16x8 (&wf_n)[NI], bf16x8 (&xf_n)[4], bool read_next,
+                     uint32_t slot_n, uint32_t kk_n, auto n_loads_c, const unsigned char* base,
+                     const uint32_t (&off)[LOADS], uint32_t kt_l, uint32_t slot_l, int first_load) {
+        constexpr int N_LOADS = decltype(n_loads_c)::value;
+        constexpr int LOAD_SLOTS = NMFMA - NREAD;                         // MFMAs after the reads
+        constexpr int PER = N_LOADS ? (N_LOADS + LOAD_SLOTS - 1) / LOAD_SLOTS : 0;
 #pragma unroll
-        for (int g = 0; g < NREAD; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NREAD, 0);
-    };
-    auto k_step = [&](uint32_t kt, auto next_frags, auto next_loads) {
-        constexpr bool NEXT = decltype(next_frags)::value, LOAD = decltype(next_loads)::value;
-        const uint32_t cur = kt & 1u;
-#pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
+        for (int m = 0; m < NMFMA; ++m) {
+            acc[m / 4][m % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[m / 4], xf[m % 4], acc[m / 4][m % 4], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (kk & 1) {
-                read_frags(cur, kk + 1, wf0, xf0);
-                mfma_slice<NI>(acc, wf1, xf1);
+            if (m < NREAD) {
+                if (read_next) read_frag(slot_n, kk_n, m, wf_n, xf_n);
             } else {
-                read_frags(cur, kk + 1, wf1, xf1);
-                mfma_slice<NI>(acc, wf0, xf0);
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int l = (m - NREAD) * PER + q;
+                    if (l < N_LOADS) issue_one(base, off, kt_l, slot_l, first_load + l);
+                }
             }
-            pin_slice();
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // X loads of a later step, spread over slices 0..2: counts per slice
+    constexpr int XA = (LOADS + 2) / 3, XB = (LOADS - XA + 1) / 2, XC = LOADS - XA - XB;
+    using none = std::integral_constant<int, 0>;
+    // `slot` is the ring slot of X of step kt; W of step kt sits in the next slot.
+    // LOAD_X: X of step kt+2 is issued during slices 0..2 (into the slot W of step kt-1 used);
+    // LOAD_W: W of step kt+2 is issued during slice 3 (into the slot X of step kt used).
+    auto k_step = [&](uint32_t kt, uint32_t slot, auto load_x, auto load_w, auto wait, auto next) {
+        constexpr bool LOAD_X = decltype(load_x)::value, LOAD_W = decltype(load_w)::value, NEXT = decltype(next)::value;
+        constexpr int WAIT = decltype(wait)::value;
+        const uint32_t slot_x2 = ring_add(slot, 4);     // (2(kt+2)) % 5
+        using xa = std::integral_constant<int, LOAD_X ? XA : 0>;
+        using xb = std::integral_constant<int, LOAD_X ? XB : 0>;
+        using xc = std::integral_constant<int, LOAD_X ? XC : 0>;
+        using wl = std::integral_constant<int, LOAD_W ? LOADS : 0>;
+        slice(wf0, xf0, wf1, xf1, true, slot, 1, xa{}, xbase, xoff, kt + 2, slot_x2, 0);
+        slice(wf1, xf1, wf0, xf0, true, slot, 2, xb{}, xbase, xoff, kt + 2, slot_x2, XA);
+        slice(wf0, xf0, wf1, xf1, true, slot, 3, xc{}, xbase, xoff, kt + 2, slot_x2, XA + XB);
         if constexpr (NEXT) {
-            wait_loads<0>();
+            wait_loads<WAIT>();
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (NEXT) read_frags(cur ^ 1u, 0, wf0, xf0);
-        if constexpr (LOAD) issue_loads(kt + 2);
-        mfma_slice<NI>(acc, wf1, xf1);
-        if constexpr (NEXT) {
-#pragma unroll
-            for (int g = 0; g < NREAD; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            if constexpr (LOAD) {
-#pragma unroll
-                for (int g = 0; g < NMFMA - NREAD; ++g) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x020, (2 * LOADS + NMFMA - NREAD - 1) / (NMFMA - NREAD), 0);
-                }
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        slice(wf1, xf1, wf0, xf0, NEXT, ring_add(slot, 2), 0, wl{}, wbase, woff, kt + 2, slot, 0);
     };
     using yes = std::true_type;
     using no = std::false_type;
-    uint32_t kt = 0;
-    for (; kt + 2 < n_k; ++kt) k_step(kt, yes{}, yes{});
-    k_step(kt, yes{}, no{});       // step n_k-2: nothing left to issue
-    k_step(kt + 1, no{}, no{});    // step n_k-1
+    const std::integral_constant<int, 0> w0;
+    const std::integral_constant<int, LOADS> w1;      // the X tile of the step after next may still be in flight
+    uint32_t kt = 0, slot = 0;
+    auto advance = [&]() {
+        ++kt;
+        slot = ring_add(slot, 2);
+    };
+    // step 0: X of step 2 is already on its way (issued above); only W of step 2 is issued here
+    k_step(kt, slot, no{}, yes{}, w1, yes{});
+    advance();
+    // At the barrier of step kt the loads in flight, oldest first, are X(kt+1), W(kt+1), X(kt+2): the last may stay.
+    for (; kt + 2 < n_k; advance()) k_step(kt, slot, yes{}, yes{}, w1, yes{});
+    k_step(kt, slot, no{}, no{}, w0, yes{});     // step n_k-2: the last step must have landed completely
+    advance();
+    k_step(kt, slot, no{}, no{}, w0, no{});      // step n_k-1
     __syncthreads();
     store_tile<NI>(acc, smem + wave * (128 * NI * 64), lane, a.y[tc.tensor], (size_t)a.row_begin,
                    tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D);
@@ -394,14 +431,14 @@ extern "C" int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf1
     static bool attr_set = false;   // dynamic LDS above 64 KB needs the attribute once per process
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)qkv_gemm_direct_kernel<kMainWN>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes);
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void*)qkv_gemm_staged_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(e));
         attr_set = true;
     }
-    if (a.D % BK == 0 && a.D >= 2 * BK)
-        hipLaunchKernelGGL(qkv_gemm_direct_kernel<kMainWN>, dim3(n_tiles), dim3(128 * kMainWN), kLdsBytes, as_stream(stream), a);
+    if (a.D % BK == 0 && a.D >= 3 * BK)
+        hipLaunchKernelGGL(qkv_gemm_direct_kernel<kMainWN>, dim3(n_tiles), dim3(128 * kMainWN), kRingLdsBytes, as_stream(stream), a);
     else
         hipLaunchKernelGGL(qkv_gemm_staged_kernel, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, as_stream(stream), a);
     return check_launch("qkv_gemm_kernel");
