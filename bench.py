@@ -1,10 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the Ulysses attention-input path on one MI355X.
 
-A step is one pass of the whole hot path over one synthetic layer input, all P logical ranks:
+A step is one pass of the whole hot path over one synthetic layer input, all P logical ranks, in the V-First
+order of the paper's Section III-C (V is projected first and its layout change and selection run under the
+Q and K work).  Default schedule "vfirst3", three HIP streams:
   stream V : qkv_proj(V) -> a2a_pack(V) -> a2a_unpack(V) -> vmajor_select(V, V_prev)
-  stream QK: [after V's projection] qkv_proj(Q, K) -> qk_norm_rope(Q, K) -> a2a_pack(Q), (K) -> a2a_unpack(Q), (K)
-(the V-First order of the paper's Section III-C; --schedule serial runs the same calls on one stream).
+  stream QK: [after V's projection] qkv_proj(Q) -> qkv_proj(K) -> qk_norm_rope(K) -> a2a_pack(K) -> a2a_unpack(K)
+  stream Q : [after Q's projection] qk_norm_rope(Q) -> a2a_pack(Q) -> a2a_unpack(Q)
+"vfirst" projects Q and K in one launch on two streams; "serial" runs the same calls on one stream.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line on stdout.
 """
 import argparse
@@ -47,7 +50,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--schedule", default="vfirst", choices=["vfirst", "serial"])
+    ap.add_argument("--schedule", default="vfirst3", choices=["vfirst", "vfirst3", "serial"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     args = ap.parse_args()
@@ -139,6 +142,43 @@ def main() -> int:
         done.record(s_qk)
         s_v.wait_event(done)                # join: the next layer cannot start before Q and K are laid out
 
+    s_q = torch.cuda.Stream()
+
+    def step_vfirst3(ev=None):
+        """V, then Q, then K projected one after the other (the order of the paper's Section III-C); each tensor's
+        norm/RoPE and layout change run on a side stream under the next tensor's projection."""
+        if ev:
+            ev[0].record(s_v)
+        cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=s_v)
+        if ev:
+            ev[1].record(s_v)
+        v_ready = torch.cuda.Event()
+        v_ready.record(s_v)
+        cd.a2a_pack(sh, v, bv, ORDER, stream=s_v)
+        cd.a2a_unpack(sh, bv, hv, ORDER, stream=s_v)
+        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
+        s_qk.wait_event(v_ready)
+        if ev:
+            ev[2].record(s_qk)
+        cd.qkv_proj(sh, X, Wq, None, None, q, None, None, stream=s_qk)
+        q_ready = torch.cuda.Event()
+        q_ready.record(s_qk)
+        cd.qkv_proj(sh, X, None, Wk, None, None, k, None, stream=s_qk)
+        if ev:
+            ev[3].record(s_qk)
+        s_q.wait_event(q_ready)
+        cd.qk_norm_rope(sh, q, None, gq, None, cfg.eps, rope, stream=s_q)
+        cd.a2a_pack(sh, q, bq, ORDER, stream=s_q)
+        cd.a2a_unpack(sh, bq, hq, ORDER, stream=s_q)
+        cd.qk_norm_rope(sh, None, k, None, gk, cfg.eps, rope, stream=s_qk)
+        cd.a2a_pack(sh, k, bk, ORDER, stream=s_qk)
+        cd.a2a_unpack(sh, bk, hk, ORDER, stream=s_qk)
+        done_q, done_k = torch.cuda.Event(), torch.cuda.Event()
+        done_q.record(s_q)
+        done_k.record(s_qk)
+        s_v.wait_event(done_q)
+        s_v.wait_event(done_k)
+
     def step_serial(ev=None):
         st = s_v
         if ev:
@@ -156,7 +196,7 @@ def main() -> int:
             cd.a2a_unpack(sh, buf, dst, ORDER, stream=st)
         cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=st)
 
-    step = step_vfirst if args.schedule == "vfirst" else step_serial
+    step = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial}[args.schedule]
 
     for _ in range(args.warmup):
         step()
@@ -173,14 +213,15 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = N / (ms_per_step * 1e-3)
 
-    # dominant kernel: the projection GEMM (two launches per step: V, then Q+K)
+    # dominant kernel: the projection GEMM (launched per step as V, then Q+K -- or V, Q, K in the vfirst3 order)
+    n_launch = 3 if args.schedule == "vfirst3" else 2
     gemm_ms = [(e[0].elapsed_time(e[1]), e[2].elapsed_time(e[3])) for e in events]
-    gemm_ms_per_launch = float(np.mean([a + b for a, b in gemm_ms])) / 2.0
-    flops_per_launch = 2.0 * N * (3 * D) * D / 2.0
+    gemm_ms_per_launch = float(np.mean([a + b for a, b in gemm_ms])) / n_launch
+    flops_per_launch = 2.0 * N * (3 * D) * D / n_launch
     achieved_tflops = flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12
     roofline = {"kernel": "qkv_gemm_kernel", "bound": "mfma", "achieved": round(achieved_tflops, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
-                "traffic": measured_traffic(cfg.name, args.schedule), "avg_launch_us": round(gemm_ms_per_launch * 1e3, 2), "launches_per_step": 2}
+                "traffic": measured_traffic(cfg.name, args.schedule), "avg_launch_us": round(gemm_ms_per_launch * 1e3, 2), "launches_per_step": n_launch}
 
     # ---- per-kernel times, each launched alone on one stream (not part of `value`) ----
     kernels = {}

@@ -207,6 +207,38 @@ def test_select_more_than_one_scan_round(oracle):
     assert n == len(idx)
 
 
+def test_select_large_tiles(oracle):
+    # a tile of 16 x 3200 values per slab: 6400 vectors per (tile, slab) segment, two slabs
+    rng = np.random.default_rng(79)
+    S, N, W, T = 2, 160, 3200, 16
+    cur = f32_to_bf16_bits(rng.standard_normal((S, N, W)).astype(np.float32))
+    prev, changed = perturb_tiles(cur, 1, T, 4, rng)
+    idx, n = _check_select(oracle, cur, prev, 1e-3, T)
+    assert np.array_equal(idx, changed)
+
+
+def test_select_repeated_calls_reuse_the_workspace(oracle):
+    # the status words of one call must not leak into the next: same buffers, different inputs
+    import torch
+    rng = np.random.default_rng(80)
+    S, N, W, T = 4, 4096, 64, 16
+    NT = N // T
+    ws = torch.empty(cd.vmajor_select_workspace_bytes(S, N, W, T), dtype=torch.uint8, device="cuda:0")
+    idx, n_act = dev_empty((NT,), "i32"), dev_empty((1,), "i32")
+    compact = dev_empty((S, NT * T, W))
+    cur = f32_to_bf16_bits(rng.standard_normal((S, N, W)).astype(np.float32))
+    cur_d = to_dev(cur)
+    for k in (200, 3, 0, NT, 57):
+        prev, changed = perturb_tiles(cur, 1, T, k, rng, sigma=0.5)
+        cd.vmajor_select(S, N, W, T, cur_d, to_dev(prev), 1e-3, None, idx, n_act, compact, NT, ws)
+        _sync()
+        n = int(n_act.cpu()[0])
+        assert n == k and np.array_equal(idx.cpu().numpy()[:n], changed)
+        got = to_host_bits(compact)
+        for j, t in enumerate(changed):
+            assert np.array_equal(got[:, j * T:(j + 1) * T], cur[:, t * T:(t + 1) * T])
+
+
 # ---------------------------------------------------------------------------
 # norm + RoPE
 # ---------------------------------------------------------------------------
