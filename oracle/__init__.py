@@ -11,16 +11,21 @@ Every function here is pinned by tests that do not go through this package's
 own formulas (brute force on tiny inputs, closed forms, invariants, library
 routines in special cases); no function is "parity unpinned".
 """
+from . import ref  # noqa: F401
 from .ref import (  # noqa: F401
     a2a_exchange,
     a2a_pack,
+    a2a_pack_hs,
     a2a_unpack,
+    a2a_unpack_seq,
     build_c,
     qk_norm_rope,
     qkv_proj,
     rms_norm,
     rope_rotate,
     token_coords,
+    vmajor_gather,
+    vmajor_scatter,
     vmajor_select,
     widen,
 )

@@ -119,3 +119,72 @@ int oracle_vmajor_select(int S, int N, int W, int T, const uint16_t* cur, const 
     }
     return n_active;
 }
+
+/*
+ * V-Major, sender side (Section III-D: Q and K send only their active part): gather the tiles listed
+ * in idx[0..n_active) of x [S][N][W] into compact [S][cap_tiles*T][W], tile j of the list at rows j*T .. ;
+ * tiles beyond cap_tiles are not gathered.
+ */
+void oracle_vmajor_gather(int S, int N, int W, int T, const uint16_t* x, const int32_t* idx, int n_active,
+                          uint16_t* compact, int cap_tiles) {
+    for (int j = 0; j < n_active && j < cap_tiles; ++j)
+        for (int s = 0; s < S; ++s)
+            for (int m = 0; m < T; ++m)
+                for (int w = 0; w < W; ++w)
+                    compact[((int64_t)s * cap_tiles * T + (int64_t)j * T + m) * W + w] =
+                        x[((int64_t)s * N + (int64_t)idx[j] * T + m) * W + w];
+}
+
+/*
+ * V-Major, receiver side (Section III-D: the receiver rebuilds the step's tensor from its cache): overwrite the
+ * tiles listed in idx of the cached tensor [S][N][W] with the received active tiles; every other tile keeps
+ * its cached value.
+ */
+void oracle_vmajor_scatter(int S, int N, int W, int T, const uint16_t* compact, const int32_t* idx, int n_active,
+                           uint16_t* cache, int cap_tiles) {
+    for (int j = 0; j < n_active && j < cap_tiles; ++j)
+        for (int s = 0; s < S; ++s)
+            for (int m = 0; m < T; ++m)
+                for (int w = 0; w < W; ++w)
+                    cache[((int64_t)s * N + (int64_t)idx[j] * T + m) * W + w] =
+                        compact[((int64_t)s * cap_tiles * T + (int64_t)j * T + m) * W + w];
+}
+
+/*
+ * Second Ulysses all-to-all (Section II-A: after attention, head-parallel layout back to sequence-parallel
+ * layout), as its steps.  Rank p holds y [Hp][N][d] for its heads; the chunk it sends to rank r carries the
+ * tokens r owns: chunk(p->r)[n][hl][i] = y[p*Hp + hl][r*Ns + n][i].
+ * Slot of chunk(p->r): SEND_MAJOR p*P + r (sender p's buffer), RECV_MAJOR r*P + p (receiver r's buffer).
+ */
+void oracle_a2a_pack_hs(const uint16_t* y_hs, uint16_t* xbuf, int N, int H, int d, int P,
+                        int rank_begin, int rank_count, int slot_order) {
+    const int Ns = N / P, Hp = H / P;
+    const int64_t chunk = (int64_t)Ns * Hp * d;
+#pragma omp parallel for schedule(static)
+    for (int p = rank_begin; p < rank_begin + rank_count; ++p)      /* source ranks: head owners */
+        for (int r = 0; r < P; ++r) {
+            uint16_t* c = xbuf + slot_of(p, r, P, slot_order) * chunk;
+            for (int n = 0; n < Ns; ++n)
+                for (int hl = 0; hl < Hp; ++hl)
+                    for (int i = 0; i < d; ++i)
+                        c[((int64_t)n * Hp + hl) * d + i] =
+                            y_hs[((int64_t)(p * Hp + hl) * N + (r * Ns + n)) * d + i];
+        }
+}
+
+/* x_seq[r*Ns + n][p*Hp + hl][i] = chunk(p->r)[n][hl][i], for destination ranks r (token owners) in the range */
+void oracle_a2a_unpack_seq(const uint16_t* xbuf, uint16_t* x_seq, int N, int H, int d, int P,
+                           int rank_begin, int rank_count, int slot_order) {
+    const int Ns = N / P, Hp = H / P;
+    const int64_t chunk = (int64_t)Ns * Hp * d;
+#pragma omp parallel for schedule(static)
+    for (int r = rank_begin; r < rank_begin + rank_count; ++r)
+        for (int p = 0; p < P; ++p) {
+            const uint16_t* c = xbuf + slot_of(p, r, P, slot_order) * chunk;
+            for (int n = 0; n < Ns; ++n)
+                for (int hl = 0; hl < Hp; ++hl)
+                    for (int i = 0; i < d; ++i)
+                        x_seq[((int64_t)(r * Ns + n) * H + (p * Hp + hl)) * d + i] =
+                            c[((int64_t)n * Hp + hl) * d + i];
+        }
+}

@@ -49,6 +49,14 @@ def _c():
         lib.oracle_a2a_unpack.restype = None
         lib.oracle_vmajor_select.argtypes = [ci, ci, ci, ci, u16p, u16p, ctypes.c_float, i32p, i32p, u16p, ci]
         lib.oracle_vmajor_select.restype = ci
+        lib.oracle_vmajor_gather.argtypes = [ci, ci, ci, ci, u16p, i32p, ci, u16p, ci]
+        lib.oracle_vmajor_gather.restype = None
+        lib.oracle_vmajor_scatter.argtypes = [ci, ci, ci, ci, u16p, i32p, ci, u16p, ci]
+        lib.oracle_vmajor_scatter.restype = None
+        lib.oracle_a2a_pack_hs.argtypes = [u16p, u16p, ci, ci, ci, ci, ci, ci, ci]
+        lib.oracle_a2a_pack_hs.restype = None
+        lib.oracle_a2a_unpack_seq.argtypes = [u16p, u16p, ci, ci, ci, ci, ci, ci, ci]
+        lib.oracle_a2a_unpack_seq.restype = None
         _lib = lib
     return _lib
 
@@ -191,3 +199,49 @@ def vmajor_select(v_cur: np.ndarray, v_prev: np.ndarray, tau: float, tile_tokens
         S, N, W, tile_tokens, _u16(v_cur), _u16(v_prev), np.float32(tau), _i32(flags), _i32(idx),
         _u16(compact) if want_compact else None, cap)
     return flags, idx[:n_active].copy(), int(n_active), compact
+
+
+def vmajor_gather(x: np.ndarray, idx: np.ndarray, tile_tokens: int = 16, cap_tiles: Optional[int] = None) -> np.ndarray:
+    """Gather the listed tiles of x [S][N][W] into [S][cap*T][W] (Section III-D, extraction of active projections)."""
+    S, N, W = x.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    cap = max(len(idx), 1) if cap_tiles is None else cap_tiles
+    out = np.zeros((S, cap * tile_tokens, W), dtype=np.uint16)
+    _c().oracle_vmajor_gather(S, N, W, tile_tokens, _u16(x), _i32(idx), len(idx), _u16(out), cap)
+    return out
+
+
+def vmajor_scatter(compact: np.ndarray, idx: np.ndarray, cache: np.ndarray, tile_tokens: int = 16) -> np.ndarray:
+    """Overwrite the listed tiles of a copy of cache [S][N][W] with compact [S][cap*T][W] (receiver reconstruction)."""
+    S, N, W = cache.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    cap = compact.shape[1] // tile_tokens
+    out = cache.copy()
+    _c().oracle_vmajor_scatter(S, N, W, tile_tokens, _u16(compact), _i32(idx), len(idx), _u16(out), cap)
+    return out
+
+
+# ---------------------------------------------------------------------------
+# Ulysses all-to-all #2: head-parallel -> sequence-parallel (Section II-A)
+# ---------------------------------------------------------------------------
+
+def a2a_pack_hs(y_hs: np.ndarray, P: int, slot_order: int = SEND_MAJOR, rank_begin: int = 0,
+                rank_count: Optional[int] = None, out: Optional[np.ndarray] = None) -> np.ndarray:
+    """[H][N][d] -> exchange buffer [P*P][Ns][Hp][d]; only source ranks (head owners) in the range are written."""
+    H, N, d = y_hs.shape
+    rank_count = P if rank_count is None else rank_count
+    if out is None:
+        out = np.zeros((P * P, N // P, H // P, d), dtype=np.uint16)
+    _c().oracle_a2a_pack_hs(_u16(y_hs), _u16(out), N, H, d, P, rank_begin, rank_count, slot_order)
+    return out
+
+
+def a2a_unpack_seq(xbuf: np.ndarray, N: int, H: int, d: int, P: int, slot_order: int = SEND_MAJOR,
+                   rank_begin: int = 0, rank_count: Optional[int] = None,
+                   out: Optional[np.ndarray] = None) -> np.ndarray:
+    """Exchange buffer -> sequence-parallel [N][H][d]; only destination ranks (token owners) in the range are written."""
+    rank_count = P if rank_count is None else rank_count
+    if out is None:
+        out = np.zeros((N, H, d), dtype=np.uint16)
+    _c().oracle_a2a_unpack_seq(_u16(xbuf), _u16(out), N, H, d, P, rank_begin, rank_count, slot_order)
+    return out

@@ -457,3 +457,90 @@ def test_select_scatter_back_leaves_nothing_active(oracle):
         rebuilt[:, t * T:(t + 1) * T, :] = compact[:, j * T:(j + 1) * T, :]
     assert oracle.vmajor_select(cur, rebuilt, cfg.tau, T)[2] == 0
     assert np.array_equal(rebuilt, cur)
+
+
+# ---------------------------------------------------------------------------
+# V-Major gather / scatter (sender-side extraction, receiver-side reconstruction)
+# ---------------------------------------------------------------------------
+
+def test_gather_scatter_brute_force_and_reconstruction(oracle):
+    rng = np.random.default_rng(21)
+    S, N, W, T = 3, 96, 8, 16
+    x = rng.integers(0, 65536, size=(S, N, W)).astype(np.uint16)
+    x_prev = rng.integers(0, 65536, size=(S, N, W)).astype(np.uint16)
+    idx = np.array([1, 4, 5], dtype=np.int32)
+    g = oracle.vmajor_gather(x, idx, T)
+    assert g.shape == (S, 3 * T, W)
+    for j, t in enumerate(idx):
+        for s in range(S):
+            for m in range(T):
+                for w in range(W):
+                    assert g[s, j * T + m, w] == x[s, t * T + m, w]
+    rebuilt = oracle.vmajor_scatter(g, idx, x_prev, T)
+    for t in range(N // T):
+        want = x if t in idx else x_prev
+        assert np.array_equal(rebuilt[:, t * T:(t + 1) * T], want[:, t * T:(t + 1) * T])
+    # an empty list changes nothing; a small capacity gathers / scatters only the first tiles
+    assert np.array_equal(oracle.vmajor_scatter(g, np.zeros(0, np.int32), x_prev, T), x_prev)
+    g2 = oracle.vmajor_gather(x, idx, T, cap_tiles=2)
+    assert g2.shape == (S, 2 * T, W) and np.array_equal(g2, g[:, :2 * T])
+    r2 = oracle.vmajor_scatter(g2, idx, x_prev, T)
+    assert np.array_equal(r2[:, 5 * T:6 * T], x_prev[:, 5 * T:6 * T]) and np.array_equal(r2[:, 4 * T:5 * T], x[:, 4 * T:5 * T])
+
+
+def test_gather_by_selected_tiles_equals_the_selections_own_compaction(oracle):
+    cfg = CONFIGS["C1"]
+    cur, prev, changed = make_v_pair(cfg)
+    _, idx, n, compact = oracle.vmajor_select(cur, prev, cfg.tau, cfg.tile_tokens)
+    g = oracle.vmajor_gather(cur, idx, cfg.tile_tokens, cap_tiles=cfg.NT)
+    assert np.array_equal(g[:, :n * cfg.tile_tokens], compact[:, :n * cfg.tile_tokens])
+    # sender gathers, receiver scatters into its cache: the cache becomes the current tensor
+    assert np.array_equal(oracle.vmajor_scatter(g, idx, prev, cfg.tile_tokens), cur)
+
+
+# ---------------------------------------------------------------------------
+# second all-to-all: head-parallel -> sequence-parallel
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,H,d,P", [(32, 4, 8, 2), (48, 6, 8, 3), (16, 4, 8, 1), (64, 4, 16, 4)])
+def test_second_all_to_all_is_the_inverse_transpose(oracle, N, H, d, P):
+    y = np.arange(N * H * d, dtype=np.uint32).astype(np.uint16).reshape(H, N, d)
+    want = np.ascontiguousarray(y.transpose(1, 0, 2))
+    for order in (0, 1):
+        buf = oracle.a2a_pack_hs(y, P, order)
+        assert np.array_equal(np.sort(buf.reshape(-1)), y.reshape(-1))
+        assert np.array_equal(oracle.a2a_unpack_seq(buf, N, H, d, P, order), want)
+    # literal round trip: first all-to-all, then the second, gives the tensor back
+    x = np.random.default_rng(3).integers(0, 65536, size=(N, H, d)).astype(np.uint16)
+    hs = oracle.a2a_unpack(oracle.a2a_pack(x, P, 1), N, H, d, P, 1)
+    back = oracle.a2a_unpack_seq(oracle.a2a_pack_hs(hs, P, 0), N, H, d, P, 0)
+    assert np.array_equal(back, x)
+
+
+def test_second_all_to_all_chunk_contents_brute_force(oracle):
+    N, H, d, P = 48, 6, 8, 3
+    Ns, Hp = N // P, H // P
+    y = np.arange(N * H * d, dtype=np.uint32).astype(np.uint16).reshape(H, N, d)
+    send = oracle.a2a_pack_hs(y, P, 0).reshape(-1)
+    recv = oracle.a2a_pack_hs(y, P, 1).reshape(-1)
+    chunk = Ns * Hp * d
+    for p in range(P):            # sender: owner of heads p*Hp ..
+        for r in range(P):        # receiver: owner of tokens r*Ns ..
+            for n in range(Ns):
+                for hl in range(Hp):
+                    for i in (0, d - 1):
+                        src = ((p * Hp + hl) * N + r * Ns + n) * d + i
+                        off = (n * Hp + hl) * d + i
+                        assert send[(p * P + r) * chunk + off] == src
+                        assert recv[(r * P + p) * chunk + off] == src
+    # per-rank calls fill the same buffer as one call
+    whole = oracle.a2a_pack_hs(y, P, 1)
+    parts = np.zeros_like(whole)
+    for p in (2, 0, 1):
+        oracle.a2a_pack_hs(y, P, 1, rank_begin=p, rank_count=1, out=parts)
+    assert np.array_equal(parts, whole)
+    out = np.zeros((N, H, d), dtype=np.uint16)
+    oracle.a2a_unpack_seq(whole, N, H, d, P, 1, rank_begin=1, rank_count=2, out=out)
+    assert not out[:Ns].any()
+    oracle.a2a_unpack_seq(whole, N, H, d, P, 1, rank_begin=0, rank_count=1, out=out)
+    assert np.array_equal(out, y.transpose(1, 0, 2))
