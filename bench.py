@@ -261,6 +261,13 @@ def main() -> int:
         f_act = cfg.n_changed / NT
         add("vmajor_select", timed(lambda: cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act,
                                                             compact, cap, ws)), nbytes=(2 + f_act) * tensor_bytes)
+        # rows after the hot path: sender-side gather / receiver-side scatter of the active tiles, second all-to-all
+        act = bf((H, cap * T, d))
+        add("vmajor_gather", timed(lambda: cd.vmajor_gather(H, N, d, T, hq, idx, n_act, act, cap)), nbytes=2 * f_act * tensor_bytes)
+        add("vmajor_scatter", timed(lambda: cd.vmajor_scatter(H, N, d, T, act, idx, n_act, hk, cap)), nbytes=2 * f_act * tensor_bytes)
+        add("a2a_pack_hs", timed(lambda: cd.a2a_pack_hs(sh, hv, bv, ORDER)), nbytes=2 * tensor_bytes)
+        add("a2a_unpack_seq", timed(lambda: cd.a2a_unpack_seq(sh, bv, v, ORDER)), nbytes=2 * tensor_bytes)
+        del act
         add("copy_same_bytes", timed(lambda: cd.util_copy(v, bv, tensor_bytes)), nbytes=2 * tensor_bytes)
         big = 1000 << 20   # not a power of two: source and destination must not alias onto the same HBM banks
         src_big = torch.empty(big + (3 << 20), dtype=torch.uint8, device=dev)

@@ -156,6 +156,44 @@ COCODIFF_API int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t
 /* Bytes of device scratch cocodiff_vmajor_select needs for this shape (0 on a bad shape). */
 COCODIFF_API size_t cocodiff_vmajor_select_workspace_bytes(int32_t S, int32_t N, int32_t W, int32_t tile_tokens);
 
+/*
+ * V-Major, sender side (Section III-D: Q and K send only their active part; the list comes from V's selection).
+ * compact[s][j*tile_tokens + m][w] = x[s][active_idx[j]*tile_tokens + m][w] for j < min(*n_active, cap_tiles).
+ * x [S][N][W] (sequence layout: S = 1, W = D; head-parallel: S = H, W = d); compact [S][cap_tiles*tile_tokens][W];
+ * active_idx, n_active: DEVICE data as written by cocodiff_vmajor_select (no host read, no synchronisation).
+ * List entries outside [0, N/tile_tokens) are skipped.  Shape rules as for the selection; cap_tiles >= 1.
+ */
+COCODIFF_API int cocodiff_vmajor_gather(int32_t S, int32_t N, int32_t W, int32_t tile_tokens, const cocodiff_bf16* x,
+                                        const int32_t* active_idx, const int32_t* n_active, cocodiff_bf16* compact,
+                                        int32_t cap_tiles, void* stream);
+
+/*
+ * V-Major, receiver side (Section III-D: indexed overwrite of the cached tensor), IN PLACE on `cache`:
+ * cache[s][active_idx[j]*tile_tokens + m][w] = compact[s][j*tile_tokens + m][w] for j < min(*n_active, cap_tiles);
+ * every other tile of cache [S][N][W] keeps its value.  Same argument rules as cocodiff_vmajor_gather.
+ */
+COCODIFF_API int cocodiff_vmajor_scatter(int32_t S, int32_t N, int32_t W, int32_t tile_tokens, const cocodiff_bf16* compact,
+                                         const int32_t* active_idx, const int32_t* n_active, cocodiff_bf16* cache,
+                                         int32_t cap_tiles, void* stream);
+
+/*
+ * Second all-to-all (Section II-A: after attention, head-parallel back to sequence-parallel), sender side.
+ * y_hs [H][N][d] -> xbuf, P*P chunks of [N/P][H/P][d]:
+ *   chunk(p->r)[n][hl][i] = y_hs[p*H/P + hl][r*N/P + n][i]   for SOURCE ranks p (head owners) in the range.
+ * Slot of chunk(p->r): p*P + r (SEND_MAJOR) or r*P + p (RECV_MAJOR).
+ */
+COCODIFF_API int cocodiff_a2a_pack_hs(const cocodiff_shape* shape, const cocodiff_bf16* y_hs, cocodiff_bf16* xbuf,
+                                      int slot_order, void* stream);
+
+/*
+ * Second all-to-all, receiver side: xbuf -> y_seq [N][H][d]:
+ *   y_seq[r*N/P + n][p*H/P + hl][i] = chunk(p->r)[n][hl][i]   for DESTINATION ranks r (token owners) in the range.
+ * With the same slot_order, pack_hs + unpack_seq gives y_seq[n][h][i] == y_hs[h][n][i]; after
+ * cocodiff_a2a_pack + cocodiff_a2a_unpack it returns the original tensor.
+ */
+COCODIFF_API int cocodiff_a2a_unpack_seq(const cocodiff_shape* shape, const cocodiff_bf16* xbuf, cocodiff_bf16* y_seq,
+                                         int slot_order, void* stream);
+
 /* Host helpers (not on the hot path). */
 
 /* Bytes of the cos/sin table described at cocodiff_rope (0 on a bad description; `cs` is ignored). */

@@ -11,12 +11,16 @@ from .binding import (  # noqa: F401
     Rope,
     Shape,
     a2a_pack,
+    a2a_pack_hs,
     a2a_unpack,
+    a2a_unpack_seq,
     qk_norm_rope,
     qkv_proj,
     rope_table,
     util_copy,
     version,
+    vmajor_gather,
+    vmajor_scatter,
     vmajor_select,
     vmajor_select_workspace_bytes,
 )

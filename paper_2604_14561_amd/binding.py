@@ -21,7 +21,8 @@ SEND_MAJOR, RECV_MAJOR = 0, 1
 
 EXPORTS = (
     "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
-    "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_rope_table_bytes",
+    "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
+    "cocodiff_vmajor_scatter", "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
     "cocodiff_rope_table_fill", "cocodiff_util_copy", "cocodiff_version", "cocodiff_last_error",
 )
 
@@ -72,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_a2a_pack.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_a2a_unpack.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_vmajor_select.argtypes = [i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.cocodiff_vmajor_gather.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+        L.cocodiff_vmajor_scatter.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+        L.cocodiff_a2a_pack_hs.argtypes = [sp, vp, vp, ci, vp]
+        L.cocodiff_a2a_unpack_seq.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_vmajor_select_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.cocodiff_vmajor_select_workspace_bytes.restype = sz
         L.cocodiff_rope_table_bytes.argtypes = [rp]
@@ -81,7 +86,8 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_version.restype = ctypes.c_char_p
         L.cocodiff_last_error.restype = ctypes.c_char_p
         for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
-                     "cocodiff_vmajor_select", "cocodiff_rope_table_fill", "cocodiff_util_copy"):
+                     "cocodiff_vmajor_select", "cocodiff_vmajor_gather", "cocodiff_vmajor_scatter",
+                     "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_fill", "cocodiff_util_copy"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -148,6 +154,24 @@ def vmajor_select(S: int, N: int, W: int, tile_tokens: int, v_cur, v_prev, tau: 
     _check(lib().cocodiff_vmajor_select(S, N, W, tile_tokens, _ptr(v_cur), _ptr(v_prev), float(tau), _ptr(flags),
                                         _ptr(active_idx), _ptr(n_active), _ptr(compact), int(cap_tiles),
                                         _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def vmajor_gather(S: int, N: int, W: int, tile_tokens: int, x, active_idx, n_active, compact, cap_tiles: int, stream=None) -> None:
+    _check(lib().cocodiff_vmajor_gather(S, N, W, tile_tokens, _ptr(x), _ptr(active_idx), _ptr(n_active), _ptr(compact),
+                                        int(cap_tiles), _stream(stream)))
+
+
+def vmajor_scatter(S: int, N: int, W: int, tile_tokens: int, compact, active_idx, n_active, cache, cap_tiles: int, stream=None) -> None:
+    _check(lib().cocodiff_vmajor_scatter(S, N, W, tile_tokens, _ptr(compact), _ptr(active_idx), _ptr(n_active), _ptr(cache),
+                                         int(cap_tiles), _stream(stream)))
+
+
+def a2a_pack_hs(shape: Shape, y_hs, xbuf, slot_order: int = SEND_MAJOR, stream=None) -> None:
+    _check(lib().cocodiff_a2a_pack_hs(ctypes.byref(shape), _ptr(y_hs), _ptr(xbuf), int(slot_order), _stream(stream)))
+
+
+def a2a_unpack_seq(shape: Shape, xbuf, y_seq, slot_order: int = SEND_MAJOR, stream=None) -> None:
+    _check(lib().cocodiff_a2a_unpack_seq(ctypes.byref(shape), _ptr(xbuf), _ptr(y_seq), int(slot_order), _stream(stream)))
 
 
 def rope_table(grid: Sequence[int], pairs: Sequence[int], theta: float) -> np.ndarray:

@@ -260,7 +260,6 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
 
     // X loads of a later step, spread over slices 0..2: counts per slice
     constexpr int XA = (LOADS + 2) / 3, XB = (LOADS - XA + 1) / 2, XC = LOADS - XA - XB;
-    using none = std::integral_constant<int, 0>;
     // `slot` is the ring slot of X of step kt; W of step kt sits in the next slot.
     // LOAD_X: X of step kt+2 is issued during slices 0..2 (into the slot W of step kt-1 used);
     // LOAD_W: W of step kt+2 is issued during slice 3 (into the slot X of step kt used).

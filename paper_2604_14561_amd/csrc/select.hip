@@ -116,6 +116,39 @@ __global__ void __launch_bounds__(kSelThreads) select_gather_kernel(const vec16*
     }
 }
 
+// Workgroup j moves tile idx[j] (j < n_active, j < cap_tiles) between x [S][N][W] and compact [S][cap*T][W]:
+// GATHER compact <- x (sender-side extraction of the active tiles), else x <- compact (receiver-side overwrite
+// of the cached tensor).  A list entry outside [0, NT) is skipped, so a corrupt list cannot fault.
+template <bool GATHER>
+__global__ void __launch_bounds__(kSelThreads) tile_move_kernel(vec16* __restrict__ x, vec16* __restrict__ compact,
+                                                                const int32_t* __restrict__ idx, const int32_t* __restrict__ n_active,
+                                                                SelectShape sh, uint32_t cap_tiles) {
+    const uint32_t j = blockIdx.x;
+    const int32_t n = *n_active;
+    if (n <= 0 || j >= (uint32_t)n) return;
+    const uint32_t t = (uint32_t)idx[j];
+    if (t >= sh.NT) return;
+    const uint32_t total = sh.S * sh.seg8;
+    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * kSelThreads) {
+        vec16 c[kSelUnroll];
+        uint64_t dst[kSelUnroll];
+#pragma unroll
+        for (int k = 0; k < kSelUnroll; ++k) {
+            const uint32_t g = g0 + k * kSelThreads;
+            if (g < total) {
+                const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
+                const uint64_t x_at = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v;
+                const uint64_t c_at = ((uint64_t)s * cap_tiles + j) * sh.seg8 + v;
+                c[k] = GATHER ? x[x_at] : compact[c_at];
+                dst[k] = GATHER ? c_at : x_at;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kSelUnroll; ++k)
+            if (g0 + k * kSelThreads < total) (GATHER ? compact : x)[dst[k]] = c[k];
+    }
+}
+
 static int select_shape(int32_t S, int32_t N, int32_t W, int32_t T, SelectShape* out) {
     if (S <= 0 || N <= 0 || W <= 0 || T <= 0) return fail(COCODIFF_ERR_SHAPE, "select: S, N, W, tile_tokens must be positive");
     if (W % 8) return fail(COCODIFF_ERR_SHAPE, "select: W (%d) must be a multiple of 8", W);
@@ -170,4 +203,35 @@ extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t t
                        (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh,
                        compact ? (uint32_t)cap_tiles : 0u);
     return check_launch("select_gather_kernel");
+}
+
+static int tile_move(bool gather, int32_t S, int32_t N, int32_t W, int32_t tile_tokens, const void* x, const void* compact,
+                     const int32_t* active_idx, const int32_t* n_active, int32_t cap_tiles, void* stream) {
+    const char* who = gather ? "vmajor_gather" : "vmajor_scatter";
+    SelectShape sh;
+    int rc = select_shape(S, N, W, tile_tokens, &sh);
+    if (rc != COCODIFF_OK) return rc;
+    if (!x || !compact || !active_idx || !n_active) return fail(COCODIFF_ERR_NULL, "%s: NULL pointer", who);
+    if (!aligned16(x) || !aligned16(compact)) return fail(COCODIFF_ERR_ALIGN, "%s: tensors must be 16-byte aligned", who);
+    if (cap_tiles < 1) return fail(COCODIFF_ERR_CAPACITY, "%s: cap_tiles (%d) must be >= 1", who, cap_tiles);
+    const uint32_t blocks = (uint32_t)cap_tiles < sh.NT ? (uint32_t)cap_tiles : sh.NT;
+    if (gather)
+        hipLaunchKernelGGL(tile_move_kernel<true>, dim3(blocks), dim3(kSelThreads), 0, as_stream(stream), (vec16*)x,
+                           (vec16*)compact, active_idx, n_active, sh, (uint32_t)cap_tiles);
+    else
+        hipLaunchKernelGGL(tile_move_kernel<false>, dim3(blocks), dim3(kSelThreads), 0, as_stream(stream), (vec16*)x,
+                           (vec16*)compact, active_idx, n_active, sh, (uint32_t)cap_tiles);
+    return check_launch(who);
+}
+
+extern "C" int cocodiff_vmajor_gather(int32_t S, int32_t N, int32_t W, int32_t tile_tokens, const cocodiff_bf16* x,
+                                      const int32_t* active_idx, const int32_t* n_active, cocodiff_bf16* compact,
+                                      int32_t cap_tiles, void* stream) {
+    return tile_move(true, S, N, W, tile_tokens, x, compact, active_idx, n_active, cap_tiles, stream);
+}
+
+extern "C" int cocodiff_vmajor_scatter(int32_t S, int32_t N, int32_t W, int32_t tile_tokens, const cocodiff_bf16* compact,
+                                       const int32_t* active_idx, const int32_t* n_active, cocodiff_bf16* cache,
+                                       int32_t cap_tiles, void* stream) {
+    return tile_move(false, S, N, W, tile_tokens, cache, compact, active_idx, n_active, cap_tiles, stream);
 }

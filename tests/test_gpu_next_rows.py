@@ -1,0 +1,168 @@
+"""GPU parity for the rows after the hot path: V-Major gather / scatter (Section III-D, sender-side extraction
+and receiver-side reconstruction) and the second all-to-all (Section II-A).  All byte work: bit-exact."""
+import numpy as np
+import pytest
+
+import paper_2604_14561_amd as cd
+from parity_util import dev_empty, to_dev, to_host_bits
+from synth import CONFIGS, make_v_pair
+
+gpu = pytest.mark.gpu
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _shape(cfg, rank_begin=0, rank_count=None):
+    return cd.Shape.make(cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, rank_begin, rank_count)
+
+
+@gpu
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_second_all_to_all_bit_exact_and_round_trip(oracle, name):
+    cfg = CONFIGS[name]
+    print(f"second all-to-all {name}", flush=True)
+    rng = np.random.default_rng(500 + cfg.index)
+    y = rng.integers(0, 65536, size=(cfg.H, cfg.N, cfg.d), dtype=np.uint16)
+    yd = to_dev(y)
+    for order in (cd.SEND_MAJOR, cd.RECV_MAJOR):
+        buf = dev_empty((cfg.P * cfg.P, cfg.Ns, cfg.Hp, cfg.d))
+        buf.fill_(-1)
+        seq = dev_empty((cfg.N, cfg.H, cfg.d))
+        seq.fill_(-1)
+        cd.a2a_pack_hs(_shape(cfg), yd, buf, order)
+        cd.a2a_unpack_seq(_shape(cfg), buf, seq, order)
+        _sync()
+        want_buf = oracle.a2a_pack_hs(y, cfg.P, order)
+        assert np.array_equal(to_host_bits(buf), want_buf)
+        got = to_host_bits(seq)
+        assert np.array_equal(got, oracle.a2a_unpack_seq(want_buf, cfg.N, cfg.H, cfg.d, cfg.P, order))
+        assert np.array_equal(got, y.transpose(1, 0, 2))
+        del buf
+    # literal round trip: first all-to-all on what came back gives the head-parallel tensor again
+    buf = dev_empty((cfg.P * cfg.P, cfg.Ns, cfg.Hp, cfg.d))
+    hs = dev_empty((cfg.H, cfg.N, cfg.d))
+    cd.a2a_pack(_shape(cfg), seq, buf, cd.RECV_MAJOR)
+    cd.a2a_unpack(_shape(cfg), buf, hs, cd.RECV_MAJOR)
+    _sync()
+    assert np.array_equal(to_host_bits(hs), y)
+
+
+@gpu
+def test_second_all_to_all_rank_ranges(oracle):
+    cfg = CONFIGS["C2"]
+    rng = np.random.default_rng(7)
+    y = rng.integers(0, 65536, size=(cfg.H, cfg.N, cfg.d), dtype=np.uint16)
+    yd = to_dev(y)
+    buf = dev_empty((cfg.P * cfg.P, cfg.Ns, cfg.Hp, cfg.d))
+    buf.fill_(-1)
+    for p in reversed(range(cfg.P)):            # one head owner at a time
+        cd.a2a_pack_hs(_shape(cfg, p, 1), yd, buf, cd.SEND_MAJOR)
+    _sync()
+    assert np.array_equal(to_host_bits(buf), oracle.a2a_pack_hs(y, cfg.P, 0))
+    seq = dev_empty((cfg.N, cfg.H, cfg.d))
+    seq.fill_(-1)
+    cd.a2a_unpack_seq(_shape(cfg, 3, 4), buf, seq, cd.SEND_MAJOR)
+    _sync()
+    got = to_host_bits(seq)
+    assert np.all(got[:3 * cfg.Ns] == 0xFFFF) and np.all(got[7 * cfg.Ns:] == 0xFFFF)
+    assert np.array_equal(got[3 * cfg.Ns:7 * cfg.Ns], y.transpose(1, 0, 2)[3 * cfg.Ns:7 * cfg.Ns])
+
+
+@gpu
+@pytest.mark.parametrize("name", ["C1", "C3", "C5"])
+def test_gather_and_scatter_close_the_selection_loop(oracle, name):
+    import torch
+    cfg = CONFIGS[name]
+    print(f"gather/scatter {name}", flush=True)
+    T, NT = cfg.tile_tokens, cfg.NT
+    cur, prev, changed = make_v_pair(cfg, layout="hs")
+    cur_d, prev_d = to_dev(cur), to_dev(prev)
+    ws = torch.empty(max(cd.vmajor_select_workspace_bytes(cfg.H, cfg.N, cfg.d, T), 16), dtype=torch.uint8, device="cuda:0")
+    idx, n_act = dev_empty((NT,), "i32"), dev_empty((1,), "i32")
+    cd.vmajor_select(cfg.H, cfg.N, cfg.d, T, cur_d, prev_d, cfg.tau, None, idx, n_act, None, 0, ws)
+    # sender: gather the active tiles of another tensor (stands for Q or K) by V's list, without reading it on the host
+    rng = np.random.default_rng(600 + cfg.index)
+    q = rng.integers(0, 65536, size=(cfg.H, cfg.N, cfg.d), dtype=np.uint16)
+    cap = cfg.n_changed + 3
+    q_act = dev_empty((cfg.H, cap * T, cfg.d))
+    q_act.fill_(-1)
+    cd.vmajor_gather(cfg.H, cfg.N, cfg.d, T, to_dev(q), idx, n_act, q_act, cap)
+    # receiver: overwrite its cached copy
+    q_cache = rng.integers(0, 65536, size=(cfg.H, cfg.N, cfg.d), dtype=np.uint16)
+    cache_d = to_dev(q_cache)
+    cd.vmajor_scatter(cfg.H, cfg.N, cfg.d, T, q_act, idx, n_act, cache_d, cap)
+    # and V itself: gather + scatter into the previous step's V must rebuild the current V
+    v_act = dev_empty((cfg.H, cap * T, cfg.d))
+    cd.vmajor_gather(cfg.H, cfg.N, cfg.d, T, cur_d, idx, n_act, v_act, cap)
+    cd.vmajor_scatter(cfg.H, cfg.N, cfg.d, T, v_act, idx, n_act, prev_d, cap)
+    _sync()
+    n = int(n_act.cpu()[0])
+    assert n == cfg.n_changed
+    want_act = oracle.vmajor_gather(q, changed, T, cap_tiles=cap)
+    got_act = to_host_bits(q_act)
+    assert np.array_equal(got_act[:, :n * T], want_act[:, :n * T])
+    assert np.all(got_act[:, n * T:] == 0xFFFF)                       # rows beyond the list are not written
+    assert np.array_equal(to_host_bits(cache_d), oracle.vmajor_scatter(want_act, changed, q_cache, T))
+    assert np.array_equal(to_host_bits(prev_d), cur)
+
+
+@gpu
+def test_gather_scatter_edge_cases(oracle):
+    rng = np.random.default_rng(9)
+    S, N, W, T = 3, 1280, 40, 16
+    NT = N // T
+    x = rng.integers(0, 65536, size=(S, N, W), dtype=np.uint16)
+    cache = rng.integers(0, 65536, size=(S, N, W), dtype=np.uint16)
+
+    def run(idx_list, n, cap):
+        idx = np.full(NT, -5, dtype=np.int32)
+        idx[:len(idx_list)] = idx_list
+        idx_d, n_d = to_dev(idx), to_dev(np.array([n], dtype=np.int32))
+        comp = dev_empty((S, cap * T, W))
+        comp.fill_(-1)
+        cd.vmajor_gather(S, N, W, T, to_dev(x), idx_d, n_d, comp, cap)
+        c_d = to_dev(cache)
+        cd.vmajor_scatter(S, N, W, T, comp, idx_d, n_d, c_d, cap)
+        _sync()
+        return to_host_bits(comp), to_host_bits(c_d)
+
+    # empty list: nothing moves
+    comp, c = run([], 0, 4)
+    assert np.all(comp == 0xFFFF) and np.array_equal(c, cache)
+    # capacity smaller than the list: only the first cap tiles move
+    lst = [0, 7, 79, 33]
+    comp, c = run(lst, 4, 2)
+    want = oracle.vmajor_gather(x, np.array(lst, np.int32), T, cap_tiles=2)
+    assert np.array_equal(comp, want)
+    assert np.array_equal(c, oracle.vmajor_scatter(want, np.array(lst, np.int32), cache, T))
+    # full list in arbitrary order, first and last tile included
+    lst = [79, 0, 41]
+    comp, c = run(lst, 3, 3)
+    want = oracle.vmajor_gather(x, np.array(lst, np.int32), T, cap_tiles=3)
+    assert np.array_equal(comp, want) and np.array_equal(c, oracle.vmajor_scatter(want, np.array(lst, np.int32), cache, T))
+    # an entry outside the tile range is skipped, not dereferenced
+    comp, c = run([5, 4000, -1, 6], 4, 4)
+    assert np.array_equal(comp[:, :T], x[:, 5 * T:6 * T]) and np.array_equal(comp[:, 3 * T:4 * T], x[:, 6 * T:7 * T])
+    assert np.all(comp[:, T:3 * T] == 0xFFFF)
+
+
+def test_next_rows_argument_errors():
+    import ctypes
+    from paper_2604_14561_amd import binding as B
+    L = B.lib()
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    g = L.cocodiff_vmajor_gather
+    assert g(4, 256, 60, 16, fake, fake, fake, fake, 4, None) == B.ERR_SHAPE
+    assert g(4, 256, 64, 16, None, fake, fake, fake, 4, None) == B.ERR_NULL
+    assert g(4, 256, 64, 16, fake, fake, None, fake, 4, None) == B.ERR_NULL
+    assert g(4, 256, 64, 16, odd, fake, fake, fake, 4, None) == B.ERR_ALIGN
+    assert g(4, 256, 64, 16, fake, fake, fake, fake, 0, None) == B.ERR_CAPACITY
+    assert L.cocodiff_vmajor_scatter(4, 250, 64, 16, fake, fake, fake, fake, 4, None) == B.ERR_SHAPE
+    s = cd.Shape.make(256, 256, 4, 64, 3)
+    assert L.cocodiff_a2a_pack_hs(ctypes.byref(s), fake, fake, 0, None) == B.ERR_SHAPE
+    s = cd.Shape.make(256, 256, 4, 64, 2)
+    assert L.cocodiff_a2a_unpack_seq(ctypes.byref(s), fake, None, 0, None) == B.ERR_NULL
+    assert L.cocodiff_a2a_pack_hs(ctypes.byref(s), fake, fake, 5, None) == B.ERR_SHAPE
