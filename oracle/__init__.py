@@ -18,12 +18,16 @@ from .ref import (  # noqa: F401
     a2a_pack_hs,
     a2a_unpack,
     a2a_unpack_seq,
+    active_count,
     build_c,
+    cache_ratio,
     qk_norm_rope,
     qkv_proj,
     rms_norm,
     rope_rotate,
     token_coords,
+    token_l1_metric,
+    topk_active,
     vmajor_gather,
     vmajor_scatter,
     vmajor_select,

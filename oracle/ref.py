@@ -245,3 +245,41 @@ def a2a_unpack_seq(xbuf: np.ndarray, N: int, H: int, d: int, P: int, slot_order:
         out = np.zeros((N, H, d), dtype=np.uint16)
     _c().oracle_a2a_unpack_seq(_u16(xbuf), _u16(out), N, H, d, P, rank_begin, rank_count, slot_order)
     return out
+
+
+# ---------------------------------------------------------------------------
+# V-Major selection as the paper states it (Section III-D): per-token L1 distance to the cached value
+# vector, the fraction r with the smallest distance stays cached, the rest is active; r follows the
+# time-varying schedule (warm-up, linear ramp, periodic full update).
+# ---------------------------------------------------------------------------
+
+def token_l1_metric(v_cur: np.ndarray, v_prev: np.ndarray) -> np.ndarray:
+    """metric[n] = sum over the token's whole value vector (all slabs s, all w) of |v_cur - v_prev|, in fp64."""
+    assert v_cur.shape == v_prev.shape
+    return np.abs(widen(v_cur) - widen(v_prev)).sum(axis=(0, 2))
+
+
+def topk_active(metric: np.ndarray, n_active: int) -> np.ndarray:
+    """Ascending indices of the n_active tokens with the largest metric; NaN ranks above every number;
+    among equal metrics the lower index is taken first."""
+    metric = np.asarray(metric)
+    n = metric.shape[0]
+    n_active = max(0, min(int(n_active), n))
+    is_nan = np.isnan(metric)
+    value = np.where(is_nan, 0.0, metric)
+    order = np.lexsort((np.arange(n), -value, ~is_nan))     # NaN first, then larger metric, then lower index
+    return np.sort(order[:n_active]).astype(np.int32)
+
+
+def cache_ratio(step: int, n_steps: int, warmup: int, sync_every: int) -> float:
+    """Cache ratio r of denoising step `step` (1-based, 1..n_steps): 0 during the warm-up steps and on every
+    sync_every-th step (full update); otherwise linear from 0 at the warm-up boundary to 1 at the last step."""
+    if step <= warmup or (sync_every > 0 and step % sync_every == 0) or n_steps <= warmup:
+        return 0.0
+    return (step - warmup) / float(n_steps - warmup)
+
+
+def active_count(step: int, n_steps: int, warmup: int, sync_every: int, n_tokens: int) -> int:
+    """Tokens communicated at this step: all but the floor(r * n_tokens) that stay cached."""
+    r = cache_ratio(step, n_steps, warmup, sync_every)
+    return n_tokens - int(np.floor(r * n_tokens + 1e-9))

@@ -544,3 +544,68 @@ def test_second_all_to_all_chunk_contents_brute_force(oracle):
     assert not out[:Ns].any()
     oracle.a2a_unpack_seq(whole, N, H, d, P, 1, rank_begin=0, rank_count=1, out=out)
     assert np.array_equal(out, y.transpose(1, 0, 2))
+
+
+# ---------------------------------------------------------------------------
+# the paper's own selection rule: per-token L1 distance, top (1 - r) fraction, cache schedule
+# ---------------------------------------------------------------------------
+
+def test_token_l1_metric_brute_force_and_closed_form(oracle):
+    rng = np.random.default_rng(31)
+    S, N, W = 3, 10, 8
+    cur = _rand_bits(rng, (S, N, W))
+    prev = _rand_bits(rng, (S, N, W))
+    m = oracle.token_l1_metric(cur, prev)
+    cf, pf = bf16_bits_to_f32(cur).astype(np.float64), bf16_bits_to_f32(prev).astype(np.float64)
+    for n in range(N):
+        acc = 0.0
+        for s in range(S):
+            for w in range(W):
+                acc += abs(cf[s, n, w] - pf[s, n, w])
+        assert abs(m[n] - acc) < 1e-12
+    # closed form: every element of token 4 moved by exactly 0.5 -> S*W*0.5; untouched tokens -> 0
+    prev2 = cur.copy()
+    prev2[:, 4, :] = f32_to_bf16_bits(bf16_bits_to_f32(np.ascontiguousarray(cur[:, 4, :])) * 0 + 0.5)
+    cur2 = cur.copy()
+    cur2[:, 4, :] = f32_to_bf16_bits(np.ones((S, W), dtype=np.float32))
+    m2 = oracle.token_l1_metric(cur2, prev2)
+    assert m2[4] == S * W * 0.5 and np.count_nonzero(m2) == 1
+    # layout independence: the same values as one slab [1][N][S*W]
+    cs = np.ascontiguousarray(cur.transpose(1, 0, 2)).reshape(1, N, S * W)
+    ps = np.ascontiguousarray(prev.transpose(1, 0, 2)).reshape(1, N, S * W)
+    assert np.allclose(oracle.token_l1_metric(cs, ps), m, rtol=1e-14)
+
+
+def test_topk_active_rules(oracle):
+    m = np.array([0.5, 3.0, 3.0, 0.0, 7.0, 3.0, 1.0])
+    assert oracle.topk_active(m, 0).tolist() == []
+    assert oracle.topk_active(m, 1).tolist() == [4]
+    assert oracle.topk_active(m, 2).tolist() == [1, 4]          # tie at 3.0: lower index first
+    assert oracle.topk_active(m, 3).tolist() == [1, 2, 4]
+    assert oracle.topk_active(m, 4).tolist() == [1, 2, 4, 5]
+    assert oracle.topk_active(m, 7).tolist() == list(range(7))
+    assert oracle.topk_active(m, 99).tolist() == list(range(7))
+    mn = np.array([1.0, np.nan, np.inf, 2.0])
+    assert oracle.topk_active(mn, 1).tolist() == [1]            # NaN counts as the largest change
+    assert oracle.topk_active(mn, 2).tolist() == [1, 2]
+    # brute force on random data with many ties
+    rng = np.random.default_rng(32)
+    m = rng.integers(0, 5, size=200).astype(np.float64)
+    for k in (0, 1, 17, 100, 199, 200):
+        pairs = sorted(((-m[i], i) for i in range(200)))[:k]
+        assert oracle.topk_active(m, k).tolist() == sorted(i for _, i in pairs)
+
+
+def test_cache_schedule_matches_the_papers_setup(oracle):
+    # evaluation setup: 50 denoising steps, 5 warm-up steps, full update every 10 steps
+    T, warm, sync = 50, 5, 10
+    r = [oracle.cache_ratio(t, T, warm, sync) for t in range(1, T + 1)]
+    assert all(x == 0.0 for x in r[:5])                        # warm-up: full exchange
+    assert all(r[t - 1] == 0.0 for t in (10, 20, 30, 40, 50))  # periodic full update
+    assert r[5] == pytest.approx(1 / 45) and r[48] == pytest.approx(44 / 45)   # linear from 0 towards 1
+    body = [r[t - 1] for t in range(6, 50) if t % 10]
+    assert all(b > a for a, b in zip(body, body[1:]))
+    assert oracle.active_count(3, T, warm, sync, 9216) == 9216
+    assert oracle.active_count(20, T, warm, sync, 9216) == 9216
+    assert oracle.active_count(49, T, warm, sync, 9216) == 9216 - (9216 * 44) // 45
+    assert oracle.active_count(28, T, warm, sync, 900) == 900 - int(900 * 23 / 45)
