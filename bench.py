@@ -268,6 +268,12 @@ def main() -> int:
         add("a2a_pack_hs", timed(lambda: cd.a2a_pack_hs(sh, hv, bv, ORDER)), nbytes=2 * tensor_bytes)
         add("a2a_unpack_seq", timed(lambda: cd.a2a_unpack_seq(sh, bv, v, ORDER)), nbytes=2 * tensor_bytes)
         del act
+        metric = torch.empty(N, dtype=torch.float32, device=dev)
+        tok_idx = torch.empty(N, dtype=torch.int32, device=dev)
+        tok_n = torch.zeros(1, dtype=torch.int32, device=dev)
+        add("vmajor_token_metric", timed(lambda: cd.vmajor_token_metric(H, N, d, hv, hv_prev, metric)), nbytes=2 * tensor_bytes)
+        k_act = cd.cache_active_count(27, 50, 5, 10, N)      # mid-schedule step of the paper's 50-step setup
+        add("vmajor_topk", timed(lambda: cd.vmajor_topk(N, metric, k_act, tok_idx, tok_n)))
         add("copy_same_bytes", timed(lambda: cd.util_copy(v, bv, tensor_bytes)), nbytes=2 * tensor_bytes)
         big = 1000 << 20   # not a power of two: source and destination must not alias onto the same HBM banks
         src_big = torch.empty(big + (3 << 20), dtype=torch.uint8, device=dev)

@@ -177,6 +177,34 @@ COCODIFF_API int cocodiff_vmajor_scatter(int32_t S, int32_t N, int32_t W, int32_
                                          int32_t cap_tiles, void* stream);
 
 /*
+ * V-Major selection as the paper states it (Section III-D), step 1: one scalar per token,
+ * metric[n] = sum over the token's whole value vector (all slabs s, all w) of |v_cur - v_prev|, the L1 distance
+ * to the cached value vector, accumulated in fp32.  v_cur, v_prev [S][N][W] bf16; metric [N] fp32 (device).
+ * Rules: S, N, W > 0, W % 8 == 0.
+ */
+COCODIFF_API int cocodiff_vmajor_token_metric(int32_t S, int32_t N, int32_t W, const cocodiff_bf16* v_cur,
+                                              const cocodiff_bf16* v_prev, float* metric, void* stream);
+
+/*
+ * Step 2: the n_keep tokens with the largest metric are active (the others stay cached).  NaN ranks above every
+ * number; among equal metrics the lower token index is taken first, so the answer is unique.
+ * active_idx [N] int32 receives the active token ids in ascending order, *n_active = n_keep (both DEVICE, in the
+ * form cocodiff_vmajor_gather / _scatter take with tile_tokens = 1).  Rules: N > 0, 0 <= n_keep <= N.
+ */
+COCODIFF_API int cocodiff_vmajor_topk(int32_t N, const float* metric, int32_t n_keep, int32_t* active_idx,
+                                      int32_t* n_active, void* stream);
+
+/*
+ * Time-varying cache schedule (Section III-D), host arithmetic: number of active tokens at denoising step `step`
+ * (1-based, 1..n_steps).  Steps up to `warmup` and every sync_every-th step exchange everything (n_tokens);
+ * otherwise the cache ratio r rises linearly from 0 at the warm-up boundary to 1 at the last step and
+ * floor(r * n_tokens) tokens stay cached.  sync_every <= 0 disables the periodic full update.  Returns -1 on
+ * bad arguments.  The paper's setup is n_steps = 50, warmup = 5, sync_every = 10.
+ */
+COCODIFF_API int32_t cocodiff_cache_active_count(int32_t step, int32_t n_steps, int32_t warmup, int32_t sync_every,
+                                                 int32_t n_tokens);
+
+/*
  * Second all-to-all (Section II-A: after attention, head-parallel back to sequence-parallel), sender side.
  * y_hs [H][N][d] -> xbuf, P*P chunks of [N/P][H/P][d]:
  *   chunk(p->r)[n][hl][i] = y_hs[p*H/P + hl][r*N/P + n][i]   for SOURCE ranks p (head owners) in the range.

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     a2a_pack_hs,
     a2a_unpack,
     a2a_unpack_seq,
+    cache_active_count,
     qk_norm_rope,
     qkv_proj,
     rope_table,
@@ -22,5 +23,7 @@ from .binding import (  # noqa: F401
     vmajor_gather,
     vmajor_scatter,
     vmajor_select,
+    vmajor_token_metric,
+    vmajor_topk,
     vmajor_select_workspace_bytes,
 )

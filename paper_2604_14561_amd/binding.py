@@ -22,7 +22,8 @@ SEND_MAJOR, RECV_MAJOR = 0, 1
 EXPORTS = (
     "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
-    "cocodiff_vmajor_scatter", "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
+    "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
+    "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
     "cocodiff_rope_table_fill", "cocodiff_util_copy", "cocodiff_version", "cocodiff_last_error",
 )
 
@@ -75,6 +76,10 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_vmajor_select.argtypes = [i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, i32, vp, sz, vp]
         L.cocodiff_vmajor_gather.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
         L.cocodiff_vmajor_scatter.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+        L.cocodiff_vmajor_token_metric.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+        L.cocodiff_vmajor_topk.argtypes = [i32, vp, i32, vp, vp, vp]
+        L.cocodiff_cache_active_count.argtypes = [i32, i32, i32, i32, i32]
+        L.cocodiff_cache_active_count.restype = i32
         L.cocodiff_a2a_pack_hs.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_a2a_unpack_seq.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_vmajor_select_workspace_bytes.argtypes = [i32, i32, i32, i32]
@@ -87,6 +92,7 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_last_error.restype = ctypes.c_char_p
         for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
                      "cocodiff_vmajor_select", "cocodiff_vmajor_gather", "cocodiff_vmajor_scatter",
+                     "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk",
                      "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_fill", "cocodiff_util_copy"):
             getattr(L, name).restype = ci
         _lib = L
@@ -164,6 +170,18 @@ def vmajor_gather(S: int, N: int, W: int, tile_tokens: int, x, active_idx, n_act
 def vmajor_scatter(S: int, N: int, W: int, tile_tokens: int, compact, active_idx, n_active, cache, cap_tiles: int, stream=None) -> None:
     _check(lib().cocodiff_vmajor_scatter(S, N, W, tile_tokens, _ptr(compact), _ptr(active_idx), _ptr(n_active), _ptr(cache),
                                          int(cap_tiles), _stream(stream)))
+
+
+def vmajor_token_metric(S: int, N: int, W: int, v_cur, v_prev, metric, stream=None) -> None:
+    _check(lib().cocodiff_vmajor_token_metric(S, N, W, _ptr(v_cur), _ptr(v_prev), _ptr(metric), _stream(stream)))
+
+
+def vmajor_topk(N: int, metric, n_keep: int, active_idx, n_active, stream=None) -> None:
+    _check(lib().cocodiff_vmajor_topk(N, _ptr(metric), int(n_keep), _ptr(active_idx), _ptr(n_active), _stream(stream)))
+
+
+def cache_active_count(step: int, n_steps: int, warmup: int, sync_every: int, n_tokens: int) -> int:
+    return int(lib().cocodiff_cache_active_count(step, n_steps, warmup, sync_every, n_tokens))
 
 
 def a2a_pack_hs(shape: Shape, y_hs, xbuf, slot_order: int = SEND_MAJOR, stream=None) -> None:

@@ -294,7 +294,10 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     k_step(kt, slot, no{}, yes{}, w1, yes{});
     advance();
     // At the barrier of step kt the loads in flight, oldest first, are X(kt+1), W(kt+1), X(kt+2): the last may stay.
-    for (; kt + 2 < n_k; advance()) k_step(kt, slot, yes{}, yes{}, w1, yes{});
+    while (kt + 2 < n_k) {
+        k_step(kt, slot, yes{}, yes{}, w1, yes{});
+        advance();
+    }
     k_step(kt, slot, no{}, no{}, w0, yes{});     // step n_k-2: the last step must have landed completely
     advance();
     k_step(kt, slot, no{}, no{}, w0, no{});      // step n_k-1

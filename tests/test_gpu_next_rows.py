@@ -149,6 +149,71 @@ def test_gather_scatter_edge_cases(oracle):
     assert np.all(comp[:, T:3 * T] == 0xFFFF)
 
 
+@gpu
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C5"])
+def test_token_metric_and_topk(oracle, name):
+    import torch
+    cfg = CONFIGS[name]
+    print(f"token metric / top-k {name}", flush=True)
+    cur, prev, changed = make_v_pair(cfg, layout="hs")
+    # make the metric non-trivial everywhere: a second, smaller perturbation on every token of some random tiles
+    from synth import perturb_tiles
+    prev, _ = perturb_tiles(prev, 1, 1, cfg.N // 3, np.random.default_rng(cfg.index), sigma=0.01)
+    N = cfg.N
+    metric = torch.empty(N, dtype=torch.float32, device="cuda:0")
+    cd.vmajor_token_metric(cfg.H, N, cfg.d, to_dev(cur), to_dev(prev), metric)
+    _sync()
+    got = metric.cpu().numpy()
+    want = oracle.token_l1_metric(cur, prev)
+    # fp32 accumulation of 3072 non-negative terms against the fp64 sum
+    assert np.all(np.abs(got - want) <= 1e-4 * np.maximum(want, 1e-3)), float(np.max(np.abs(got - want)))
+    # the integer decision is taken on the metric the GPU produced (fp32), on both sides
+    idx, n_act = dev_empty((N,), "i32"), dev_empty((1,), "i32")
+    for step in (3, 6, 20, 27, 49):
+        k = cd.cache_active_count(step, 50, 5, 10, N)
+        assert k == oracle.active_count(step, 50, 5, 10, N)
+        idx.fill_(-1)
+        cd.vmajor_topk(N, metric, k, idx, n_act)
+        _sync()
+        assert int(n_act.cpu()[0]) == k
+        assert np.array_equal(idx.cpu().numpy()[:k], oracle.topk_active(got, k))
+
+
+@gpu
+def test_topk_ties_nan_and_extremes(oracle):
+    import torch
+    rng = np.random.default_rng(44)
+    N = 5000
+    m = rng.integers(0, 6, size=N).astype(np.float32)          # heavy ties
+    m[17] = np.nan
+    m[4000] = np.inf
+    m[3] = -0.0
+    md = torch.from_numpy(m).to("cuda:0")
+    idx, n_act = dev_empty((N,), "i32"), dev_empty((1,), "i32")
+    for k in (0, 1, 2, 3, 777, 2500, N - 1, N):
+        cd.vmajor_topk(N, md, k, idx, n_act)
+        _sync()
+        assert int(n_act.cpu()[0]) == k
+        assert np.array_equal(idx.cpu().numpy()[:k], oracle.topk_active(m.astype(np.float64), k)), k
+    # token-granular gather by the list: tile_tokens = 1
+    S, W = 2, 16
+    x = rng.integers(0, 65536, size=(S, N, W), dtype=np.uint16)
+    k = 123
+    cd.vmajor_topk(N, md, k, idx, n_act)
+    comp = dev_empty((S, k, W))
+    cd.vmajor_gather(S, N, W, 1, to_dev(x), idx, n_act, comp, k)
+    _sync()
+    assert np.array_equal(to_host_bits(comp), x[:, oracle.topk_active(m.astype(np.float64), k), :])
+
+
+def test_cache_schedule_host_arithmetic(oracle):
+    for n_tokens in (9216, 900, 99840, 7):
+        for step in range(1, 51):
+            assert cd.cache_active_count(step, 50, 5, 10, n_tokens) == oracle.active_count(step, 50, 5, 10, n_tokens)
+    assert cd.cache_active_count(0, 50, 5, 10, 100) == -1 and cd.cache_active_count(3, 50, 5, 10, 0) == -1
+    assert cd.cache_active_count(30, 50, 5, 0, 90) == 90 - (90 * 25) // 45     # no periodic update
+
+
 def test_next_rows_argument_errors():
     import ctypes
     from paper_2604_14561_amd import binding as B
@@ -166,3 +231,9 @@ def test_next_rows_argument_errors():
     s = cd.Shape.make(256, 256, 4, 64, 2)
     assert L.cocodiff_a2a_unpack_seq(ctypes.byref(s), fake, None, 0, None) == B.ERR_NULL
     assert L.cocodiff_a2a_pack_hs(ctypes.byref(s), fake, fake, 5, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_token_metric(4, 256, 60, fake, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_token_metric(4, 256, 64, fake, None, fake, None) == B.ERR_NULL
+    assert L.cocodiff_vmajor_token_metric(4, 256, 64, odd, fake, fake, None) == B.ERR_ALIGN
+    assert L.cocodiff_vmajor_topk(256, fake, 257, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(256, fake, -1, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(256, None, 5, fake, fake, None) == B.ERR_NULL
