@@ -208,8 +208,10 @@ def main() -> int:
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(events[i])
+    t_enq = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    log(f"  host enqueue time per step {(t_enq - t0) * 1e3 / args.steps:.3f} ms of {(t1 - t0) * 1e3 / args.steps:.3f} ms")
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = N / (ms_per_step * 1e-3)
 
@@ -219,7 +221,7 @@ def main() -> int:
     gemm_ms_per_launch = float(np.mean([a + b for a, b in gemm_ms])) / n_launch
     flops_per_launch = 2.0 * N * (3 * D) * D / n_launch
     achieved_tflops = flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12
-    roofline = {"kernel": "qkv_gemm_kernel", "bound": "mfma", "achieved": round(achieved_tflops, 2),
+    roofline = {"kernel": "qkv_gemm_direct_kernel", "bound": "mfma", "achieved": round(achieved_tflops, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
                 "traffic": measured_traffic(cfg.name, args.schedule), "avg_launch_us": round(gemm_ms_per_launch * 1e3, 2), "launches_per_step": n_launch}
 
@@ -270,10 +272,10 @@ def main() -> int:
         del act
         metric = torch.empty(N, dtype=torch.float32, device=dev)
         tok_idx = torch.empty(N, dtype=torch.int32, device=dev)
-        tok_n = torch.zeros(1, dtype=torch.int32, device=dev)
+        tok_n = torch.zeros(P, dtype=torch.int32, device=dev)
         add("vmajor_token_metric", timed(lambda: cd.vmajor_token_metric(H, N, d, hv, hv_prev, metric)), nbytes=2 * tensor_bytes)
-        k_act = cd.cache_active_count(27, 50, 5, 10, N)      # mid-schedule step of the paper's 50-step setup
-        add("vmajor_topk", timed(lambda: cd.vmajor_topk(N, metric, k_act, tok_idx, tok_n)))
+        k_act = cd.cache_active_count(27, 50, 5, 10, N // P)  # mid-schedule step of the paper's 50-step setup
+        add("vmajor_topk", timed(lambda: cd.vmajor_topk(P, N // P, metric, k_act, tok_idx, tok_n)))  # every rank ranks its own tokens
         add("copy_same_bytes", timed(lambda: cd.util_copy(v, bv, tensor_bytes)), nbytes=2 * tensor_bytes)
         big = 1000 << 20   # not a power of two: source and destination must not alias onto the same HBM banks
         src_big = torch.empty(big + (3 << 20), dtype=torch.uint8, device=dev)

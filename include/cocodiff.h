@@ -186,12 +186,15 @@ COCODIFF_API int cocodiff_vmajor_token_metric(int32_t S, int32_t N, int32_t W, c
                                               const cocodiff_bf16* v_prev, float* metric, void* stream);
 
 /*
- * Step 2: the n_keep tokens with the largest metric are active (the others stay cached).  NaN ranks above every
- * number; among equal metrics the lower token index is taken first, so the answer is unique.
- * active_idx [N] int32 receives the active token ids in ascending order, *n_active = n_keep (both DEVICE, in the
- * form cocodiff_vmajor_gather / _scatter take with tile_tokens = 1).  Rules: N > 0, 0 <= n_keep <= N.
+ * Step 2, for n_seg independent segments of N tokens each (one per logical rank: a rank ranks its own tokens):
+ * in every segment the n_keep tokens with the largest metric are active (the others stay cached).  NaN ranks
+ * above every number; among equal metrics the lower token index is taken first, so the answer is unique.
+ * metric [n_seg][N] fp32; active_idx [n_seg][N] int32: the first n_keep entries of row g receive segment g's
+ * active token ids (local to the segment, ascending), the rest of the row is left alone; n_active [n_seg], every
+ * entry = n_keep (all DEVICE; row g is in the form cocodiff_vmajor_gather / _scatter take with tile_tokens = 1).
+ * Rules: n_seg, N > 0, n_seg * N < 2^31, 0 <= n_keep <= N.
  */
-COCODIFF_API int cocodiff_vmajor_topk(int32_t N, const float* metric, int32_t n_keep, int32_t* active_idx,
+COCODIFF_API int cocodiff_vmajor_topk(int32_t n_seg, int32_t N, const float* metric, int32_t n_keep, int32_t* active_idx,
                                       int32_t* n_active, void* stream);
 
 /*

@@ -129,7 +129,9 @@ __global__ void __launch_bounds__(kSelThreads) tile_move_kernel(vec16* __restric
     const uint32_t t = (uint32_t)idx[j];
     if (t >= sh.NT) return;
     const uint32_t total = sh.S * sh.seg8;
-    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * kSelThreads) {
+    // blockIdx.y strides over the tile's vectors in pieces of kSelUnroll * kSelThreads, so that a short list
+    // still spreads over the whole chip
+    for (uint32_t g0 = blockIdx.y * (kSelUnroll * kSelThreads) + threadIdx.x; g0 < total; g0 += gridDim.y * (kSelUnroll * kSelThreads)) {
         vec16 c[kSelUnroll];
         uint64_t dst[kSelUnroll];
 #pragma unroll
@@ -215,11 +217,13 @@ static int tile_move(bool gather, int32_t S, int32_t N, int32_t W, int32_t tile_
     if (!aligned16(x) || !aligned16(compact)) return fail(COCODIFF_ERR_ALIGN, "%s: tensors must be 16-byte aligned", who);
     if (cap_tiles < 1) return fail(COCODIFF_ERR_CAPACITY, "%s: cap_tiles (%d) must be >= 1", who, cap_tiles);
     const uint32_t blocks = (uint32_t)cap_tiles < sh.NT ? (uint32_t)cap_tiles : sh.NT;
+    const uint32_t pieces = (sh.S * sh.seg8 + kSelUnroll * kSelThreads - 1) / (kSelUnroll * kSelThreads);
+    const dim3 grid(blocks, pieces < 64 ? pieces : 64);
     if (gather)
-        hipLaunchKernelGGL(tile_move_kernel<true>, dim3(blocks), dim3(kSelThreads), 0, as_stream(stream), (vec16*)x,
+        hipLaunchKernelGGL(tile_move_kernel<true>, grid, dim3(kSelThreads), 0, as_stream(stream), (vec16*)x,
                            (vec16*)compact, active_idx, n_active, sh, (uint32_t)cap_tiles);
     else
-        hipLaunchKernelGGL(tile_move_kernel<false>, dim3(blocks), dim3(kSelThreads), 0, as_stream(stream), (vec16*)x,
+        hipLaunchKernelGGL(tile_move_kernel<false>, grid, dim3(kSelThreads), 0, as_stream(stream), (vec16*)x,
                            (vec16*)compact, active_idx, n_active, sh, (uint32_t)cap_tiles);
     return check_launch(who);
 }

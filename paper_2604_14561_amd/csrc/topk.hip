@@ -4,9 +4,10 @@
 //
 //   token_metric_kernel -- one wavefront per token streams the token's value vector from both tensors once
 //                          (HBM-bound), fp32 sum of |cur - prev| per lane, wavefront tree reduction;
-//   topk_kernel         -- one workgroup: 4-pass radix select (8 bits per pass, LDS histogram) of the K-th
-//                          largest key, then an index-ordered compaction that takes every token above the
-//                          threshold and the lowest-indexed tokens equal to it until K are taken.
+//   topk_kernel         -- one workgroup per segment (a logical rank's tokens), keys cached in LDS: 4-pass radix
+//                          select (8 bits per pass, LDS histogram) of the K-th largest key, then an
+//                          index-ordered compaction that takes every token above the threshold and the
+//                          lowest-indexed tokens equal to it until K are taken.
 #include "internal.h"
 
 namespace cocodiff {
@@ -61,14 +62,19 @@ __device__ __forceinline__ uint32_t metric_key(float m) {
 }
 
 constexpr int kTopkThreads = 1024;
+constexpr uint32_t kTopkCachedKeys = 32768;   // keys of one segment kept in LDS (128 KB) when they fit
 
-// Exclusive prefix count of `flag` over the workgroup; `total` gets the workgroup's count.
-__device__ __forceinline__ uint32_t block_prefix(bool flag, uint32_t* wave_tot, uint32_t& total) {
+// Exclusive prefix sum of `v` over the workgroup in thread order; `total` gets the workgroup's sum.
+__device__ __forceinline__ uint32_t block_scan(uint32_t v, uint32_t* wave_tot, uint32_t& total) {
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint64_t ball = __ballot(flag);
-    const uint32_t below = __popcll(ball & ((1ull << lane) - 1ull));
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off, 64);
+        if (lane >= (uint32_t)off) incl += up;
+    }
     __syncthreads();                               // wave_tot may still be read from the previous call
-    if (lane == 0) wave_tot[wave] = __popcll(ball);
+    if (lane == 63) wave_tot[wave] = incl;
     __syncthreads();
     uint32_t before = 0, tot = 0;
 #pragma unroll
@@ -78,35 +84,44 @@ __device__ __forceinline__ uint32_t block_prefix(bool flag, uint32_t* wave_tot, 
         tot += c;
     }
     total = tot;
-    return before + below;
+    return before + incl - v;
 }
 
+// One workgroup per segment (a logical rank's tokens).  CACHED: the segment's keys sit in LDS after one read of
+// the metric; otherwise every pass reads the metric again (L2-resident).
+template <bool CACHED>
 __global__ void __launch_bounds__(kTopkThreads) topk_kernel(const float* __restrict__ metric, uint32_t N, uint32_t K,
                                                             int32_t* __restrict__ idx, int32_t* __restrict__ n_active) {
+    extern __shared__ uint32_t s_keys[];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_tot[kTopkThreads / 64];
     __shared__ uint32_t s_prefix, s_remaining;
-    if (threadIdx.x == 0) *n_active = (int32_t)K;
+    metric += (size_t)blockIdx.x * N;
+    idx += (size_t)blockIdx.x * N;
+    if (threadIdx.x == 0) n_active[blockIdx.x] = (int32_t)K;
     if (K == 0) return;
+    if (CACHED) {
+        for (uint32_t n = threadIdx.x; n < N; n += kTopkThreads) s_keys[n] = metric_key(metric[n]);
+        __syncthreads();
+    }
+    auto key_at = [&](uint32_t n) { return CACHED ? s_keys[n] : metric_key(metric[n]); };
     // ---- the K-th largest key, one byte per pass from the top
     uint32_t prefix = 0, mask = 0, remaining = K;
     for (int pass = 3; pass >= 0; --pass) {
         if (threadIdx.x < 256) hist[threadIdx.x] = 0;
         __syncthreads();
         for (uint32_t n = threadIdx.x; n < N; n += kTopkThreads) {
-            const uint32_t key = metric_key(metric[n]);
+            const uint32_t key = key_at(n);
             if ((key & mask) == prefix) atomicAdd(&hist[(key >> (8 * pass)) & 255u], 1u);
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t cum = 0;
-            int b = 255;
-            for (; b > 0; --b) {
-                if (cum + hist[b] >= remaining) break;
-                cum += hist[b];
-            }
-            s_prefix = prefix | ((uint32_t)b << (8 * pass));
-            s_remaining = remaining - cum;         // how many keys of this bin (and, at the end, of this value) to take
+        // bin of the `remaining`-th largest key: thread t looks at bin 255 - t; `above` = keys in higher bins
+        const uint32_t mine = threadIdx.x < 256 ? hist[255 - threadIdx.x] : 0u;
+        uint32_t in_play;
+        const uint32_t above = block_scan(mine, wave_tot, in_play);
+        if (above < remaining && above + mine >= remaining) {      // exactly one thread: 1 <= remaining <= in_play
+            s_prefix = prefix | ((255u - threadIdx.x) << (8 * pass));
+            s_remaining = remaining - above;       // how many keys of this bin (and, at the end, of this value) to take
         }
         __syncthreads();
         prefix = s_prefix;
@@ -115,20 +130,26 @@ __global__ void __launch_bounds__(kTopkThreads) topk_kernel(const float* __restr
         __syncthreads();
     }
     const uint32_t thr = prefix;                   // key of the K-th largest; `remaining` tokens equal to it are taken
-    // ---- compaction in index order
-    uint32_t out_before = 0, eq_before = 0;
-    for (uint32_t base = 0; base < N; base += kTopkThreads) {
-        const uint32_t n = base + threadIdx.x;
-        const uint32_t key = n < N ? metric_key(metric[n]) : 0u;
-        const bool gt = n < N && key > thr;
-        const bool eq = n < N && key == thr;
-        uint32_t eq_total, take_total;
-        const uint32_t eq_rank = eq_before + block_prefix(eq, wave_tot, eq_total);
-        const bool take = gt || (eq && eq_rank < remaining);
-        const uint32_t pos = out_before + block_prefix(take, wave_tot, take_total);
-        if (take) idx[pos] = (int32_t)n;
-        eq_before += eq_total;
-        out_before += take_total;
+    // ---- compaction in index order: thread t owns the contiguous run [t*per, (t+1)*per)
+    const uint32_t per = (N + kTopkThreads - 1) / kTopkThreads;
+    const uint32_t lo = threadIdx.x * per < N ? threadIdx.x * per : N;
+    const uint32_t hi = lo + per < N ? lo + per : N;
+    uint32_t n_gt = 0, n_eq = 0;
+    for (uint32_t n = lo; n < hi; ++n) {
+        const uint32_t key = key_at(n);
+        n_gt += key > thr;
+        n_eq += key == thr;
+    }
+    uint32_t eq_total, take_total;
+    uint32_t eq_rank = block_scan(n_eq, wave_tot, eq_total);          // equal keys before this run
+    const uint32_t eq_room = eq_rank < remaining ? remaining - eq_rank : 0u;
+    const uint32_t n_take = n_gt + (n_eq < eq_room ? n_eq : eq_room);
+    uint32_t pos = block_scan(n_take, wave_tot, take_total);
+    for (uint32_t n = lo; n < hi; ++n) {
+        const uint32_t key = key_at(n);
+        const bool take = key > thr || (key == thr && eq_rank < remaining);
+        eq_rank += key == thr;
+        if (take) idx[pos++] = (int32_t)n;
     }
 }
 
@@ -153,13 +174,24 @@ extern "C" int cocodiff_vmajor_token_metric(int32_t S, int32_t N, int32_t W, con
     return check_launch("token_metric_kernel");
 }
 
-extern "C" int cocodiff_vmajor_topk(int32_t N, const float* metric, int32_t n_keep, int32_t* active_idx,
+extern "C" int cocodiff_vmajor_topk(int32_t n_seg, int32_t N, const float* metric, int32_t n_keep, int32_t* active_idx,
                                     int32_t* n_active, void* stream) {
-    if (N <= 0) return fail(COCODIFF_ERR_SHAPE, "topk: N must be positive");
+    if (n_seg <= 0 || N <= 0) return fail(COCODIFF_ERR_SHAPE, "topk: n_seg and N must be positive");
+    if ((int64_t)n_seg * N >= ((int64_t)1 << 31)) return fail(COCODIFF_ERR_SHAPE, "topk: n_seg * N must be below 2^31");
     if (n_keep < 0 || n_keep > N) return fail(COCODIFF_ERR_SHAPE, "topk: n_keep (%d) must be in [0, N = %d]", n_keep, N);
     if (!metric || !active_idx || !n_active) return fail(COCODIFF_ERR_NULL, "topk: NULL pointer");
-    hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(kTopkThreads), 0, as_stream(stream), metric, (uint32_t)N,
-                       (uint32_t)n_keep, active_idx, n_active);
+    if ((uint32_t)N <= kTopkCachedKeys) {
+        static int lds_ok = [] {
+            return (int)hipFuncSetAttribute((const void*)topk_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)(kTopkCachedKeys * sizeof(uint32_t)));
+        }();
+        if (lds_ok != (int)hipSuccess) return fail(COCODIFF_ERR_HIP, "topk: cannot raise the kernel's LDS limit");
+        hipLaunchKernelGGL(topk_kernel<true>, dim3(n_seg), dim3(kTopkThreads), (size_t)N * sizeof(uint32_t), as_stream(stream),
+                           metric, (uint32_t)N, (uint32_t)n_keep, active_idx, n_active);
+    } else {
+        hipLaunchKernelGGL(topk_kernel<false>, dim3(n_seg), dim3(kTopkThreads), 0, as_stream(stream), metric, (uint32_t)N,
+                           (uint32_t)n_keep, active_idx, n_active);
+    }
     return check_launch("topk_kernel");
 }
 

@@ -173,10 +173,23 @@ def test_token_metric_and_topk(oracle, name):
         k = cd.cache_active_count(step, 50, 5, 10, N)
         assert k == oracle.active_count(step, 50, 5, 10, N)
         idx.fill_(-1)
-        cd.vmajor_topk(N, metric, k, idx, n_act)
+        cd.vmajor_topk(1, N, metric, k, idx, n_act)
         _sync()
         assert int(n_act.cpu()[0]) == k
         assert np.array_equal(idx.cpu().numpy()[:k], oracle.topk_active(got, k))
+    # one segment per logical rank: each rank ranks its own N/P tokens, ids local to the rank
+    P, Ns = cfg.P, cfg.N // cfg.P
+    n_act = dev_empty((P,), "i32")
+    for step in (6, 27, 50):
+        k = cd.cache_active_count(step, 50, 5, 10, Ns)
+        idx.fill_(-1)
+        cd.vmajor_topk(P, Ns, metric, k, idx, n_act)
+        _sync()
+        assert np.all(n_act.cpu().numpy() == k)
+        rows = idx.cpu().numpy().reshape(P, Ns)
+        for r in range(P):
+            assert np.array_equal(rows[r, :k], oracle.topk_active(got[r * Ns:(r + 1) * Ns], k)), (step, r)
+            assert np.all(rows[r, k:] == -1)
 
 
 @gpu
@@ -191,15 +204,24 @@ def test_topk_ties_nan_and_extremes(oracle):
     md = torch.from_numpy(m).to("cuda:0")
     idx, n_act = dev_empty((N,), "i32"), dev_empty((1,), "i32")
     for k in (0, 1, 2, 3, 777, 2500, N - 1, N):
-        cd.vmajor_topk(N, md, k, idx, n_act)
+        cd.vmajor_topk(1, N, md, k, idx, n_act)
         _sync()
         assert int(n_act.cpu()[0]) == k
         assert np.array_equal(idx.cpu().numpy()[:k], oracle.topk_active(m.astype(np.float64), k)), k
+    # a segment too long for the LDS key cache: the variant that reads the metric again on every pass
+    NL = 40000
+    ml = rng.integers(0, 1000, size=NL).astype(np.float32) * 0.25
+    mld = torch.from_numpy(ml).to("cuda:0")
+    idx_l, n_l = dev_empty((NL,), "i32"), dev_empty((1,), "i32")
+    for k in (1, 9999, NL - 1, NL):
+        cd.vmajor_topk(1, NL, mld, k, idx_l, n_l)
+        _sync()
+        assert np.array_equal(idx_l.cpu().numpy()[:k], oracle.topk_active(ml.astype(np.float64), k)), k
     # token-granular gather by the list: tile_tokens = 1
     S, W = 2, 16
     x = rng.integers(0, 65536, size=(S, N, W), dtype=np.uint16)
     k = 123
-    cd.vmajor_topk(N, md, k, idx, n_act)
+    cd.vmajor_topk(1, N, md, k, idx, n_act)
     comp = dev_empty((S, k, W))
     cd.vmajor_gather(S, N, W, 1, to_dev(x), idx, n_act, comp, k)
     _sync()
@@ -234,6 +256,8 @@ def test_next_rows_argument_errors():
     assert L.cocodiff_vmajor_token_metric(4, 256, 60, fake, fake, fake, None) == B.ERR_SHAPE
     assert L.cocodiff_vmajor_token_metric(4, 256, 64, fake, None, fake, None) == B.ERR_NULL
     assert L.cocodiff_vmajor_token_metric(4, 256, 64, odd, fake, fake, None) == B.ERR_ALIGN
-    assert L.cocodiff_vmajor_topk(256, fake, 257, fake, fake, None) == B.ERR_SHAPE
-    assert L.cocodiff_vmajor_topk(256, fake, -1, fake, fake, None) == B.ERR_SHAPE
-    assert L.cocodiff_vmajor_topk(256, None, 5, fake, fake, None) == B.ERR_NULL
+    assert L.cocodiff_vmajor_topk(1, 256, fake, 257, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(1, 256, fake, -1, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(0, 256, fake, 5, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(1 << 16, 1 << 16, fake, 5, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(1, 256, None, 5, fake, fake, None) == B.ERR_NULL
