@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     qkv_proj,
     rope_table,
     util_copy,
+    util_mfma_rate,
     version,
     vmajor_gather,
     vmajor_scatter,

@@ -24,7 +24,7 @@ EXPORTS = (
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
     "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
-    "cocodiff_rope_table_fill", "cocodiff_util_copy", "cocodiff_version", "cocodiff_last_error",
+    "cocodiff_rope_table_fill", "cocodiff_util_copy", "cocodiff_util_mfma_rate", "cocodiff_version", "cocodiff_last_error",
 )
 
 
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_util_copy.argtypes = [vp, vp, sz, vp]
         L.cocodiff_version.restype = ctypes.c_char_p
         L.cocodiff_last_error.restype = ctypes.c_char_p
+        L.cocodiff_util_mfma_rate.argtypes = [i32, i32, vp, vp]
+        L.cocodiff_util_mfma_rate.restype = ctypes.c_int64
         for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
                      "cocodiff_vmajor_select", "cocodiff_vmajor_gather", "cocodiff_vmajor_scatter",
                      "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk",
@@ -205,3 +207,11 @@ def rope_table(grid: Sequence[int], pairs: Sequence[int], theta: float) -> np.nd
 
 def util_copy(src, dst, nbytes: int, stream=None) -> None:
     _check(lib().cocodiff_util_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)))
+
+
+def util_mfma_rate(blocks: int, iters: int, sink, stream=None) -> int:
+    """Launch the register-only matrix-core loop; returns the launch's floating-point operation count."""
+    flops = int(lib().cocodiff_util_mfma_rate(int(blocks), int(iters), _ptr(sink), _stream(stream)))
+    if flops < 0:
+        _check(flops)
+    return flops

@@ -52,17 +52,45 @@ static int check_rope_desc(const cocodiff_rope* r) {
     return COCODIFF_OK;
 }
 
-// Each workgroup copies 1024 consecutive 16-byte vectors, four per lane, loads before stores.
-template <bool STREAM>
+// One 16-byte vector per thread: small workgroups measured fastest on data that is not in the last-level cache.
+template <bool NT_LD, bool NT_ST>
 __global__ void __launch_bounds__(256) copy_kernel(const vec16* __restrict__ src, vec16* __restrict__ dst, size_t n_vec) {
-    const size_t base = (size_t)blockIdx.x * 1024 + threadIdx.x;
-    vec16 v[4];
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n_vec) st_vec<NT_ST>(dst + i, ld_vec<NT_LD>(src + i));
+}
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 mfma_in_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float mfma_acc_t;
+
+constexpr int kMfmaChains = 8;   // independent accumulators per wavefront: hides the matrix core's result latency
+
+// Register-only loop of v_mfma_f32_32x32x16_bf16: no memory traffic, operands are small pseudo-random bf16 values
+// that differ per lane (constant operands draw less power and clock higher than real data does).
+__global__ void __launch_bounds__(256) mfma_rate_kernel(uint32_t iters, float* __restrict__ sink) {
+    uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+    union { uint16_t u[8]; mfma_in_t v; } a, b;
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-        if (base + k * 256 < n_vec) v[k] = ld_vec<STREAM>(src + base + k * 256);
+    for (int i = 0; i < 8; ++i) {
+        h = h * 1664525u + 1013904223u;
+        a.u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));      // bf16 of magnitude 2^-7 .. 2, either sign
+        h = h * 1664525u + 1013904223u;
+        b.u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));
+    }
+    mfma_acc_t acc[kMfmaChains];
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
-        if (base + k * 256 < n_vec) st_vec<STREAM>(dst + base + k * 256, v[k]);
+    for (int c = 0; c < kMfmaChains; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+    for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int c = 0; c < kMfmaChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc[c], 0, 0, 0);
+    }
+    float total = 0.f;
+#pragma unroll
+    for (int c = 0; c < kMfmaChains; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) total += acc[c][e];
+    if (total == 123.456f) sink[0] = total;   // keeps the loop alive; practically never true
 }
 
 }  // namespace cocodiff
@@ -106,13 +134,22 @@ int cocodiff_util_copy(const void* src, void* dst, size_t bytes, void* stream) {
     if (bytes % 16) return fail(COCODIFF_ERR_SHAPE, "copy: bytes (%zu) must be a multiple of 16", bytes);
     if (bytes == 0) return COCODIFF_OK;
     const size_t n_vec = bytes / 16;
-    const size_t blocks = (n_vec + 1023) / 1024;
+    const size_t blocks = (n_vec + 255) / 256;
     if (blocks >= ((size_t)1 << 31)) return fail(COCODIFF_ERR_SHAPE, "copy: %zu bytes is too much for one launch", bytes);
-    if (should_stream(2 * bytes))
-        hipLaunchKernelGGL(copy_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), (const vec16*)src, (vec16*)dst, n_vec);
-    else
-        hipLaunchKernelGGL(copy_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), (const vec16*)src, (vec16*)dst, n_vec);
+    with_policy(stream_loads(2 * bytes), stream_stores(2 * bytes), [&](auto L, auto S) {
+        hipLaunchKernelGGL((copy_kernel<decltype(L)::value, decltype(S)::value>), dim3((unsigned)blocks), dim3(256), 0,
+                           as_stream(stream), (const vec16*)src, (vec16*)dst, n_vec);
+    });
     return check_launch("copy_kernel");
+}
+
+int64_t cocodiff_util_mfma_rate(int32_t blocks, int32_t iters, float* sink, void* stream) {
+    if (blocks <= 0 || iters <= 0) return fail(COCODIFF_ERR_SHAPE, "mfma_rate: blocks and iters must be positive");
+    if (!sink) return fail(COCODIFF_ERR_NULL, "mfma_rate: NULL sink");
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), (uint32_t)iters, sink);
+    const int rc = check_launch("mfma_rate_kernel");
+    if (rc != COCODIFF_OK) return rc;
+    return (int64_t)blocks * 4 * iters * kMfmaChains * (2LL * 32 * 32 * 16);
 }
 
 }  // extern "C"

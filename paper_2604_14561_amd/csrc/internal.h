@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <cstdlib>
+#include <type_traits>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -22,10 +24,43 @@ int check_launch(const char* what);
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
-// HBM-bound kernels stream (non-temporal hints) once the bytes they touch are several times the 256 MB
-// last-level cache; below that, cached accesses measured faster and let a consumer kernel find its
-// producer's output on chip.
-inline bool should_stream(size_t bytes_touched) { return bytes_touched > ((size_t)768 << 20); }
+// Cache policy of the HBM-bound kernels, from measurements on data that is not in the 256 MB last-level cache
+// (rotating buffer sets) and on data that is:
+//   * stores are non-temporal: nothing of the output stays in L2 to be written back when the kernel ends;
+//   * loads of data that no later kernel reads again (the cached previous-step tensor, a tensor rewritten in
+//     place) are non-temporal;
+//   * other loads are cached while the launch touches less than ~192 MB (a consumer may find its producer's
+//     output on chip) and non-temporal above.
+// COCODIFF_STREAM_LD_MB / _ST_MB / _ONCE_MB in the environment (read once) move the three thresholds: tuning
+// knobs, not part of the interface.
+inline size_t tune_value(const char* name, size_t dflt) {
+    const char* e = getenv(name);
+    return e ? (size_t)strtoull(e, nullptr, 10) : dflt;
+}
+inline bool stream_loads(size_t bytes_touched) {
+    static const size_t threshold = tune_value("COCODIFF_STREAM_LD_MB", 192) << 20;
+    return bytes_touched > threshold;
+}
+inline bool stream_stores(size_t bytes_touched) {
+    static const size_t threshold = tune_value("COCODIFF_STREAM_ST_MB", 0) << 20;
+    return bytes_touched > threshold;
+}
+inline bool stream_loads_once(size_t bytes_touched) {
+    static const size_t threshold = tune_value("COCODIFF_STREAM_ONCE_MB", 0) << 20;
+    return bytes_touched > threshold;
+}
+
+// Calls f(std::bool_constant<nt_ld>{}, std::bool_constant<nt_st>{}): run-time policy -> template arguments.
+template <typename F>
+inline void with_policy(bool nt_ld, bool nt_st, F&& f) {
+    if (nt_ld) {
+        if (nt_st) f(std::true_type{}, std::true_type{});
+        else f(std::true_type{}, std::false_type{});
+    } else {
+        if (nt_st) f(std::false_type{}, std::true_type{});
+        else f(std::false_type{}, std::false_type{});
+    }
+}
 
 // ---- device helpers -------------------------------------------------------
 

@@ -46,7 +46,7 @@ __device__ __forceinline__ float group_sum(float v, uint32_t width) {
 
 constexpr int kMaxSteps = 8;
 
-template <int STEPS, bool STREAM>   // STEPS 0 = any number of steps, taken kMaxSteps at a time
+template <int STEPS, bool NT_LD, bool NT_ST>   // STEPS 0 = any number of steps, taken kMaxSteps at a time
 __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t run = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -104,7 +104,7 @@ __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
         vec16 in[UN];
 #pragma unroll
         for (int k = 0; k < UN; ++k)
-            if (STEPS || s0 + k < total_steps) in[k] = ld_vec<STREAM>(row + (size_t)(s0 + k) * 64);
+            if (STEPS || s0 + k < total_steps) in[k] = ld_vec<NT_LD>(row + (size_t)(s0 + k) * 64);
 #pragma unroll
         for (int k = 0; k < UN; ++k) {
             if (!(STEPS || s0 + k < total_steps)) continue;
@@ -126,7 +126,7 @@ __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
                 const float od = x[2 * i + 1] * rinv * g[2 * i + 1];
                 o[i] = pack_bf16x2(e * cs_c[i] - od * cs_s[i], e * cs_s[i] + od * cs_c[i]);
             }
-            st_vec<STREAM>(row + (size_t)(s0 + k) * 64, vec16{o[0], o[1], o[2], o[3]});
+            st_vec<NT_ST>(row + (size_t)(s0 + k) * 64, vec16{o[0], o[1], o[2], o[3]});
         }
     }
 }
@@ -188,12 +188,12 @@ extern "C" int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf16*
     const uint32_t runs = (a.n_tokens + tokens_per_wave - 1) / tokens_per_wave;
     const dim3 grid((runs + 3) / 4, nt), block(256);
     hipStream_t st = as_stream(stream);
-    const bool stream_it = should_stream((size_t)nt * a.n_tokens * D8 * 32);
-#define COCODIFF_NR_LAUNCH(S)                                                                     \
-    do {                                                                                          \
-        if (stream_it) hipLaunchKernelGGL((norm_rope_kernel<S, true>), grid, block, 0, st, a);    \
-        else hipLaunchKernelGGL((norm_rope_kernel<S, false>), grid, block, 0, st, a);             \
-    } while (0)
+    const size_t touched = (size_t)nt * a.n_tokens * D8 * 32;
+    const bool nt_ld = stream_loads_once(touched), nt_st = stream_stores(touched);   // in place: every element read once
+#define COCODIFF_NR_LAUNCH(S)                                                                                      \
+    with_policy(nt_ld, nt_st, [&](auto L, auto W) {                                                                \
+        hipLaunchKernelGGL((norm_rope_kernel<S, decltype(L)::value, decltype(W)::value>), grid, block, 0, st, a);  \
+    })
     switch (a.steps) {
         case 1: COCODIFF_NR_LAUNCH(1); break;
         case 2: COCODIFF_NR_LAUNCH(2); break;

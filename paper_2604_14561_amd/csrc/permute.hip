@@ -10,7 +10,6 @@
 namespace cocodiff {
 
 constexpr int kThreads = 256;
-constexpr int kVecPerThread = 4;
 
 struct PermuteArgs {
     uint32_t Ns, P, D8, d8, row8, chunk8;
@@ -24,75 +23,49 @@ __device__ __forceinline__ uint32_t slot_of(uint32_t sender, uint32_t receiver, 
     return recv_major ? receiver * P + sender : sender * P + receiver;
 }
 
-// Walks the sequence-parallel tensor [N][H][d] linearly over the token range of the launch.
+// Walks the sequence-parallel tensor [N][H][d] linearly over the token range of the launch, one vector per thread
+// (small workgroups measured fastest on cold data and disturb a concurrent projection least).
 // TO_BUF: x_seq -> exchange buffer (first all-to-all, sender = token owner r, receiver = head owner p);
 // else:   exchange buffer -> x_seq (second all-to-all, sender = head owner p, receiver = token owner r).
-// One thread moves kVecPerThread vectors, kThreads apart, all loads issued before the stores.
-template <bool STREAM, bool TO_BUF>
+template <bool NT_LD, bool NT_ST, bool TO_BUF>
 __global__ void __launch_bounds__(kThreads) seq_side_kernel(const vec16* __restrict__ in, vec16* __restrict__ out, PermuteArgs a) {
-    const uint32_t base = blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
-    vec16 val[kVecPerThread];
-    size_t dst[kVecPerThread];
-#pragma unroll
-    for (int k = 0; k < kVecPerThread; ++k) {
-        const uint32_t g = base + k * kThreads;
-        if (g < a.n_vec) {
-            const uint32_t tl = g / a.D8;            // token within the range
-            const uint32_t v = g - tl * a.D8;        // vector within the token row
-            const uint32_t n = a.first + tl;         // global token
-            const uint32_t r = n / a.Ns;             // token owner
-            const uint32_t m = n - r * a.Ns;         // token within the rank
-            const uint32_t p = v / a.row8;           // head owner
-            const uint32_t c = v - p * a.row8;       // (hl, i) within the chunk row
-            const size_t seq_at = (size_t)n * a.D8 + v;
-            const size_t buf_at = (size_t)(TO_BUF ? slot_of(r, p, a.P, a.recv_major) : slot_of(p, r, a.P, a.recv_major)) * a.chunk8 +
-                                  m * a.row8 + c;
-            val[k] = ld_vec<STREAM>(in + (TO_BUF ? seq_at : buf_at));
-            dst[k] = TO_BUF ? buf_at : seq_at;
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < kVecPerThread; ++k) {
-        const uint32_t g = base + k * kThreads;
-        if (g < a.n_vec) st_vec<STREAM>(out + dst[k], val[k]);
-    }
+    const uint32_t g = blockIdx.x * kThreads + threadIdx.x;
+    if (g >= a.n_vec) return;
+    const uint32_t tl = g / a.D8;            // token within the range
+    const uint32_t v = g - tl * a.D8;        // vector within the token row
+    const uint32_t n = a.first + tl;         // global token
+    const uint32_t r = n / a.Ns;             // token owner
+    const uint32_t m = n - r * a.Ns;         // token within the rank
+    const uint32_t p = v / a.row8;           // head owner
+    const uint32_t c = v - p * a.row8;       // (hl, i) within the chunk row
+    const size_t seq_at = (size_t)n * a.D8 + v;
+    const size_t buf_at = (size_t)(TO_BUF ? slot_of(r, p, a.P, a.recv_major) : slot_of(p, r, a.P, a.recv_major)) * a.chunk8 +
+                          m * a.row8 + c;
+    st_vec<NT_ST>(out + (TO_BUF ? buf_at : seq_at), ld_vec<NT_LD>(in + (TO_BUF ? seq_at : buf_at)));
 }
 
 // Walks the head-parallel tensor [H][N][d] linearly over the head range of the launch.
 // TO_BUF: x_hs -> exchange buffer (second all-to-all, sender = head owner p, receiver = token owner r);
 // else:   exchange buffer -> x_hs (first all-to-all, sender = token owner r, receiver = head owner p).
-template <bool STREAM, bool TO_BUF>
+template <bool NT_LD, bool NT_ST, bool TO_BUF>
 __global__ void __launch_bounds__(kThreads) head_side_kernel(const vec16* __restrict__ in, vec16* __restrict__ out, PermuteArgs a) {
-    const uint32_t base = blockIdx.x * (kThreads * kVecPerThread) + threadIdx.x;
-    const uint32_t head8 = a.N * a.d8;               // vectors per head slab
+    const uint32_t g = blockIdx.x * kThreads + threadIdx.x;
+    if (g >= a.n_vec) return;
+    const uint32_t head8 = a.N * a.d8;       // vectors per head slab
     const uint32_t Hp = a.row8 / a.d8;
-    vec16 val[kVecPerThread];
-    size_t dst[kVecPerThread];
-#pragma unroll
-    for (int k = 0; k < kVecPerThread; ++k) {
-        const uint32_t g = base + k * kThreads;
-        if (g < a.n_vec) {
-            const uint32_t hl_range = g / head8;
-            const uint32_t rem = g - hl_range * head8;
-            const uint32_t h = a.first + hl_range;   // global head
-            const uint32_t n = rem / a.d8;           // global token
-            const uint32_t i8 = rem - n * a.d8;
-            const uint32_t p = h / Hp;               // head owner
-            const uint32_t hl = h - p * Hp;
-            const uint32_t r = n / a.Ns;             // token owner
-            const uint32_t m = n - r * a.Ns;
-            const size_t hs_at = (size_t)a.first * head8 + g;
-            const size_t buf_at = (size_t)(TO_BUF ? slot_of(p, r, a.P, a.recv_major) : slot_of(r, p, a.P, a.recv_major)) * a.chunk8 +
-                                  m * a.row8 + hl * a.d8 + i8;
-            val[k] = ld_vec<STREAM>(in + (TO_BUF ? hs_at : buf_at));
-            dst[k] = TO_BUF ? buf_at : hs_at;
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < kVecPerThread; ++k) {
-        const uint32_t g = base + k * kThreads;
-        if (g < a.n_vec) st_vec<STREAM>(out + dst[k], val[k]);
-    }
+    const uint32_t hl_range = g / head8;
+    const uint32_t rem = g - hl_range * head8;
+    const uint32_t h = a.first + hl_range;   // global head
+    const uint32_t n = rem / a.d8;           // global token
+    const uint32_t i8 = rem - n * a.d8;
+    const uint32_t p = h / Hp;               // head owner
+    const uint32_t hl = h - p * Hp;
+    const uint32_t r = n / a.Ns;             // token owner
+    const uint32_t m = n - r * a.Ns;
+    const size_t hs_at = (size_t)a.first * head8 + g;
+    const size_t buf_at = (size_t)(TO_BUF ? slot_of(p, r, a.P, a.recv_major) : slot_of(r, p, a.P, a.recv_major)) * a.chunk8 +
+                          m * a.row8 + hl * a.d8 + i8;
+    st_vec<NT_ST>(out + (TO_BUF ? buf_at : hs_at), ld_vec<NT_LD>(in + (TO_BUF ? hs_at : buf_at)));
 }
 
 static int check_permute(const cocodiff_shape* s, const void* in, const void* out, int slot_order, const char* who) {
@@ -130,12 +103,11 @@ static int launch_seq_side(const cocodiff_shape* shape, const void* in, void* ou
     PermuteArgs a = make_args(shape, slot_order);
     a.first = shape->rank_begin * a.Ns;
     a.n_vec = (uint32_t)shape->rank_count * a.Ns * a.D8;
-    const uint32_t per_block = kThreads * kVecPerThread;
-    const dim3 grid((a.n_vec + per_block - 1) / per_block), block(kThreads);
-    if (should_stream((size_t)a.n_vec * 32))
-        hipLaunchKernelGGL((seq_side_kernel<true, TO_BUF>), grid, block, 0, as_stream(stream), (const vec16*)in, (vec16*)out, a);
-    else
-        hipLaunchKernelGGL((seq_side_kernel<false, TO_BUF>), grid, block, 0, as_stream(stream), (const vec16*)in, (vec16*)out, a);
+    const dim3 grid((a.n_vec + kThreads - 1) / kThreads), block(kThreads);
+    with_policy(stream_loads((size_t)a.n_vec * 32), stream_stores((size_t)a.n_vec * 32), [&](auto L, auto S) {
+        hipLaunchKernelGGL((seq_side_kernel<decltype(L)::value, decltype(S)::value, TO_BUF>), grid, block, 0, as_stream(stream),
+                           (const vec16*)in, (vec16*)out, a);
+    });
     return check_launch(who);
 }
 
@@ -148,12 +120,11 @@ static int launch_head_side(const cocodiff_shape* shape, const void* in, void* o
     const uint32_t Hp = shape->H / shape->P;
     a.first = shape->rank_begin * Hp;
     a.n_vec = (uint32_t)shape->rank_count * Hp * a.N * a.d8;
-    const uint32_t per_block = kThreads * kVecPerThread;
-    const dim3 grid((a.n_vec + per_block - 1) / per_block), block(kThreads);
-    if (should_stream((size_t)a.n_vec * 32))
-        hipLaunchKernelGGL((head_side_kernel<true, TO_BUF>), grid, block, 0, as_stream(stream), (const vec16*)in, (vec16*)out, a);
-    else
-        hipLaunchKernelGGL((head_side_kernel<false, TO_BUF>), grid, block, 0, as_stream(stream), (const vec16*)in, (vec16*)out, a);
+    const dim3 grid((a.n_vec + kThreads - 1) / kThreads), block(kThreads);
+    with_policy(stream_loads((size_t)a.n_vec * 32), stream_stores((size_t)a.n_vec * 32), [&](auto L, auto S) {
+        hipLaunchKernelGGL((head_side_kernel<decltype(L)::value, decltype(S)::value, TO_BUF>), grid, block, 0, as_stream(stream),
+                           (const vec16*)in, (vec16*)out, a);
+    });
     return check_launch(who);
 }
 

@@ -37,29 +37,29 @@ __device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, floa
 }
 
 // Workgroup t: flag of tile t.
-template <bool STREAM>
-__global__ void __launch_bounds__(kSelThreads) select_flag_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
+template <bool NT_CUR, bool NT_PREV, int THREADS>
+__global__ void __launch_bounds__(THREADS) select_flag_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
                                                                   float tau, int32_t* __restrict__ tile_flag,
                                                                   int32_t* __restrict__ user_flags, SelectShape sh) {
     const uint32_t t = blockIdx.x;
     bool changed = false;
     // the tile's S segments form one index space g = s*seg8 + v; a lane keeps kSelUnroll vectors of each tensor in flight
     const uint32_t total = sh.S * sh.seg8;
-    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * kSelThreads) {
+    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * THREADS) {
         vec16 c[kSelUnroll], p[kSelUnroll];
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k) {
-            const uint32_t g = g0 + k * kSelThreads;
+            const uint32_t g = g0 + k * THREADS;
             if (g < total) {
                 const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
                 const uint64_t at = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v;
-                c[k] = ld_vec<STREAM>(cur + at);
-                p[k] = ld_vec<STREAM>(prev + at);
+                c[k] = ld_vec<NT_CUR>(cur + at);
+                p[k] = ld_vec<NT_PREV>(prev + at);
             }
         }
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k)
-            if (g0 + k * kSelThreads < total) changed |= vec_changed(c[k], p[k], tau);
+            if (g0 + k * THREADS < total) changed |= vec_changed(c[k], p[k], tau);
     }
     const int any = __syncthreads_or(changed ? 1 : 0) ? 1 : 0;
     if (threadIdx.x == 0) {
@@ -69,6 +69,7 @@ __global__ void __launch_bounds__(kSelThreads) select_flag_kernel(const vec16* _
 }
 
 // Sum over the workgroup of one count per lane; every lane gets the total.
+template <int THREADS>
 __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* wave_tot) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -76,34 +77,35 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* wave_tot) {
     __syncthreads();
     uint32_t tot = 0;
 #pragma unroll
-    for (int w = 0; w < kSelThreads / 64; ++w) tot += wave_tot[w];
+    for (int w = 0; w < THREADS / 64; ++w) tot += wave_tot[w];
     return tot;
 }
 
 // Workgroup t: if tile t is flagged, its list slot is the number of flagged tiles before it.
-__global__ void __launch_bounds__(kSelThreads) select_gather_kernel(const vec16* __restrict__ cur, const int32_t* __restrict__ tile_flag,
+template <int THREADS>
+__global__ void __launch_bounds__(THREADS) select_gather_kernel(const vec16* __restrict__ cur, const int32_t* __restrict__ tile_flag,
                                                                     int32_t* __restrict__ idx, int32_t* __restrict__ n_active,
                                                                     vec16* __restrict__ compact, SelectShape sh, uint32_t cap_tiles) {
-    __shared__ uint32_t wave_tot[kSelThreads / 64];
+    __shared__ uint32_t wave_tot[THREADS / 64];
     const uint32_t t = blockIdx.x;
     const bool mine = tile_flag[t] != 0;
     const bool last = t + 1 == sh.NT;
     if (!mine && !last) return;
     uint32_t before = 0;
-    for (uint32_t u = threadIdx.x; u < t; u += kSelThreads) before += tile_flag[u] != 0 ? 1u : 0u;
-    const uint32_t slot = block_sum(before, wave_tot);
+    for (uint32_t u = threadIdx.x; u < t; u += THREADS) before += tile_flag[u] != 0 ? 1u : 0u;
+    const uint32_t slot = block_sum<THREADS>(before, wave_tot);
     if (threadIdx.x == 0) {
         if (mine) idx[slot] = (int32_t)t;
         if (last) *n_active = (int32_t)(slot + (mine ? 1u : 0u));
     }
     if (!mine || !compact || slot >= cap_tiles) return;
     const uint32_t total = sh.S * sh.seg8;
-    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * kSelThreads) {
+    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * THREADS) {
         vec16 c[kSelUnroll];
         uint64_t dst[kSelUnroll];
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k) {
-            const uint32_t g = g0 + k * kSelThreads;
+            const uint32_t g = g0 + k * THREADS;
             if (g < total) {
                 const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
                 c[k] = cur[(uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v];
@@ -112,7 +114,7 @@ __global__ void __launch_bounds__(kSelThreads) select_gather_kernel(const vec16*
         }
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k)
-            if (g0 + k * kSelThreads < total) st_nt(compact + dst[k], c[k]);
+            if (g0 + k * THREADS < total) st_nt(compact + dst[k], c[k]);
     }
 }
 
@@ -147,7 +149,7 @@ __global__ void __launch_bounds__(kSelThreads) tile_move_kernel(vec16* __restric
         }
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k)
-            if (g0 + k * kSelThreads < total) (GATHER ? compact : x)[dst[k]] = c[k];
+            if (g0 + k * kSelThreads < total) st_nt((GATHER ? compact : x) + dst[k], c[k]);
     }
 }
 
@@ -193,17 +195,35 @@ extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t t
     hipStream_t st = as_stream(stream);
     int32_t* tile_flag = (int32_t*)workspace;
 
-    if (should_stream((size_t)S * sh.slab8 * 32))
-        hipLaunchKernelGGL(select_flag_kernel<true>, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
-                           (const vec16*)v_prev, tau, tile_flag, flags, sh);
-    else
-        hipLaunchKernelGGL(select_flag_kernel<false>, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
-                           (const vec16*)v_prev, tau, tile_flag, flags, sh);
+    const size_t touched = (size_t)S * sh.slab8 * 32;
+    // workgroup size: a tile in as few passes as possible (kSelUnroll vectors per lane and pass), 256..1024 lanes
+    const uint32_t per_tile = sh.S * sh.seg8;
+    const int threads = per_tile > 512 * kSelUnroll ? 1024 : per_tile > 256 * kSelUnroll ? 512 : 256;
+    // v_cur stays cached: the second launch reads the active tiles again
+    with_policy(false, stream_loads_once(touched), [&](auto C, auto Pv) {
+        constexpr bool c = decltype(C)::value, pv = decltype(Pv)::value;
+        if (threads == 1024)
+            hipLaunchKernelGGL((select_flag_kernel<c, pv, 1024>), dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur,
+                               (const vec16*)v_prev, tau, tile_flag, flags, sh);
+        else if (threads == 512)
+            hipLaunchKernelGGL((select_flag_kernel<c, pv, 512>), dim3(sh.NT), dim3(512), 0, st, (const vec16*)v_cur,
+                               (const vec16*)v_prev, tau, tile_flag, flags, sh);
+        else
+            hipLaunchKernelGGL((select_flag_kernel<c, pv, 256>), dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur,
+                               (const vec16*)v_prev, tau, tile_flag, flags, sh);
+    });
     rc = check_launch("select_flag_kernel");
     if (rc != COCODIFF_OK) return rc;
-    hipLaunchKernelGGL(select_gather_kernel, dim3(sh.NT), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
-                       (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh,
-                       compact ? (uint32_t)cap_tiles : 0u);
+    const uint32_t cap = compact ? (uint32_t)cap_tiles : 0u;
+    if (threads == 1024)
+        hipLaunchKernelGGL(select_gather_kernel<1024>, dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur,
+                           (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh, cap);
+    else if (threads == 512)
+        hipLaunchKernelGGL(select_gather_kernel<512>, dim3(sh.NT), dim3(512), 0, st, (const vec16*)v_cur,
+                           (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh, cap);
+    else
+        hipLaunchKernelGGL(select_gather_kernel<256>, dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur,
+                           (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh, cap);
     return check_launch("select_gather_kernel");
 }
 

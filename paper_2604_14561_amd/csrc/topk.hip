@@ -16,7 +16,7 @@ constexpr int kMetricWaves = 4;
 constexpr int kMetricUnroll = 6;
 
 // metric[n] = sum over slabs s and w of |cur[s][n][w] - prev[s][n][w]|
-template <bool STREAM>
+template <bool NT_CUR, bool NT_PREV>
 __global__ void __launch_bounds__(64 * kMetricWaves) token_metric_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
                                                                          float* __restrict__ metric, uint32_t S, uint32_t N, uint32_t W8) {
     const uint32_t lane = threadIdx.x & 63u;
@@ -32,8 +32,8 @@ __global__ void __launch_bounds__(64 * kMetricWaves) token_metric_kernel(const v
             if (g < total) {
                 const uint32_t s = g / W8, v = g - s * W8;
                 const uint64_t at = ((uint64_t)s * N + n) * W8 + v;
-                c[k] = ld_vec<STREAM>(cur + at);
-                p[k] = ld_vec<STREAM>(prev + at);
+                c[k] = ld_vec<NT_CUR>(cur + at);
+                p[k] = ld_vec<NT_PREV>(prev + at);
             }
         }
 #pragma unroll
@@ -165,12 +165,11 @@ extern "C" int cocodiff_vmajor_token_metric(int32_t S, int32_t N, int32_t W, con
     if (!v_cur || !v_prev || !metric) return fail(COCODIFF_ERR_NULL, "token_metric: NULL pointer");
     if (!aligned16(v_cur) || !aligned16(v_prev)) return fail(COCODIFF_ERR_ALIGN, "token_metric: tensors must be 16-byte aligned");
     const dim3 grid(((uint32_t)N + kMetricWaves - 1) / kMetricWaves), block(64 * kMetricWaves);
-    if (should_stream((size_t)S * N * W * 4))
-        hipLaunchKernelGGL(token_metric_kernel<true>, grid, block, 0, as_stream(stream), (const vec16*)v_cur,
-                           (const vec16*)v_prev, metric, (uint32_t)S, (uint32_t)N, (uint32_t)(W / 8));
-    else
-        hipLaunchKernelGGL(token_metric_kernel<false>, grid, block, 0, as_stream(stream), (const vec16*)v_cur,
-                           (const vec16*)v_prev, metric, (uint32_t)S, (uint32_t)N, (uint32_t)(W / 8));
+    const size_t touched = (size_t)S * N * W * 4;
+    with_policy(stream_loads(touched), stream_loads_once(touched), [&](auto C, auto Pv) {
+        hipLaunchKernelGGL((token_metric_kernel<decltype(C)::value, decltype(Pv)::value>), grid, block, 0, as_stream(stream),
+                           (const vec16*)v_cur, (const vec16*)v_prev, metric, (uint32_t)S, (uint32_t)N, (uint32_t)(W / 8));
+    });
     return check_launch("token_metric_kernel");
 }
 

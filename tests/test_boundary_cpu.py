@@ -110,6 +110,8 @@ def test_copy_argument_errors():
     assert L.cocodiff_util_copy(odd, fake, 16, None) == B.ERR_ALIGN
     assert L.cocodiff_util_copy(fake, fake, 24, None) == B.ERR_SHAPE
     assert L.cocodiff_util_copy(fake, fake, 0, None) == B.OK   # nothing to do, nothing launched
+    assert L.cocodiff_util_mfma_rate(0, 10, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_util_mfma_rate(256, 10, None, None) == B.ERR_NULL
 
 
 def test_rope_table_layout_and_closed_form_values():
