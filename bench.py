@@ -50,7 +50,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--schedule", default="vfirst3", choices=["vfirst", "vfirst3", "serial"])
+    ap.add_argument("--schedule", default="vfirst3", choices=["vfirst", "vfirst3", "serial", "fused3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     args = ap.parse_args()
@@ -196,27 +196,68 @@ def main() -> int:
             cd.a2a_unpack(sh, buf, dst, ORDER, stream=st)
         cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=st)
 
-    step = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial}[args.schedule]
+    def step_fused3(ev=None):
+        """The vfirst3 order with the fused calls: V's projection writes the exchange buffer itself, Q and K are
+        normalised and rotated on their way into theirs (3 fewer launches and passes over HBM per step)."""
+        if ev:
+            ev[0].record(s_v)
+        cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
+        if ev:
+            ev[1].record(s_v)
+        v_ready = torch.cuda.Event()
+        v_ready.record(s_v)
+        cd.a2a_unpack(sh, bv, hv, ORDER, stream=s_v)
+        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
+        s_qk.wait_event(v_ready)
+        if ev:
+            ev[2].record(s_qk)
+        cd.qkv_proj(sh, X, Wq, None, None, q, None, None, stream=s_qk)
+        q_ready = torch.cuda.Event()
+        q_ready.record(s_qk)
+        cd.qkv_proj(sh, X, None, Wk, None, None, k, None, stream=s_qk)
+        if ev:
+            ev[3].record(s_qk)
+        s_q.wait_event(q_ready)
+        cd.qk_norm_rope_pack(sh, q, None, gq, None, cfg.eps, rope, bq, None, ORDER, stream=s_q)
+        cd.a2a_unpack(sh, bq, hq, ORDER, stream=s_q)
+        cd.qk_norm_rope_pack(sh, None, k, None, gk, cfg.eps, rope, None, bk, ORDER, stream=s_qk)
+        cd.a2a_unpack(sh, bk, hk, ORDER, stream=s_qk)
+        done_q, done_k = torch.cuda.Event(), torch.cuda.Event()
+        done_q.record(s_q)
+        done_k.record(s_qk)
+        s_v.wait_event(done_q)
+        s_v.wait_event(done_k)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    assert int(n_act.cpu()[0]) == cfg.n_changed, "selection did not find the perturbed tiles"
+    schedules = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial, "fused3": step_fused3}
+    step = schedules[args.schedule]
 
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(events[i])
-    t_enq = time.perf_counter()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    log(f"  host enqueue time per step {(t_enq - t0) * 1e3 / args.steps:.3f} ms of {(t1 - t0) * 1e3 / args.steps:.3f} ms")
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    def time_schedule(step_fn):
+        for _ in range(args.warmup):
+            step_fn()
+        torch.cuda.synchronize()
+        assert int(n_act.cpu()[0]) == cfg.n_changed, "selection did not find the perturbed tiles"
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step_fn(evs[i])
+        t_enq = time.perf_counter()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        log(f"  host enqueue time per step {(t_enq - t0) * 1e3 / args.steps:.3f} ms of {(t1 - t0) * 1e3 / args.steps:.3f} ms")
+        return (t1 - t0) * 1e3 / args.steps, evs
+
+    ms_per_step, events = time_schedule(step)
     tokens_per_s = N / (ms_per_step * 1e-3)
+    # the same step with the fused entry points, reported beside the headline (which keeps the stand-alone calls)
+    fused = None
+    if args.schedule == "vfirst3":
+        ms_fused, _ = time_schedule(step_fused3)
+        fused = {"schedule": "fused3", "ms_per_step": round(ms_fused, 4), "value": round(N / (ms_fused * 1e-3), 1), "unit": "tokens/s"}
+        log(f"  fused3 schedule: {fused}")
 
     # dominant kernel: the projection GEMM (launched per step as V, then Q+K -- or V, Q, K in the vfirst3 order)
-    n_launch = 3 if args.schedule == "vfirst3" else 2
+    n_launch = 3 if args.schedule in ("vfirst3", "fused3") else 2
     gemm_ms = [(e[0].elapsed_time(e[1]), e[2].elapsed_time(e[3])) for e in events]
     gemm_ms_per_launch = float(np.mean([a + b for a, b in gemm_ms])) / n_launch
     flops_per_launch = 2.0 * N * (3 * D) * D / n_launch
@@ -283,6 +324,7 @@ def main() -> int:
         add("qkv_proj_v", [lambda: cd.qkv_proj(sh, X, None, None, Wv, None, None, v)], flops=g1)
         add("qkv_proj_qk", [lambda: cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None)], flops=2 * g1)
         add("qkv_proj_qkv", [lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v)], flops=3 * g1)
+        add("qkv_proj_pack_v", [lambda: cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER)], flops=g1)
 
         # rotation sets: a (token-major), b (exchange buffer), h and p (head-parallel current / previous V; never written)
         R = int(min(64, max(1, -(-(640 << 20) // (2 * tensor_bytes)))))
@@ -313,6 +355,8 @@ def main() -> int:
         add("a2a_pack", each(lambda s_: cd.a2a_pack(sh, s_["a"], s_["b"], ORDER)), nbytes=2 * tensor_bytes)
         add("a2a_unpack", each(lambda s_: cd.a2a_unpack(sh, s_["b"], s_["a"], ORDER)), nbytes=2 * tensor_bytes)
         add("qk_norm_rope", each(lambda s_: cd.qk_norm_rope(sh, s_["a"], s_["b"], gq, gk, cfg.eps, rope)), nbytes=4 * tensor_bytes)
+        add("qk_norm_rope_pack", each(lambda s_: cd.qk_norm_rope_pack(sh, s_["h"], s_["p"], gq, gk, cfg.eps, rope, s_["a"], s_["b"], ORDER)),
+            nbytes=4 * tensor_bytes)
         add("copy_same_bytes", each(lambda s_: cd.util_copy(s_["a"], s_["b"], tensor_bytes)), nbytes=2 * tensor_bytes)
         kernels["copy_1000MiB"] = {"us": round(copy_us, 2), "GB/s": attainable["hbm_copy_GB/s"],
                                    "frac_hbm_peak": round(attainable["hbm_copy_GB/s"] / PEAK_HBM_GBS, 4)}
@@ -384,6 +428,7 @@ def main() -> int:
                    "schedule": args.schedule, "global_batch": 1, "seq_len": N},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "fused_path": fused,
         "attainable": attainable,
         "kernels": kernels,
     }

@@ -115,6 +115,26 @@ COCODIFF_API int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf1
                           const cocodiff_rope* rope, void* stream);
 
 /*
+ * Fusions of the steps above (same arithmetic, fewer passes over HBM; Section III-C keeps tensor preparation for
+ * the exchange off the critical path -- here it disappears into the producing kernel):
+ *
+ * cocodiff_qkv_proj_pack  = cocodiff_qkv_proj followed by cocodiff_a2a_pack of every given tensor: the projection
+ *   writes its rows straight into the exchange buffers qbuf / kbuf / vbuf ([P*P slots][N/P][H/P][d], slot order as
+ *   in cocodiff_a2a_pack); no [N][D] tensor is written.  Bit-identical to the two calls.
+ * cocodiff_qk_norm_rope_pack = cocodiff_qk_norm_rope followed by cocodiff_a2a_pack: q / k ([N][D], read only, not
+ *   modified) are normalised and rotated on the way into qbuf / kbuf.  Bit-identical to the two calls.
+ * Argument rules of the calls they replace apply; a given tensor needs its buffer (COCODIFF_ERR_NULL otherwise).
+ */
+COCODIFF_API int cocodiff_qkv_proj_pack(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                        const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                        cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, cocodiff_bf16* vbuf, int slot_order,
+                                        void* stream);
+COCODIFF_API int cocodiff_qk_norm_rope_pack(const cocodiff_shape* shape, const cocodiff_bf16* q, const cocodiff_bf16* k,
+                                            const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                            const cocodiff_rope* rope, cocodiff_bf16* qbuf, cocodiff_bf16* kbuf,
+                                            int slot_order, void* stream);
+
+/*
  * Step 3a -- pack (Section II-A all-to-all, sender side; Section III-B "tensor preparation").
  * x_seq [N][H][d] -> xbuf, P*P chunks of [N/P][H/P][d]:
  *   chunk(r->p)[n][hl][i] = x_seq[r*N/P + n][p*H/P + hl][i]   for SOURCE ranks r in the range.

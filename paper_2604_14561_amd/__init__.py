@@ -16,7 +16,9 @@ from .binding import (  # noqa: F401
     a2a_unpack_seq,
     cache_active_count,
     qk_norm_rope,
+    qk_norm_rope_pack,
     qkv_proj,
+    qkv_proj_pack,
     rope_table,
     util_copy,
     util_mfma_rate,

@@ -20,7 +20,7 @@ ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_CAPACITY, ERR_HIP = -1, -2, -3, -4, -5
 SEND_MAJOR, RECV_MAJOR = 0, 1
 
 EXPORTS = (
-    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
+    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
     "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
@@ -92,7 +92,9 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_last_error.restype = ctypes.c_char_p
         L.cocodiff_util_mfma_rate.argtypes = [i32, i32, vp, vp]
         L.cocodiff_util_mfma_rate.restype = ctypes.c_int64
-        for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
+        L.cocodiff_qkv_proj_pack.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ci, vp]
+        L.cocodiff_qk_norm_rope_pack.argtypes = [sp, vp, vp, vp, vp, ctypes.c_float, rp, vp, vp, ci, vp]
+        for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
                      "cocodiff_vmajor_select", "cocodiff_vmajor_gather", "cocodiff_vmajor_scatter",
                      "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk",
                      "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_fill", "cocodiff_util_copy"):
@@ -141,6 +143,18 @@ def qkv_proj(shape: Shape, x, wq, wk, wv, q, k, v, stream=None) -> None:
 def qk_norm_rope(shape: Shape, q, k, gamma_q, gamma_k, eps: float, rope: Rope, stream=None) -> None:
     _check(lib().cocodiff_qk_norm_rope(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(gamma_q), _ptr(gamma_k),
                                        float(eps), ctypes.byref(rope), _stream(stream)))
+
+
+def qkv_proj_pack(shape: Shape, x, wq, wk, wv, qbuf, kbuf, vbuf, slot_order: int = SEND_MAJOR, stream=None) -> None:
+    _check(lib().cocodiff_qkv_proj_pack(ctypes.byref(shape), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv),
+                                        _ptr(qbuf), _ptr(kbuf), _ptr(vbuf), int(slot_order), _stream(stream)))
+
+
+def qk_norm_rope_pack(shape: Shape, q, k, gamma_q, gamma_k, eps: float, rope: Rope, qbuf, kbuf,
+                      slot_order: int = SEND_MAJOR, stream=None) -> None:
+    _check(lib().cocodiff_qk_norm_rope_pack(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(gamma_q), _ptr(gamma_k),
+                                            float(eps), ctypes.byref(rope), _ptr(qbuf), _ptr(kbuf), int(slot_order),
+                                            _stream(stream)))
 
 
 def a2a_pack(shape: Shape, x_seq, xbuf, slot_order: int = SEND_MAJOR, stream=None) -> None:

@@ -37,6 +37,10 @@ struct GemmArgs {
     int32_t row_begin, M;      // token rows [row_begin, row_begin + M)
     int32_t D;                 // features per tensor = K
     int32_t tiles_m, tiles_n_per_tensor;
+    // outputs in exchange-buffer (chunk) order instead of [N][D]: tokens per rank, ranks, 16-byte vectors per
+    // chunk row and per chunk, slot order
+    uint32_t Ns, P, row8, chunk8;
+    int32_t recv_major;
 };
 
 // [rows][64] bf16 tiles (128-byte rows): any 16 consecutive rows of one column land in 16 different
@@ -89,10 +93,12 @@ __device__ __forceinline__ void mfma_slice(f32x16 (&acc)[NI][4], const bf16x8 (&
 // Round to bf16, transpose through this wavefront's private LDS region (128 token rows of NI*32 features),
 // write whole rows.  Accumulator element e of lane l in MFMA tile (i, j): feature 32i + 8*(e/4) + 4*(l/32)
 // + e%4, token 32j + l%32.  16-byte column c of LDS row r is stored at column c ^ (r & (columns - 1)).
-template <int NI>
+// PACKED: the 8 features a lane writes for token n = r*Ns + m go to chunk (sender r, receiver p = feature / (Hp*d))
+// of the exchange buffer Y, row m (Hp*d is a multiple of 8, so a 16-byte vector never straddles two chunks).
+template <int NI, bool PACKED>
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][4], unsigned char* ep, uint32_t lane,
                                            uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
-                                           uint32_t M, uint32_t D) {
+                                           uint32_t M, uint32_t D, const GemmArgs& a) {
     constexpr uint32_t COLS = NI * 4;            // 16-byte columns per row
     constexpr uint32_t ROWB = COLS * 16;         // bytes per row
     const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
@@ -120,7 +126,16 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][4], unsigned 
         const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & (COLS - 1u))) << 4));
         const uint32_t tok = tok0 + row;
         const uint32_t feat = feat0 + c16 * 8u;
-        if (tok < M && feat < D) *reinterpret_cast<vec16*>(Y + (row0 + tok) * D + feat) = v;
+        if (tok < M && feat < D) {
+            if (PACKED) {
+                const uint32_t n = (uint32_t)row0 + tok, r = n / a.Ns, m = n - r * a.Ns;
+                const uint32_t v8 = feat >> 3, p = v8 / a.row8, c = v8 - p * a.row8;
+                const size_t slot = a.recv_major ? (size_t)p * a.P + r : (size_t)r * a.P + p;
+                reinterpret_cast<vec16*>(Y)[slot * a.chunk8 + (size_t)m * a.row8 + c] = v;
+            } else {
+                *reinterpret_cast<vec16*>(Y + (row0 + tok) * D + feat) = v;
+            }
+        }
     }
 }
 
@@ -158,7 +173,7 @@ __device__ __forceinline__ void load_to_lds(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
 }
 
-template <int WN>
+template <int WN, bool PACKED>
 __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     constexpr int WAVES = 2 * WN;
     constexpr int NI = BN / WN / 32;               // feature tiles per wavefront: 4 or 2
@@ -302,8 +317,8 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     advance();
     k_step(kt, slot, no{}, no{}, w0, no{});      // step n_k-1
     __syncthreads();
-    store_tile<NI>(acc, smem + wave * (128 * NI * 64), lane, a.y[tc.tensor], (size_t)a.row_begin,
-                   tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D);
+    store_tile<NI, PACKED>(acc, smem + wave * (128 * NI * 64), lane, a.y[tc.tensor], (size_t)a.row_begin,
+                           tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -313,6 +328,7 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
 constexpr int kStagedThreads = 256;
 constexpr int kVecPerOperand = BM * (BK / 8) / kStagedThreads;   // 16-byte vectors per lane per operand per stage: 8
 
+template <bool PACKED>
 __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const TileCoord tc = tile_of_block(a);
@@ -384,8 +400,8 @@ __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArg
         if (kt + 1 < n_k) store_stage(cur ^ 1u);
         __syncthreads();
     }
-    store_tile<4>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t,
-                  tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D);
+    store_tile<4, PACKED>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t,
+                          tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
 constexpr int kMainWN = 4;   // 8 wavefronts per workgroup in the main kernel
@@ -394,11 +410,14 @@ constexpr int kMainWN = 4;   // 8 wavefronts per workgroup in the main kernel
 
 using namespace cocodiff;
 
-extern "C" int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf16* x,
-                                 const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
-                                 cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, void* stream) {
+// packed = false: q, k, v are [N][D].  packed = true: they are exchange buffers, written in chunk order.
+static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                       const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                       cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, bool packed, int slot_order, void* stream) {
     int rc = check_shape(shape);
     if (rc != COCODIFF_OK) return rc;
+    if (packed && slot_order != COCODIFF_SEND_MAJOR && slot_order != COCODIFF_RECV_MAJOR)
+        return fail(COCODIFF_ERR_SHAPE, "qkv_proj_pack: slot_order (%d) must be SEND_MAJOR or RECV_MAJOR", slot_order);
     if (!x) return fail(COCODIFF_ERR_NULL, "qkv_proj: x is NULL");
     if ((wq == nullptr) != (q == nullptr) || (wk == nullptr) != (k == nullptr) || (wv == nullptr) != (v == nullptr))
         return fail(COCODIFF_ERR_NULL, "qkv_proj: a weight and its output must be given together");
@@ -407,6 +426,11 @@ extern "C" int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf1
         return fail(COCODIFF_ERR_ALIGN, "qkv_proj: pointers must be 16-byte aligned");
 
     GemmArgs a;
+    a.Ns = (uint32_t)(shape->N / shape->P);
+    a.P = (uint32_t)shape->P;
+    a.row8 = (uint32_t)(shape->H / shape->P) * (uint32_t)(shape->d / 8);
+    a.chunk8 = a.Ns * a.row8;
+    a.recv_major = slot_order == COCODIFF_RECV_MAJOR;
     a.x = x;
     a.n_tensors = 0;
     const cocodiff_bf16* ws[3] = {wv, wq, wk};   // V first: its tiles are dealt out before Q's and K's
@@ -432,16 +456,36 @@ extern "C" int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf1
 
     static bool attr_set = false;   // dynamic LDS above 64 KB needs the attribute once per process
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)qkv_gemm_direct_kernel<kMainWN>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)qkv_gemm_staged_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        hipError_t e = hipSuccess;
+        const void* ring[2] = {(const void*)qkv_gemm_direct_kernel<kMainWN, false>, (const void*)qkv_gemm_direct_kernel<kMainWN, true>};
+        const void* staged[2] = {(const void*)qkv_gemm_staged_kernel<false>, (const void*)qkv_gemm_staged_kernel<true>};
+        for (int i = 0; i < 2 && e == hipSuccess; ++i) {
+            e = hipFuncSetAttribute(ring[i], hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes);
+            if (e == hipSuccess) e = hipFuncSetAttribute(staged[i], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        }
         if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(e));
         attr_set = true;
     }
-    if (a.D % BK == 0 && a.D >= 3 * BK)
-        hipLaunchKernelGGL(qkv_gemm_direct_kernel<kMainWN>, dim3(n_tiles), dim3(128 * kMainWN), kRingLdsBytes, as_stream(stream), a);
+    const bool ring_kernel = a.D % BK == 0 && a.D >= 3 * BK;
+    if (ring_kernel && packed)
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<kMainWN, true>), dim3(n_tiles), dim3(128 * kMainWN), kRingLdsBytes, as_stream(stream), a);
+    else if (ring_kernel)
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<kMainWN, false>), dim3(n_tiles), dim3(128 * kMainWN), kRingLdsBytes, as_stream(stream), a);
+    else if (packed)
+        hipLaunchKernelGGL(qkv_gemm_staged_kernel<true>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, as_stream(stream), a);
     else
-        hipLaunchKernelGGL(qkv_gemm_staged_kernel, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, as_stream(stream), a);
+        hipLaunchKernelGGL(qkv_gemm_staged_kernel<false>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, as_stream(stream), a);
     return check_launch("qkv_gemm_kernel");
+}
+
+extern "C" int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                 const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                 cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, void* stream) {
+    return proj_launch(shape, x, wq, wk, wv, q, k, v, false, COCODIFF_SEND_MAJOR, stream);
+}
+
+extern "C" int cocodiff_qkv_proj_pack(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                      const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                      cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, cocodiff_bf16* vbuf, int slot_order, void* stream) {
+    return proj_launch(shape, x, wq, wk, wv, qbuf, kbuf, vbuf, true, slot_order, stream);
 }

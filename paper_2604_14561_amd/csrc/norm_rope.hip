@@ -20,6 +20,9 @@ struct RopeDev {
 
 struct NormRopeArgs {
     uint16_t* tensor[2];
+    uint16_t* packed[2];              // PACK: the exchange buffers the result goes to (tensor[] is then read only)
+    uint32_t Ns, P, row8, chunk8;     // PACK: tokens per rank, ranks, vectors per chunk row and per chunk
+    int recv_major;
     const uint16_t* gamma[2];
     uint32_t D8, d8;
     uint32_t first_token, n_tokens;   // token range of this launch
@@ -46,7 +49,7 @@ __device__ __forceinline__ float group_sum(float v, uint32_t width) {
 
 constexpr int kMaxSteps = 8;
 
-template <int STEPS, bool NT_LD, bool NT_ST>   // STEPS 0 = any number of steps, taken kMaxSteps at a time
+template <int STEPS, bool NT_LD, bool NT_ST, bool PACK>   // STEPS 0 = any number of steps, taken kMaxSteps at a time
 __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t run = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -98,6 +101,10 @@ __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
     }
 
     vec16* row = reinterpret_cast<vec16*>(base) + (size_t)n * a.D8 + v_first;
+    // PACK: vector v of token n = r*Ns + m goes to chunk (sender r, receiver p = v / row8), row m, column v % row8
+    vec16* const pbase = PACK ? reinterpret_cast<vec16*>(a.packed[blockIdx.y]) : nullptr;
+    const uint32_t r_own = PACK ? n / a.Ns : 0u;
+    const uint32_t m_in = PACK ? n - r_own * a.Ns : 0u;
     const uint32_t total_steps = STEPS ? (uint32_t)STEPS : a.steps;
     for (uint32_t s0 = 0; s0 < total_steps; s0 += kMaxSteps) {
         constexpr int UN = STEPS ? (STEPS < kMaxSteps ? STEPS : kMaxSteps) : kMaxSteps;
@@ -126,7 +133,14 @@ __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
                 const float od = x[2 * i + 1] * rinv * g[2 * i + 1];
                 o[i] = pack_bf16x2(e * cs_c[i] - od * cs_s[i], e * cs_s[i] + od * cs_c[i]);
             }
-            st_vec<NT_ST>(row + (size_t)(s0 + k) * 64, vec16{o[0], o[1], o[2], o[3]});
+            if (PACK) {
+                const uint32_t v = v_first + (s0 + k) * 64u;
+                const uint32_t p = v / a.row8, c = v - p * a.row8;
+                const size_t slot = a.recv_major ? (size_t)p * a.P + r_own : (size_t)r_own * a.P + p;
+                st_vec<NT_ST>(pbase + slot * a.chunk8 + (size_t)m_in * a.row8 + c, vec16{o[0], o[1], o[2], o[3]});
+            } else {
+                st_vec<NT_ST>(row + (size_t)(s0 + k) * 64, vec16{o[0], o[1], o[2], o[3]});
+            }
         }
     }
 }
@@ -135,11 +149,19 @@ __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
 
 using namespace cocodiff;
 
-extern "C" int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf16* q, cocodiff_bf16* k,
-                                     const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
-                                     const cocodiff_rope* rope, void* stream) {
+// pack = false: in place on q / k.  pack = true: q / k are read, the result goes to qbuf / kbuf in chunk order.
+static int norm_rope_launch(const cocodiff_shape* shape, cocodiff_bf16* q, cocodiff_bf16* k,
+                            const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                            const cocodiff_rope* rope, cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, int slot_order, bool pack,
+                            void* stream) {
     int rc = check_shape(shape);
     if (rc != COCODIFF_OK) return rc;
+    if (pack) {
+        if ((q && !qbuf) || (k && !kbuf)) return fail(COCODIFF_ERR_NULL, "qk_norm_rope_pack: exchange buffer missing for a given tensor");
+        if (!aligned16(qbuf) || !aligned16(kbuf)) return fail(COCODIFF_ERR_ALIGN, "qk_norm_rope_pack: buffers must be 16-byte aligned");
+        if (slot_order != COCODIFF_SEND_MAJOR && slot_order != COCODIFF_RECV_MAJOR)
+            return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope_pack: slot_order (%d) must be SEND_MAJOR or RECV_MAJOR", slot_order);
+    }
     if (!q && !k) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: q and k are both NULL");
     if ((q && !gamma_q) || (k && !gamma_k)) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: gamma missing for a given tensor");
     if (!rope || !rope->cs) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: rope description or its table is NULL");
@@ -163,10 +185,15 @@ extern "C" int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf16*
 
     NormRopeArgs a;
     int nt = 0;
-    if (q) { a.tensor[nt] = q; a.gamma[nt] = gamma_q; ++nt; }
-    if (k) { a.tensor[nt] = k; a.gamma[nt] = gamma_k; ++nt; }
-    if (nt == 1) { a.tensor[1] = a.tensor[0]; a.gamma[1] = a.gamma[0]; }
+    if (q) { a.tensor[nt] = q; a.gamma[nt] = gamma_q; a.packed[nt] = qbuf; ++nt; }
+    if (k) { a.tensor[nt] = k; a.gamma[nt] = gamma_k; a.packed[nt] = kbuf; ++nt; }
+    if (nt == 1) { a.tensor[1] = a.tensor[0]; a.gamma[1] = a.gamma[0]; a.packed[1] = a.packed[0]; }
     const uint32_t Ns = shape->N / shape->P;
+    a.Ns = Ns;
+    a.P = (uint32_t)shape->P;
+    a.row8 = (uint32_t)(shape->H / shape->P) * d8;
+    a.chunk8 = Ns * a.row8;
+    a.recv_major = slot_order == COCODIFF_RECV_MAJOR;
     a.D8 = D8;
     a.d8 = d8;
     a.first_token = shape->rank_begin * Ns;
@@ -190,9 +217,10 @@ extern "C" int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf16*
     hipStream_t st = as_stream(stream);
     const size_t touched = (size_t)nt * a.n_tokens * D8 * 32;
     const bool nt_ld = stream_loads_once(touched), nt_st = stream_stores(touched);   // in place: every element read once
-#define COCODIFF_NR_LAUNCH(S)                                                                                      \
-    with_policy(nt_ld, nt_st, [&](auto L, auto W) {                                                                \
-        hipLaunchKernelGGL((norm_rope_kernel<S, decltype(L)::value, decltype(W)::value>), grid, block, 0, st, a);  \
+#define COCODIFF_NR_LAUNCH(S)                                                                                                \
+    with_policy(nt_ld, nt_st, [&](auto L, auto W) {                                                                          \
+        if (pack) hipLaunchKernelGGL((norm_rope_kernel<S, decltype(L)::value, decltype(W)::value, true>), grid, block, 0, st, a);  \
+        else hipLaunchKernelGGL((norm_rope_kernel<S, decltype(L)::value, decltype(W)::value, false>), grid, block, 0, st, a);      \
     })
     switch (a.steps) {
         case 1: COCODIFF_NR_LAUNCH(1); break;
@@ -204,4 +232,18 @@ extern "C" int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf16*
     }
 #undef COCODIFF_NR_LAUNCH
     return check_launch("norm_rope_kernel");
+}
+
+extern "C" int cocodiff_qk_norm_rope(const cocodiff_shape* shape, cocodiff_bf16* q, cocodiff_bf16* k,
+                                     const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                     const cocodiff_rope* rope, void* stream) {
+    return norm_rope_launch(shape, q, k, gamma_q, gamma_k, eps, rope, nullptr, nullptr, COCODIFF_SEND_MAJOR, false, stream);
+}
+
+extern "C" int cocodiff_qk_norm_rope_pack(const cocodiff_shape* shape, const cocodiff_bf16* q, const cocodiff_bf16* k,
+                                          const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                          const cocodiff_rope* rope, cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, int slot_order,
+                                          void* stream) {
+    return norm_rope_launch(shape, const_cast<cocodiff_bf16*>(q), const_cast<cocodiff_bf16*>(k), gamma_q, gamma_k, eps, rope,
+                            qbuf, kbuf, slot_order, true, stream);
 }

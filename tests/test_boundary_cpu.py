@@ -140,3 +140,22 @@ def test_binding_refuses_host_tensors():
     x = torch.zeros(256, 256, dtype=torch.int16)
     with pytest.raises(ValueError):
         cd.a2a_pack(s, x, x, cd.SEND_MAJOR, stream=0)
+
+
+def test_fused_entry_points_check_arguments_before_any_launch():
+    L = B.lib()
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    s = cd.Shape.make(256, 256, 4, 64, 2)
+    bad = cd.Shape.make(250, 256, 4, 64, 2)
+    f = L.cocodiff_qkv_proj_pack
+    assert f(ctypes.byref(bad), fake, fake, None, None, fake, None, None, 0, None) == B.ERR_SHAPE
+    assert f(ctypes.byref(s), fake, fake, None, None, fake, None, None, 9, None) == B.ERR_SHAPE      # slot order
+    assert f(ctypes.byref(s), fake, fake, None, None, None, None, None, 0, None) == B.ERR_NULL       # weight without buffer
+    assert f(ctypes.byref(s), None, fake, None, None, fake, None, None, 0, None) == B.ERR_NULL
+    assert f(ctypes.byref(s), fake, fake, None, None, odd, None, None, 0, None) == B.ERR_ALIGN
+    rope = cd.Rope.make((16, 16), (16, 16), 10000.0, 0x1000)
+    g = L.cocodiff_qk_norm_rope_pack
+    assert g(ctypes.byref(s), fake, None, fake, None, 1e-6, ctypes.byref(rope), None, None, 0, None) == B.ERR_NULL   # q without qbuf
+    assert g(ctypes.byref(s), None, None, None, None, 1e-6, ctypes.byref(rope), fake, fake, 0, None) == B.ERR_NULL
+    assert g(ctypes.byref(s), fake, None, fake, None, 1e-6, ctypes.byref(rope), odd, None, 0, None) == B.ERR_ALIGN
+    assert g(ctypes.byref(s), fake, None, fake, None, 1e-6, ctypes.byref(rope), fake, None, 4, None) == B.ERR_SHAPE

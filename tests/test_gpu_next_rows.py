@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import paper_2604_14561_amd as cd
-from parity_util import dev_empty, to_dev, to_host_bits
+from parity_util import assert_float_parity, dev_empty, to_dev, to_host_bits
 from synth import CONFIGS, make_v_pair
 
 gpu = pytest.mark.gpu
@@ -226,6 +226,98 @@ def test_topk_ties_nan_and_extremes(oracle):
     cd.vmajor_gather(S, N, W, 1, to_dev(x), idx, n_act, comp, k)
     _sync()
     assert np.array_equal(to_host_bits(comp), x[:, oracle.topk_active(m.astype(np.float64), k), :])
+
+
+# ---------------------------------------------------------------------------
+# fusions: projection -> exchange buffer, norm + RoPE -> exchange buffer
+# ---------------------------------------------------------------------------
+
+@gpu
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C1", 1), ("C2", 1), ("C3", 1), ("C5", 0)])
+def test_proj_pack_equals_proj_then_pack(oracle, name, order):
+    cfg = CONFIGS[name]
+    print(f"proj_pack {name} order {order}", flush=True)
+    from synth import make_layer_inputs, sample_token_ids
+    inp = make_layer_inputs(cfg)
+    sh = cd.Shape.make(cfg.N, cfg.D, cfg.H, cfg.d, cfg.P)
+    X, Wq, Wv = to_dev(inp["X"]), to_dev(inp["Wq"]), to_dev(inp["Wv"])
+    q, v = dev_empty((cfg.N, cfg.D)), dev_empty((cfg.N, cfg.D))
+    bq, bv, fq, fv = (dev_empty((cfg.N * cfg.D,)) for _ in range(4))
+    cd.qkv_proj(sh, X, Wq, None, Wv, q, None, v)
+    cd.a2a_pack(sh, q, bq, order)
+    cd.a2a_pack(sh, v, bv, order)
+    for t in (fq, fv):
+        t.fill_(-1)
+    cd.qkv_proj_pack(sh, X, Wq, None, Wv, fq, None, fv, order)
+    _sync()
+    assert np.array_equal(to_host_bits(fq), to_host_bits(bq)) and np.array_equal(to_host_bits(fv), to_host_bits(bv))
+    # and against the oracle: pack(round_bf16(fp64 projection)) on sampled tokens, within the float tolerance
+    ids = np.arange(cfg.N) if name in ("C1", "C2") else sample_token_ids(cfg, random_tiles_per_rank=2)
+    hs = dev_empty((cfg.H, cfg.N, cfg.d))
+    cd.a2a_unpack(sh, fv, hs, order)
+    _sync()
+    got = to_host_bits(hs).transpose(1, 0, 2).reshape(cfg.N, cfg.D)[ids]
+    assert_float_parity(got, oracle.qkv_proj(inp["X"][ids], inp["Wv"]), f"proj_pack {name}")
+    # a rank range writes only that range's chunks
+    fq.fill_(-1)
+    r0 = cfg.P - 1
+    cd.qkv_proj_pack(cd.Shape.make(cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, r0, 1), X, Wq, None, None, fq, None, None, order)
+    _sync()
+    part, full = to_host_bits(fq).reshape(cfg.P, cfg.P, -1), to_host_bits(bq).reshape(cfg.P, cfg.P, -1)
+    mine = np.zeros((cfg.P, cfg.P), dtype=bool)
+    if order == cd.SEND_MAJOR:
+        mine[r0, :] = True
+    else:
+        mine[:, r0] = True
+    assert np.array_equal(part[mine], full[mine]) and np.all(part[~mine] == 0xFFFF)
+
+
+@gpu
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C5", 1)])
+def test_norm_rope_pack_equals_norm_rope_then_pack(oracle, name, order):
+    import torch
+    cfg = CONFIGS[name]
+    print(f"norm_rope_pack {name} order {order}", flush=True)
+    rng = np.random.default_rng(cfg.index + 70)
+    from synth import f32_to_bf16_bits
+    q0 = f32_to_bf16_bits(rng.standard_normal((cfg.N, cfg.D), dtype=np.float32))
+    k0 = f32_to_bf16_bits(rng.standard_normal((cfg.N, cfg.D), dtype=np.float32) * np.float32(3.0))
+    gq = f32_to_bf16_bits((1 + 0.1 * rng.standard_normal(cfg.d)).astype(np.float32))
+    gk = f32_to_bf16_bits((1 + 0.1 * rng.standard_normal(cfg.d)).astype(np.float32))
+    table = torch.from_numpy(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta)).to("cuda:0")
+    rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, table.data_ptr())
+    sh = cd.Shape.make(cfg.N, cfg.D, cfg.H, cfg.d, cfg.P)
+    qd, kd, gqd, gkd = to_dev(q0), to_dev(k0), to_dev(gq), to_dev(gk)
+    fq, fk, bq, bk = (dev_empty((cfg.N * cfg.D,)) for _ in range(4))
+    for t in (fq, fk):
+        t.fill_(-1)
+    cd.qk_norm_rope_pack(sh, qd, kd, gqd, gkd, cfg.eps, rope, fq, fk, order)
+    _sync()
+    assert np.array_equal(to_host_bits(qd), q0) and np.array_equal(to_host_bits(kd), k0)     # inputs untouched
+    cd.qk_norm_rope(sh, qd, kd, gqd, gkd, cfg.eps, rope)
+    cd.a2a_pack(sh, qd, bq, order)
+    cd.a2a_pack(sh, kd, bk, order)
+    _sync()
+    assert np.array_equal(to_host_bits(fq), to_host_bits(bq)) and np.array_equal(to_host_bits(fk), to_host_bits(bk))
+    # one tensor alone, one rank alone
+    fq.fill_(-1)
+    cd.qk_norm_rope_pack(cd.Shape.make(cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, 0, 1), to_dev(q0), None, gqd, None, cfg.eps, rope, fq, None, order)
+    _sync()
+    part, full = to_host_bits(fq).reshape(cfg.P, cfg.P, -1), to_host_bits(bq).reshape(cfg.P, cfg.P, -1)
+    mine = np.zeros((cfg.P, cfg.P), dtype=bool)
+    if order == cd.SEND_MAJOR:
+        mine[0, :] = True
+    else:
+        mine[:, 0] = True
+    assert np.array_equal(part[mine], full[mine]) and np.all(part[~mine] == 0xFFFF)
+    # the oracle: pack(norm_rope) on the first rank's tokens
+    ids = np.arange(cfg.Ns)
+    want = oracle.qk_norm_rope(q0[ids].reshape(-1, cfg.H, cfg.d), ids, gq, cfg.eps, cfg.grid, cfg.pairs, cfg.theta)
+    hs = dev_empty((cfg.H, cfg.N, cfg.d))
+    cd.a2a_unpack(sh, bq, hs, order)
+    _sync()
+    got = to_host_bits(hs).transpose(1, 0, 2)[ids]
+    assert_float_parity(got, want, f"norm_rope_pack {name}")
 
 
 def test_cache_schedule_host_arithmetic(oracle):
