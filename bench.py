@@ -198,7 +198,8 @@ def main() -> int:
 
     def step_fused3(ev=None):
         """The vfirst3 order with the fused calls: V's projection writes the exchange buffer itself, Q and K are
-        normalised and rotated on their way into theirs (3 fewer launches and passes over HBM per step)."""
+        normalised and rotated on their way into theirs, V's unpack computes the selection's flags (5 fewer launches
+        and 4 fewer passes over HBM per step)."""
         if ev:
             ev[0].record(s_v)
         cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
@@ -206,8 +207,7 @@ def main() -> int:
             ev[1].record(s_v)
         v_ready = torch.cuda.Event()
         v_ready.record(s_v)
-        cd.a2a_unpack(sh, bv, hv, ORDER, stream=s_v)
-        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
+        cd.a2a_unpack_select(sh, bv, ORDER, hv, hv_prev, T, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
         s_qk.wait_event(v_ready)
         if ev:
             ev[2].record(s_qk)
@@ -345,6 +345,8 @@ def main() -> int:
 
         add("vmajor_select", each(lambda s_: cd.vmajor_select(H, N, d, T, s_["h"], s_["p"], cfg.tau, flags, idx, n_act, compact, cap, ws)),
             nbytes=(2 + f_act) * tensor_bytes)
+        add("a2a_unpack_select", each(lambda s_: cd.a2a_unpack_select(sh, s_["b"], ORDER, s_["a"], s_["p"], T, cfg.tau, flags, idx, n_act, compact, cap, ws)),
+            nbytes=(3 + f_act) * tensor_bytes)
         add("vmajor_token_metric", each(lambda s_: cd.vmajor_token_metric(H, N, d, s_["h"], s_["p"], metric)), nbytes=2 * tensor_bytes)
         add("vmajor_topk", [lambda: cd.vmajor_topk(P, N // P, metric, k_act, tok_idx, tok_n)])   # every rank ranks its own tokens
         # rows after the hot path: sender-side gather / receiver-side scatter of the active tiles, second all-to-all

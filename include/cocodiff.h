@@ -135,6 +135,20 @@ COCODIFF_API int cocodiff_qk_norm_rope_pack(const cocodiff_shape* shape, const c
                                             int slot_order, void* stream);
 
 /*
+ * cocodiff_a2a_unpack_select = cocodiff_a2a_unpack of V followed by cocodiff_vmajor_select on the unpacked tensor
+ * (head-parallel: S = H, W = d): the selection's first pass reads the current values from the exchange buffer
+ * vbuf, writes them to their place in v_hs [H][N][d] and compares them with v_prev on the way, so the unpacked
+ * tensor is not read again for the flags.  Bit-identical to the two calls (v_hs, flags, active_idx, n_active,
+ * compact).  The rank range of `shape` must be all P ranks (a tile's flag needs every head).  Other arguments
+ * and rules as for cocodiff_vmajor_select with S = H, N, W = d.
+ */
+COCODIFF_API int cocodiff_a2a_unpack_select(const cocodiff_shape* shape, const cocodiff_bf16* vbuf, int slot_order,
+                                            cocodiff_bf16* v_hs, const cocodiff_bf16* v_prev, int32_t tile_tokens, float tau,
+                                            int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                                            cocodiff_bf16* compact, int32_t cap_tiles,
+                                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Step 3a -- pack (Section II-A all-to-all, sender side; Section III-B "tensor preparation").
  * x_seq [N][H][d] -> xbuf, P*P chunks of [N/P][H/P][d]:
  *   chunk(r->p)[n][hl][i] = x_seq[r*N/P + n][p*H/P + hl][i]   for SOURCE ranks r in the range.

@@ -20,7 +20,8 @@ ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_CAPACITY, ERR_HIP = -1, -2, -3, -4, -5
 SEND_MAJOR, RECV_MAJOR = 0, 1
 
 EXPORTS = (
-    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
+    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack",
+    "cocodiff_a2a_unpack_select", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
     "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
@@ -92,6 +93,8 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_last_error.restype = ctypes.c_char_p
         L.cocodiff_util_mfma_rate.argtypes = [i32, i32, vp, vp]
         L.cocodiff_util_mfma_rate.restype = ctypes.c_int64
+        L.cocodiff_a2a_unpack_select.argtypes = [sp, vp, ci, vp, vp, i32, f32, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.cocodiff_a2a_unpack_select.restype = ci
         L.cocodiff_qkv_proj_pack.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ci, vp]
         L.cocodiff_qk_norm_rope_pack.argtypes = [sp, vp, vp, vp, vp, ctypes.c_float, rp, vp, vp, ci, vp]
         for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
@@ -155,6 +158,14 @@ def qk_norm_rope_pack(shape: Shape, q, k, gamma_q, gamma_k, eps: float, rope: Ro
     _check(lib().cocodiff_qk_norm_rope_pack(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(gamma_q), _ptr(gamma_k),
                                             float(eps), ctypes.byref(rope), _ptr(qbuf), _ptr(kbuf), int(slot_order),
                                             _stream(stream)))
+
+
+def a2a_unpack_select(shape: Shape, vbuf, slot_order: int, v_hs, v_prev, tile_tokens: int, tau: float, flags, active_idx,
+                      n_active, compact, cap_tiles: int, workspace, stream=None) -> None:
+    _check(lib().cocodiff_a2a_unpack_select(ctypes.byref(shape), _ptr(vbuf), int(slot_order), _ptr(v_hs), _ptr(v_prev),
+                                            int(tile_tokens), float(tau), _ptr(flags), _ptr(active_idx), _ptr(n_active),
+                                            _ptr(compact), int(cap_tiles), _ptr(workspace),
+                                            int(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 
 def a2a_pack(shape: Shape, x_seq, xbuf, slot_order: int = SEND_MAJOR, stream=None) -> None:

@@ -36,30 +36,55 @@ __device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, floa
     return changed;
 }
 
-// Workgroup t: flag of tile t.
-template <bool NT_CUR, bool NT_PREV, int THREADS>
+// Where the current tensor comes from when the flag pass also does the receiver-side unpack of the first
+// all-to-all: the exchange buffer, chunk (sender r -> receiver p) = [Ns tokens][Hp heads][d].
+struct UnpackSource {
+    const vec16* buf;
+    vec16* hs_out;               // the head-parallel tensor being produced ([H][N][d])
+    uint32_t Ns, P, Hp, d8, T;   // tokens per rank, ranks, heads per rank, vectors per head row, tokens per tile
+    uint32_t row8, chunk8;
+    int recv_major;
+};
+
+// Workgroup t: flag of tile t.  FROM_BUF: the current values are read from the exchange buffer (and written to
+// their place in the head-parallel tensor on the way) instead of from `cur`.
+template <bool NT_CUR, bool NT_PREV, int THREADS, bool FROM_BUF>
 __global__ void __launch_bounds__(THREADS) select_flag_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
-                                                                  float tau, int32_t* __restrict__ tile_flag,
-                                                                  int32_t* __restrict__ user_flags, SelectShape sh) {
+                                                              float tau, int32_t* __restrict__ tile_flag,
+                                                              int32_t* __restrict__ user_flags, SelectShape sh, UnpackSource u) {
     const uint32_t t = blockIdx.x;
     bool changed = false;
     // the tile's S segments form one index space g = s*seg8 + v; a lane keeps kSelUnroll vectors of each tensor in flight
     const uint32_t total = sh.S * sh.seg8;
     for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * THREADS) {
         vec16 c[kSelUnroll], p[kSelUnroll];
+        uint64_t hs_at[kSelUnroll];
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k) {
             const uint32_t g = g0 + k * THREADS;
             if (g < total) {
                 const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
                 const uint64_t at = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v;
-                c[k] = ld_vec<NT_CUR>(cur + at);
+                if (FROM_BUF) {
+                    // s is the head, v = (token in tile) * d8 + i8
+                    const uint32_t tl = v / u.d8, i8 = v - tl * u.d8;
+                    const uint32_t n = t * u.T + tl, r = n / u.Ns, m = n - r * u.Ns;
+                    const uint32_t pr = s / u.Hp, hl = s - pr * u.Hp;
+                    const size_t slot = u.recv_major ? (size_t)pr * u.P + r : (size_t)r * u.P + pr;
+                    c[k] = ld_nt(u.buf + slot * u.chunk8 + (size_t)m * u.row8 + hl * u.d8 + i8);
+                    hs_at[k] = at;
+                } else {
+                    c[k] = ld_vec<NT_CUR>(cur + at);
+                }
                 p[k] = ld_vec<NT_PREV>(prev + at);
             }
         }
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k)
-            if (g0 + k * THREADS < total) changed |= vec_changed(c[k], p[k], tau);
+            if (g0 + k * THREADS < total) {
+                changed |= vec_changed(c[k], p[k], tau);
+                if (FROM_BUF) u.hs_out[hs_at[k]] = c[k];      // cached store: the gather pass reads the active tiles again
+            }
     }
     const int any = __syncthreads_or(changed ? 1 : 0) ? 1 : 0;
     if (threadIdx.x == 0) {
@@ -176,11 +201,12 @@ extern "C" size_t cocodiff_vmajor_select_workspace_bytes(int32_t S, int32_t N, i
     return (size_t)sh.NT * sizeof(int32_t);   // one flag per tile
 }
 
-extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
-                                      const cocodiff_bf16* v_cur, const cocodiff_bf16* v_prev, float tau,
-                                      int32_t* flags, int32_t* active_idx, int32_t* n_active,
-                                      cocodiff_bf16* compact, int32_t cap_tiles,
-                                      void* workspace, size_t workspace_bytes, void* stream) {
+// from_buf == nullptr: v_cur is read.  Otherwise v_cur is WRITTEN (the unpacked tensor) from from_buf->buf.
+static int select_launch(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
+                         const cocodiff_bf16* v_cur, const cocodiff_bf16* v_prev, float tau,
+                         int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                         cocodiff_bf16* compact, int32_t cap_tiles,
+                         void* workspace, size_t workspace_bytes, const UnpackSource* from_buf, void* stream) {
     SelectShape sh;
     int rc = select_shape(S, N, W, tile_tokens, &sh);
     if (rc != COCODIFF_OK) return rc;
@@ -200,17 +226,18 @@ extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t t
     const uint32_t per_tile = sh.S * sh.seg8;
     const int threads = per_tile > 512 * kSelUnroll ? 1024 : per_tile > 256 * kSelUnroll ? 512 : 256;
     // v_cur stays cached: the second launch reads the active tiles again
-    with_policy(false, stream_loads_once(touched), [&](auto C, auto Pv) {
-        constexpr bool c = decltype(C)::value, pv = decltype(Pv)::value;
+    const UnpackSource src = from_buf ? *from_buf : UnpackSource{};
+    with_policy(from_buf != nullptr, stream_loads_once(touched), [&](auto F, auto Pv) {
+        constexpr bool fb = decltype(F)::value, pv = decltype(Pv)::value;
         if (threads == 1024)
-            hipLaunchKernelGGL((select_flag_kernel<c, pv, 1024>), dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur,
-                               (const vec16*)v_prev, tau, tile_flag, flags, sh);
+            hipLaunchKernelGGL((select_flag_kernel<false, pv, 1024, fb>), dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur,
+                               (const vec16*)v_prev, tau, tile_flag, flags, sh, src);
         else if (threads == 512)
-            hipLaunchKernelGGL((select_flag_kernel<c, pv, 512>), dim3(sh.NT), dim3(512), 0, st, (const vec16*)v_cur,
-                               (const vec16*)v_prev, tau, tile_flag, flags, sh);
+            hipLaunchKernelGGL((select_flag_kernel<false, pv, 512, fb>), dim3(sh.NT), dim3(512), 0, st, (const vec16*)v_cur,
+                               (const vec16*)v_prev, tau, tile_flag, flags, sh, src);
         else
-            hipLaunchKernelGGL((select_flag_kernel<c, pv, 256>), dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur,
-                               (const vec16*)v_prev, tau, tile_flag, flags, sh);
+            hipLaunchKernelGGL((select_flag_kernel<false, pv, 256, fb>), dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur,
+                               (const vec16*)v_prev, tau, tile_flag, flags, sh, src);
     });
     rc = check_launch("select_flag_kernel");
     if (rc != COCODIFF_OK) return rc;
@@ -225,6 +252,43 @@ extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t t
         hipLaunchKernelGGL(select_gather_kernel<256>, dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur,
                            (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh, cap);
     return check_launch("select_gather_kernel");
+}
+
+extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
+                                      const cocodiff_bf16* v_cur, const cocodiff_bf16* v_prev, float tau,
+                                      int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                                      cocodiff_bf16* compact, int32_t cap_tiles,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    return select_launch(S, N, W, tile_tokens, v_cur, v_prev, tau, flags, active_idx, n_active, compact, cap_tiles, workspace,
+                         workspace_bytes, nullptr, stream);
+}
+
+extern "C" int cocodiff_a2a_unpack_select(const cocodiff_shape* shape, const cocodiff_bf16* vbuf, int slot_order,
+                                          cocodiff_bf16* v_hs, const cocodiff_bf16* v_prev, int32_t tile_tokens, float tau,
+                                          int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                                          cocodiff_bf16* compact, int32_t cap_tiles,
+                                          void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != COCODIFF_OK) return rc;
+    if (shape->rank_begin != 0 || shape->rank_count != shape->P)
+        return fail(COCODIFF_ERR_SHAPE, "unpack_select: a tile's flag needs every head, so the rank range must be all P ranks");
+    if (slot_order != COCODIFF_SEND_MAJOR && slot_order != COCODIFF_RECV_MAJOR)
+        return fail(COCODIFF_ERR_SHAPE, "unpack_select: slot_order (%d) must be SEND_MAJOR or RECV_MAJOR", slot_order);
+    if (!vbuf) return fail(COCODIFF_ERR_NULL, "unpack_select: vbuf is NULL");
+    if (!aligned16(vbuf)) return fail(COCODIFF_ERR_ALIGN, "unpack_select: vbuf must be 16-byte aligned");
+    UnpackSource u;
+    u.buf = (const vec16*)vbuf;
+    u.hs_out = (vec16*)v_hs;
+    u.Ns = (uint32_t)(shape->N / shape->P);
+    u.P = (uint32_t)shape->P;
+    u.Hp = (uint32_t)(shape->H / shape->P);
+    u.d8 = (uint32_t)(shape->d / 8);
+    u.T = (uint32_t)tile_tokens;
+    u.row8 = u.Hp * u.d8;
+    u.chunk8 = u.Ns * u.row8;
+    u.recv_major = slot_order == COCODIFF_RECV_MAJOR;
+    return select_launch(shape->H, shape->N, shape->d, tile_tokens, v_hs, v_prev, tau, flags, active_idx, n_active, compact,
+                         cap_tiles, workspace, workspace_bytes, &u, stream);
 }
 
 static int tile_move(bool gather, int32_t S, int32_t N, int32_t W, int32_t tile_tokens, const void* x, const void* compact,

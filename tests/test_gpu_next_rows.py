@@ -320,6 +320,50 @@ def test_norm_rope_pack_equals_norm_rope_then_pack(oracle, name, order):
     assert_float_parity(got, want, f"norm_rope_pack {name}")
 
 
+@gpu
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C5", 0)])
+def test_unpack_select_equals_unpack_then_select(oracle, name, order):
+    import torch
+    cfg = CONFIGS[name]
+    print(f"unpack_select {name} order {order}", flush=True)
+    cur, prev, changed = make_v_pair(cfg, layout="hs")            # [H][N][d]
+    H, N, d, T, NT = cfg.H, cfg.N, cfg.d, cfg.tile_tokens, cfg.NT
+    sh = cd.Shape.make(N, cfg.D, H, d, cfg.P)
+    seq = np.ascontiguousarray(cur.transpose(1, 0, 2))             # [N][H][d]: what the senders hold
+    buf = dev_empty((N * cfg.D,))
+    cd.a2a_pack(sh, to_dev(seq), buf, order)
+    prev_d = to_dev(prev)
+    ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device="cuda:0")
+    outs = []
+    for fused in (False, True):
+        hs = dev_empty((H, N, d))
+        hs.fill_(-1)
+        flags, idx, n_act = dev_empty((NT,), "i32"), dev_empty((NT,), "i32"), dev_empty((1,), "i32")
+        idx.fill_(-1)
+        compact = dev_empty((H, NT * T, d))
+        compact.fill_(-1)
+        if fused:
+            cd.a2a_unpack_select(sh, buf, order, hs, prev_d, T, cfg.tau, flags, idx, n_act, compact, NT, ws)
+        else:
+            cd.a2a_unpack(sh, buf, hs, order)
+            cd.vmajor_select(H, N, d, T, hs, prev_d, cfg.tau, flags, idx, n_act, compact, NT, ws)
+        _sync()
+        n = int(n_act.cpu()[0])
+        outs.append((to_host_bits(hs), flags.cpu().numpy(), idx.cpu().numpy()[:n], n, to_host_bits(compact)[:, :n * T]))
+    a, b = outs
+    assert np.array_equal(a[0], b[0]) and np.array_equal(b[0], cur)
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2]) and a[3] == b[3]
+    assert np.array_equal(a[4], b[4])
+    # and against the oracle / the generator's own list
+    o_flags, o_idx, o_n, o_comp = oracle.vmajor_select(cur, prev, cfg.tau, T)
+    assert b[3] == o_n == len(changed) and np.array_equal(b[2], o_idx[:o_n]) and np.array_equal(b[2], np.sort(changed))
+    assert np.array_equal(b[1], o_flags) and np.array_equal(b[4], o_comp[:, :o_n * T])
+    # a partial rank range is refused: a tile's flag needs every head
+    with pytest.raises(cd.CocodiffError):
+        cd.a2a_unpack_select(cd.Shape.make(N, cfg.D, H, d, cfg.P, 0, 1), buf, order, hs, prev_d, T, cfg.tau, None, idx, n_act,
+                             None, NT, ws)
+
+
 def test_cache_schedule_host_arithmetic(oracle):
     for n_tokens in (9216, 900, 99840, 7):
         for step in range(1, 51):
