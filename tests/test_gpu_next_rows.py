@@ -397,3 +397,91 @@ def test_next_rows_argument_errors():
     assert L.cocodiff_vmajor_topk(0, 256, fake, 5, fake, fake, None) == B.ERR_SHAPE
     assert L.cocodiff_vmajor_topk(1 << 16, 1 << 16, fake, 5, fake, fake, None) == B.ERR_SHAPE
     assert L.cocodiff_vmajor_topk(1, 256, None, 5, fake, fake, None) == B.ERR_NULL
+
+
+# ---------------------------------------------------------------------------
+# the benchmark's default schedule: fused entry points on three streams
+# ---------------------------------------------------------------------------
+
+@gpu
+@pytest.mark.parametrize("name", ["C2", "C3"])
+def test_fused_three_stream_step_equals_standalone_calls_and_oracle(oracle, name):
+    """The step bench.py times by default (V-First order, three streams, fused entry points) against the same step
+    through the five stand-alone calls on one stream (bit-identical: every buffer and the selection), and
+    sampled rows of its head-parallel Q against the oracle chain."""
+    import torch
+    from synth import make_layer_inputs, perturb_tiles, sample_token_ids
+    cfg = CONFIGS[name]
+    print(f"fused three-stream step {name}", flush=True)
+    N, D, H, d, P, T, NT = cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, cfg.tile_tokens, cfg.NT
+    inp = make_layer_inputs(cfg)
+    X, Wq, Wk, Wv = (to_dev(inp[k_]) for k_ in ("X", "Wq", "Wk", "Wv"))
+    gq, gk = to_dev(inp["gamma_q"]), to_dev(inp["gamma_k"])
+    table = torch.from_numpy(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta)).to("cuda:0")
+    rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, table.data_ptr())
+    sh = cd.Shape.make(N, D, H, d, P)
+    ORDER = cd.RECV_MAJOR
+    ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device="cuda:0")
+
+    def fresh():
+        o = {k_: dev_empty((N, D)) for k_ in ("q", "k", "v", "bq", "bk", "bv")}
+        o.update({k_: dev_empty((H, N, d)) for k_ in ("hq", "hk", "hv")})
+        o.update(flags=dev_empty((NT,), "i32"), idx=dev_empty((NT,), "i32"), n=dev_empty((1,), "i32"), compact=dev_empty((H, NT * T, d)))
+        for t in o.values():
+            t.fill_(-1)
+        return o
+
+    # previous-step V: the stand-alone path's own head-parallel V with a seeded set of tiles perturbed
+    a = fresh()
+    cd.qkv_proj(sh, X, None, None, Wv, None, None, a["v"])
+    cd.a2a_pack(sh, a["v"], a["bv"], ORDER)
+    cd.a2a_unpack(sh, a["bv"], a["hv"], ORDER)
+    _sync()
+    prev_host, changed = perturb_tiles(to_host_bits(a["hv"]), 1, T, cfg.n_changed, np.random.default_rng(cfg.index), cfg.noise_sigma)
+    prev = to_dev(prev_host)
+
+    # stand-alone calls, one stream
+    cd.qkv_proj(sh, X, Wq, Wk, None, a["q"], a["k"], None)
+    cd.qk_norm_rope(sh, a["q"], a["k"], gq, gk, cfg.eps, rope)
+    for src, buf, dst in (("q", "bq", "hq"), ("k", "bk", "hk")):
+        cd.a2a_pack(sh, a[src], a[buf], ORDER)
+        cd.a2a_unpack(sh, a[buf], a[dst], ORDER)
+    cd.vmajor_select(H, N, d, T, a["hv"], prev, cfg.tau, a["flags"], a["idx"], a["n"], a["compact"], NT, ws)
+    _sync()
+
+    # fused entry points, three streams, V first
+    b = fresh()
+    s_v, s_qk, s_q = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    ws2 = torch.empty_like(ws)
+    torch.cuda.synchronize()
+    cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, b["bv"], ORDER, stream=s_v)
+    v_ready = torch.cuda.Event()
+    v_ready.record(s_v)
+    cd.a2a_unpack_select(sh, b["bv"], ORDER, b["hv"], prev, T, cfg.tau, b["flags"], b["idx"], b["n"], b["compact"], NT, ws2, stream=s_v)
+    s_qk.wait_event(v_ready)
+    cd.qkv_proj(sh, X, Wq, None, None, b["q"], None, None, stream=s_qk)
+    q_ready = torch.cuda.Event()
+    q_ready.record(s_qk)
+    cd.qkv_proj(sh, X, None, Wk, None, None, b["k"], None, stream=s_qk)
+    s_q.wait_event(q_ready)
+    cd.qk_norm_rope_pack(sh, b["q"], None, gq, None, cfg.eps, rope, b["bq"], None, ORDER, stream=s_q)
+    cd.a2a_unpack(sh, b["bq"], b["hq"], ORDER, stream=s_q)
+    cd.qk_norm_rope_pack(sh, None, b["k"], None, gk, cfg.eps, rope, None, b["bk"], ORDER, stream=s_qk)
+    cd.a2a_unpack(sh, b["bk"], b["hk"], ORDER, stream=s_qk)
+    torch.cuda.synchronize()
+
+    for key in ("bq", "bk", "bv", "hq", "hk", "hv", "flags"):
+        assert np.array_equal(a[key].cpu().numpy(), b[key].cpu().numpy()), key
+    n = int(a["n"].cpu()[0])
+    assert n == int(b["n"].cpu()[0]) == cfg.n_changed
+    assert np.array_equal(a["idx"].cpu().numpy()[:n], b["idx"].cpu().numpy()[:n])
+    assert np.array_equal(a["idx"].cpu().numpy()[:n], np.sort(changed))
+    assert np.array_equal(to_host_bits(a["compact"])[:, :n * T], to_host_bits(b["compact"])[:, :n * T])
+
+    # sampled rows of the fused path's head-parallel Q against the oracle: norm + RoPE of the GPU's own bf16 projection
+    ids = np.arange(N) if name == "C2" else sample_token_ids(cfg, random_tiles_per_rank=2)
+    q_proj = to_host_bits(b["q"])[ids].reshape(-1, H, d)           # the fused path leaves the projection itself in q
+    assert_float_parity(q_proj.reshape(len(ids), D), oracle.qkv_proj(inp["X"][ids], inp["Wq"]), f"fused step {name}: Q projection")
+    want = oracle.qk_norm_rope(q_proj, ids, inp["gamma_q"], cfg.eps, cfg.grid, cfg.pairs, cfg.theta)
+    got = to_host_bits(b["hq"]).transpose(1, 0, 2)[ids]
+    assert_float_parity(got, want, f"fused step {name}: head-parallel Q")
