@@ -311,16 +311,52 @@ def main() -> int:
                     ent["frac_copy_rate"] = round(nbytes / med / 1e3 / attainable["hbm_copy_GB/s"], 4)
             kernels[name] = ent
 
+        def sclk_during(fn, secs=1.2):
+            """Median shader clock (MHz) rocm-smi reports while `fn` keeps the GPU busy; None if it cannot be read."""
+            import re
+            import subprocess
+            import threading
+            seen, stop = [], threading.Event()
+
+            def sample():
+                while not stop.is_set():
+                    try:
+                        out = subprocess.run(["rocm-smi", "--showclocks", "--csv"], capture_output=True, text=True, timeout=10).stdout
+                        row = [l for l in out.strip().splitlines() if l.startswith("card0")]
+                        m = re.findall(r"\((\d+)Mhz\)", row[0]) if row else []
+                        if len(m) >= 2:
+                            seen.append((time.time(), int(m[1])))      # columns: mclk, sclk
+                    except Exception:
+                        return
+            th = threading.Thread(target=sample, daemon=True)
+            t_begin = time.time()
+            th.start()
+            while time.time() < t_begin + secs:
+                for _ in range(20):
+                    fn()
+                torch.cuda.synchronize()
+            stop.set()
+            th.join(timeout=15)
+            mine = [c for (ts, c) in seen if ts > t_begin + 0.3]       # the first samples still see the ramp
+            return int(np.median(mine)) if mine else None
+
         # what the chip attains on the two calibration kernels: a 1000 MiB copy and a register-only MFMA loop
         big = 1000 << 20   # not a power of two: source and destination must not alias onto the same HBM banks
         src_big = torch.empty(big + (3 << 20), dtype=torch.uint8, device=dev)
         dst_big = torch.empty(big, dtype=torch.uint8, device=dev)
         copy_us = timed([lambda: cd.util_copy(src_big, dst_big, big)])[0]
         del src_big, dst_big
+        src_big2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst_big2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         sink = torch.zeros(1, dtype=torch.float32, device=dev)
         mfma_flops = cd.util_mfma_rate(2048, 4096, sink)
         mfma_us = timed([lambda: cd.util_mfma_rate(2048, 4096, sink)])[0]
         attainable = {"hbm_copy_GB/s": round(2 * big / copy_us / 1e3, 1), "mfma_loop_TFLOP/s": round(mfma_flops / mfma_us / 1e6, 1)}
+        # the chip does not hold its top clock under matrix-core load: record what it runs at
+        attainable["sclk_MHz"] = {"copy": sclk_during(lambda: cd.util_copy(src_big2, dst_big2, 256 << 20)),
+                                  "mfma_loop": sclk_during(lambda: cd.util_mfma_rate(2048, 1024, sink)),
+                                  "projection": sclk_during(lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v))}
+        del src_big2, dst_big2
         log(f"  attainable on this GPU: {attainable}")
 
         g1 = 2.0 * N * D * D
@@ -369,6 +405,10 @@ def main() -> int:
                                          "frac_mfma_peak": round(attainable["mfma_loop_TFLOP/s"] / PEAK_BF16_TFLOPS, 4)}
         del sets, act
         roofline["frac_of_mfma_loop"] = round(achieved_tflops / attainable["mfma_loop_TFLOP/s"], 4)
+        if attainable["sclk_MHz"]["projection"]:
+            # the published peak is 2.4 GHz x 256 units x 4 SIMDs x 1024 flop/clk; the same at the clock the chip holds
+            roofline["sclk_MHz"] = attainable["sclk_MHz"]["projection"]
+            roofline["frac_at_sclk"] = round(achieved_tflops / (PEAK_BF16_TFLOPS * attainable["sclk_MHz"]["projection"] / 2400.0), 4)
         for name, ent in kernels.items():
             log(f"  {name:20s} {ent}")
 
