@@ -352,11 +352,6 @@ def main() -> int:
         mfma_flops = cd.util_mfma_rate(2048, 4096, sink)
         mfma_us = timed([lambda: cd.util_mfma_rate(2048, 4096, sink)])[0]
         attainable = {"hbm_copy_GB/s": round(2 * big / copy_us / 1e3, 1), "mfma_loop_TFLOP/s": round(mfma_flops / mfma_us / 1e6, 1)}
-        # the chip does not hold its top clock under matrix-core load: record what it runs at
-        attainable["sclk_MHz"] = {"copy": sclk_during(lambda: cd.util_copy(src_big2, dst_big2, 256 << 20)),
-                                  "mfma_loop": sclk_during(lambda: cd.util_mfma_rate(2048, 1024, sink)),
-                                  "projection": sclk_during(lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v))}
-        del src_big2, dst_big2
         log(f"  attainable on this GPU: {attainable}")
 
         g1 = 2.0 * N * D * D
@@ -404,6 +399,13 @@ def main() -> int:
         kernels["mfma_register_loop"] = {"us": round(mfma_us, 2), "TFLOP/s": attainable["mfma_loop_TFLOP/s"],
                                          "frac_mfma_peak": round(attainable["mfma_loop_TFLOP/s"] / PEAK_BF16_TFLOPS, 4)}
         del sets, act
+        # the chip does not hold its top clock under matrix-core load: record what it runs at (last: the throttled
+        # state lingers and would colour the timings above)
+        attainable["sclk_MHz"] = {"copy": sclk_during(lambda: cd.util_copy(src_big2, dst_big2, 256 << 20)),
+                                  "mfma_loop": sclk_during(lambda: cd.util_mfma_rate(2048, 1024, sink)),
+                                  "projection": sclk_during(lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v))}
+        del src_big2, dst_big2
+        log(f"  shader clock under load: {attainable['sclk_MHz']}")
         roofline["frac_of_mfma_loop"] = round(achieved_tflops / attainable["mfma_loop_TFLOP/s"], 4)
         if attainable["sclk_MHz"]["projection"]:
             # the published peak is 2.4 GHz x 256 units x 4 SIMDs x 1024 flop/clk; the same at the clock the chip holds
