@@ -485,3 +485,32 @@ def test_fused_three_stream_step_equals_standalone_calls_and_oracle(oracle, name
     want = oracle.qk_norm_rope(q_proj, ids, inp["gamma_q"], cfg.eps, cfg.grid, cfg.pairs, cfg.theta)
     got = to_host_bits(b["hq"]).transpose(1, 0, 2)[ids]
     assert_float_parity(got, want, f"fused step {name}: head-parallel Q")
+
+
+@gpu
+def test_unpack_select_degenerate_cases(oracle):
+    """Nothing changed, everything changed, and a compact buffer smaller than the list: same answers as the oracle."""
+    import torch
+    cfg = CONFIGS["C1"]
+    H, N, d, T, NT = cfg.H, cfg.N, cfg.d, cfg.tile_tokens, cfg.NT
+    sh = cd.Shape.make(N, cfg.D, H, d, cfg.P)
+    cur, prev, changed = make_v_pair(cfg, layout="hs")
+    from synth import bf16_bits_to_f32, f32_to_bf16_bits
+    everything = f32_to_bf16_bits(bf16_bits_to_f32(cur) + np.float32(1.0))
+    buf = dev_empty((N * cfg.D,))
+    cd.a2a_pack(sh, to_dev(np.ascontiguousarray(cur.transpose(1, 0, 2))), buf, cd.SEND_MAJOR)
+    ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device="cuda:0")
+    for prev_bits, cap in ((cur, NT), (everything, NT), (prev, 2), (prev, 1)):
+        hs = dev_empty((H, N, d))
+        flags, idx, n_act = dev_empty((NT,), "i32"), dev_empty((NT,), "i32"), dev_empty((1,), "i32")
+        compact = dev_empty((H, cap * T, d))
+        compact.fill_(-1)
+        cd.a2a_unpack_select(sh, buf, cd.SEND_MAJOR, hs, to_dev(prev_bits), T, cfg.tau, flags, idx, n_act, compact, cap, ws)
+        _sync()
+        o_flags, o_idx, o_n, o_comp = oracle.vmajor_select(cur, prev_bits, cfg.tau, T, cap_tiles=cap)
+        n = int(n_act.cpu()[0])
+        assert n == o_n and np.array_equal(flags.cpu().numpy(), o_flags) and np.array_equal(idx.cpu().numpy()[:n], o_idx[:n])
+        kept = min(n, cap)
+        assert np.array_equal(to_host_bits(compact)[:, :kept * T], o_comp[:, :kept * T])
+        assert np.all(to_host_bits(compact)[:, kept * T:] == 0xFFFF)          # nothing written beyond the capacity
+        assert np.array_equal(to_host_bits(hs), cur)
