@@ -345,13 +345,15 @@ def main() -> int:
         src_big = torch.empty(big + (3 << 20), dtype=torch.uint8, device=dev)
         dst_big = torch.empty(big, dtype=torch.uint8, device=dev)
         copy_us = timed([lambda: cd.util_copy(src_big, dst_big, big)])[0]
+        memcpy_us = timed([lambda: dst_big.copy_(src_big[:big])])[0]      # the runtime's own device-to-device copy
         del src_big, dst_big
         src_big2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst_big2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         sink = torch.zeros(1, dtype=torch.float32, device=dev)
         mfma_flops = cd.util_mfma_rate(2048, 4096, sink)
         mfma_us = timed([lambda: cd.util_mfma_rate(2048, 4096, sink)])[0]
-        attainable = {"hbm_copy_GB/s": round(2 * big / copy_us / 1e3, 1), "mfma_loop_TFLOP/s": round(mfma_flops / mfma_us / 1e6, 1)}
+        attainable = {"hbm_copy_GB/s": round(2 * big / copy_us / 1e3, 1), "runtime_memcpy_GB/s": round(2 * big / memcpy_us / 1e3, 1),
+                      "mfma_loop_TFLOP/s": round(mfma_flops / mfma_us / 1e6, 1)}
         log(f"  attainable on this GPU: {attainable}")
 
         g1 = 2.0 * N * D * D
