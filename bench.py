@@ -6,8 +6,10 @@ order of the paper's Section III-C (V is projected first and its layout change a
 Q and K work).  Default schedule "fused3", three HIP streams, every result of the path produced (exchange buffers,
 head-parallel Q, K, V, the selection's list and compact V):
   stream V : qkv_proj_pack(V -> exchange buffer) -> a2a_unpack_select(V, V_prev)
-  stream QK: [after V's projection] qkv_proj(Q) -> qkv_proj(K) -> qk_norm_rope_pack(K) -> a2a_unpack(K)
-  stream Q : [after Q's projection] qk_norm_rope_pack(Q) -> a2a_unpack(Q)
+  stream QK: [after V's projection] qkv_proj_pack(Q) -> qkv_proj_pack(K) -> a2a_unpack_norm_rope(K)
+  stream Q : [after Q's projection] a2a_unpack_norm_rope(Q)
+(norm + RoPE on the receiving side of the exchange; "fused3s" keeps it on the sending side: qkv_proj ->
+qk_norm_rope_pack -> a2a_unpack.)
 "vfirst3" is the same order through the stand-alone calls only (projection, norm+RoPE in place, pack, unpack,
 select as separate launches); the default run times it too and reports it as `standalone_calls_path`.
 "vfirst" projects Q and K in one launch on two streams; "serial" runs the stand-alone calls on one stream.
@@ -53,7 +55,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--schedule", default="fused3", choices=["vfirst", "vfirst3", "serial", "fused3"])
+    ap.add_argument("--schedule", default="fused3", choices=["vfirst", "vfirst3", "serial", "fused3", "fused3s"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     args = ap.parse_args()
@@ -200,7 +202,37 @@ def main() -> int:
         cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=st)
 
     def step_fused3(ev=None):
-        """The vfirst3 order with the fused calls: V's projection writes the exchange buffer itself, Q and K are
+        """V-First order with the fused calls: every projection writes its exchange buffer itself (no [N][D] tensor
+        exists), V's unpack carries the selection's flag pass, Q's and K's unpack carries norm + RoPE (done on the
+        receiving side).  6 launches and 7.2 tensor passes over HBM beside the projections, against 13 and 14.2."""
+        if ev:
+            ev[0].record(s_v)
+        cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
+        if ev:
+            ev[1].record(s_v)
+        v_ready = torch.cuda.Event()
+        v_ready.record(s_v)
+        cd.a2a_unpack_select(sh, bv, ORDER, hv, hv_prev, T, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
+        s_qk.wait_event(v_ready)
+        if ev:
+            ev[2].record(s_qk)
+        cd.qkv_proj_pack(sh, X, Wq, None, None, bq, None, None, ORDER, stream=s_qk)
+        q_ready = torch.cuda.Event()
+        q_ready.record(s_qk)
+        cd.qkv_proj_pack(sh, X, None, Wk, None, None, bk, None, ORDER, stream=s_qk)
+        if ev:
+            ev[3].record(s_qk)
+        s_q.wait_event(q_ready)
+        cd.a2a_unpack_norm_rope(sh, bq, None, hq, None, gq, None, cfg.eps, rope, ORDER, stream=s_q)
+        cd.a2a_unpack_norm_rope(sh, None, bk, None, hk, None, gk, cfg.eps, rope, ORDER, stream=s_qk)
+        done_q, done_k = torch.cuda.Event(), torch.cuda.Event()
+        done_q.record(s_q)
+        done_k.record(s_qk)
+        s_v.wait_event(done_q)
+        s_v.wait_event(done_k)
+
+    def step_fused3s(ev=None):
+        """Sender-side variant of fused3: V's projection writes the exchange buffer itself, Q and K are
         normalised and rotated on their way into theirs, V's unpack computes the selection's flags (5 fewer launches
         and 4 fewer passes over HBM per step)."""
         if ev:
@@ -231,7 +263,7 @@ def main() -> int:
         s_v.wait_event(done_q)
         s_v.wait_event(done_k)
 
-    schedules = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial, "fused3": step_fused3}
+    schedules = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial, "fused3": step_fused3, "fused3s": step_fused3s}
     step = schedules[args.schedule]
 
     def time_schedule(step_fn):
@@ -260,7 +292,7 @@ def main() -> int:
         log(f"  stand-alone calls (vfirst3 schedule): {standalone}")
 
     # dominant kernel: the projection GEMM (launched per step as V, then Q+K -- or V, Q, K in the vfirst3 order)
-    n_launch = 3 if args.schedule in ("vfirst3", "fused3") else 2
+    n_launch = 3 if args.schedule in ("vfirst3", "fused3", "fused3s") else 2
     gemm_ms = [(e[0].elapsed_time(e[1]), e[2].elapsed_time(e[3])) for e in events]
     gemm_ms_per_launch = float(np.mean([a + b for a, b in gemm_ms])) / n_launch
     flops_per_launch = 2.0 * N * (3 * D) * D / n_launch
@@ -381,6 +413,8 @@ def main() -> int:
 
         add("vmajor_select", each(lambda s_: cd.vmajor_select(H, N, d, T, s_["h"], s_["p"], cfg.tau, flags, idx, n_act, compact, cap, ws)),
             nbytes=(2 + f_act) * tensor_bytes)
+        add("a2a_unpack_norm_rope", each(lambda s_: cd.a2a_unpack_norm_rope(sh, s_["h"], s_["p"], s_["a"], s_["b"], gq, gk, cfg.eps, rope, ORDER)),
+            nbytes=4 * tensor_bytes)
         add("a2a_unpack_select", each(lambda s_: cd.a2a_unpack_select(sh, s_["b"], ORDER, s_["a"], s_["p"], T, cfg.tau, flags, idx, n_act, compact, cap, ws)),
             nbytes=(3 + f_act) * tensor_bytes)
         add("vmajor_token_metric", each(lambda s_: cd.vmajor_token_metric(H, N, d, s_["h"], s_["p"], metric)), nbytes=2 * tensor_bytes)

@@ -149,6 +149,20 @@ COCODIFF_API int cocodiff_a2a_unpack_select(const cocodiff_shape* shape, const c
                                             void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * cocodiff_a2a_unpack_norm_rope: normalisation and rotation moved to the receiver side of the first all-to-all.
+ * qbuf / kbuf hold the projection itself in chunk order (what cocodiff_qkv_proj_pack writes); the unpack pass
+ * applies RMSNorm and RoPE (same arithmetic as cocodiff_qk_norm_rope, token index taken from the chunk) while it
+ * moves the rows into q_hs / k_hs [H][N][d].  The result is bit-identical to cocodiff_qk_norm_rope followed by
+ * cocodiff_a2a_pack and cocodiff_a2a_unpack; the exchange buffer carries un-normalised values instead.  The rank
+ * range of `shape` names the RECEIVING ranks (head owners), as for cocodiff_a2a_unpack.  (qbuf, q_hs, gamma_q) or
+ * (kbuf, k_hs, gamma_k) may be NULL together = skip that tensor.  d/8 must be a power of two.
+ */
+COCODIFF_API int cocodiff_a2a_unpack_norm_rope(const cocodiff_shape* shape, const cocodiff_bf16* qbuf, const cocodiff_bf16* kbuf,
+                                               cocodiff_bf16* q_hs, cocodiff_bf16* k_hs,
+                                               const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                               const cocodiff_rope* rope, int slot_order, void* stream);
+
+/*
  * Step 3a -- pack (Section II-A all-to-all, sender side; Section III-B "tensor preparation").
  * x_seq [N][H][d] -> xbuf, P*P chunks of [N/P][H/P][d]:
  *   chunk(r->p)[n][hl][i] = x_seq[r*N/P + n][p*H/P + hl][i]   for SOURCE ranks r in the range.

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     a2a_pack,
     a2a_pack_hs,
     a2a_unpack,
+    a2a_unpack_norm_rope,
     a2a_unpack_select,
     a2a_unpack_seq,
     cache_active_count,

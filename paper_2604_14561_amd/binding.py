@@ -21,7 +21,7 @@ SEND_MAJOR, RECV_MAJOR = 0, 1
 
 EXPORTS = (
     "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack",
-    "cocodiff_a2a_unpack_select", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
+    "cocodiff_a2a_unpack_select", "cocodiff_a2a_unpack_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
     "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
@@ -95,6 +95,8 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_util_mfma_rate.restype = ctypes.c_int64
         L.cocodiff_a2a_unpack_select.argtypes = [sp, vp, ci, vp, vp, i32, f32, vp, vp, vp, vp, i32, vp, sz, vp]
         L.cocodiff_a2a_unpack_select.restype = ci
+        L.cocodiff_a2a_unpack_norm_rope.argtypes = [sp, vp, vp, vp, vp, vp, vp, f32, rp, ci, vp]
+        L.cocodiff_a2a_unpack_norm_rope.restype = ci
         L.cocodiff_qkv_proj_pack.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ci, vp]
         L.cocodiff_qk_norm_rope_pack.argtypes = [sp, vp, vp, vp, vp, ctypes.c_float, rp, vp, vp, ci, vp]
         for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
@@ -158,6 +160,13 @@ def qk_norm_rope_pack(shape: Shape, q, k, gamma_q, gamma_k, eps: float, rope: Ro
     _check(lib().cocodiff_qk_norm_rope_pack(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(gamma_q), _ptr(gamma_k),
                                             float(eps), ctypes.byref(rope), _ptr(qbuf), _ptr(kbuf), int(slot_order),
                                             _stream(stream)))
+
+
+def a2a_unpack_norm_rope(shape: Shape, qbuf, kbuf, q_hs, k_hs, gamma_q, gamma_k, eps: float, rope: Rope,
+                         slot_order: int = SEND_MAJOR, stream=None) -> None:
+    _check(lib().cocodiff_a2a_unpack_norm_rope(ctypes.byref(shape), _ptr(qbuf), _ptr(kbuf), _ptr(q_hs), _ptr(k_hs),
+                                               _ptr(gamma_q), _ptr(gamma_k), float(eps), ctypes.byref(rope),
+                                               int(slot_order), _stream(stream)))
 
 
 def a2a_unpack_select(shape: Shape, vbuf, slot_order: int, v_hs, v_prev, tile_tokens: int, tau: float, flags, active_idx,

@@ -47,6 +47,63 @@ __device__ __forceinline__ float group_sum(float v, uint32_t width) {
     return v;
 }
 
+// One 16-byte vector (8 elements = 4 rotary pairs) of a head row: RMSNorm over the row's d8 vectors (one per lane,
+// adjacent lanes), scale by gamma, rotate.  Every kernel that normalises goes through this function, so the same
+// row gives the same bits wherever it is done.
+__device__ __forceinline__ vec16 norm_rope_vec(const vec16& in, const float (&g)[8], const float (&cs_c)[4],
+                                               const float (&cs_s)[4], uint32_t d8, float inv_d, float eps) {
+    const uint32_t w[4] = {in.x, in.y, in.z, in.w};
+    float x[8];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = bf16_lo(w[i]);
+        x[2 * i + 1] = bf16_hi(w[i]);
+        ss += x[2 * i] * x[2 * i] + x[2 * i + 1] * x[2 * i + 1];
+    }
+    ss = group_sum(ss, d8);
+    const float rinv = 1.0f / sqrtf(ss * inv_d + eps);
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float e = x[2 * i] * rinv * g[2 * i];
+        const float od = x[2 * i + 1] * rinv * g[2 * i + 1];
+        o[i] = pack_bf16x2(e * cs_c[i] - od * cs_s[i], e * cs_s[i] + od * cs_c[i]);
+    }
+    return vec16{o[0], o[1], o[2], o[3]};
+}
+
+// gamma of the 8 elements of vector l of a head row, and (cos, sin) of its 4 pairs for the token with grid
+// coordinates `coord`
+__device__ __forceinline__ void load_gamma(const uint16_t* __restrict__ gamma, uint32_t l, float (&g)[8]) {
+    const vec16 gv = *reinterpret_cast<const vec16*>(gamma + l * 8);
+    g[0] = bf16_lo(gv.x); g[1] = bf16_hi(gv.x); g[2] = bf16_lo(gv.y); g[3] = bf16_hi(gv.y);
+    g[4] = bf16_lo(gv.z); g[5] = bf16_hi(gv.z); g[6] = bf16_lo(gv.w); g[7] = bf16_hi(gv.w);
+}
+
+__device__ __forceinline__ void load_cos_sin(const RopeDev& rope, uint32_t n, uint32_t l, float (&cs_c)[4], float (&cs_s)[4]) {
+    // grid coordinates of the token (last axis fastest)
+    uint32_t coord[3] = {0, 0, 0};
+    uint32_t rem = n;
+    for (int ax = rope.n_axes - 1; ax >= 0; --ax) {
+        const uint32_t gsz = (uint32_t)rope.grid[ax];
+        coord[ax] = rem % gsz;
+        rem /= gsz;
+    }
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        uint32_t j = l * 4 + jj;
+        int ax = 0;
+        while (ax < rope.n_axes - 1 && j >= (uint32_t)rope.pairs[ax]) {
+            j -= (uint32_t)rope.pairs[ax];
+            ++ax;
+        }
+        const float2 v = *reinterpret_cast<const float2*>(rope.cs + rope.offset[ax] + ((size_t)coord[ax] * rope.pairs[ax] + j) * 2);
+        cs_c[jj] = v.x;
+        cs_s[jj] = v.y;
+    }
+}
+
 constexpr int kMaxSteps = 8;
 
 template <int STEPS, bool NT_LD, bool NT_ST, bool PACK>   // STEPS 0 = any number of steps, taken kMaxSteps at a time
@@ -70,35 +127,9 @@ __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
     const uint32_t n = a.first_token + tok_local;
     const uint32_t l = lane % a.d8;        // vector index inside the head row; pairs 4l .. 4l+3
 
-    // gamma for this lane's 8 elements
-    const vec16 gv = *reinterpret_cast<const vec16*>(gamma + l * 8);
-    const float g[8] = {bf16_lo(gv.x), bf16_hi(gv.x), bf16_lo(gv.y), bf16_hi(gv.y),
-                        bf16_lo(gv.z), bf16_hi(gv.z), bf16_lo(gv.w), bf16_hi(gv.w)};
-
-    // grid coordinates of the token (last axis fastest) and the (cos, sin) of this lane's 4 pairs
-    uint32_t coord[3] = {0, 0, 0};
-    {
-        uint32_t rem = n;
-        for (int ax = a.rope.n_axes - 1; ax >= 0; --ax) {
-            const uint32_t gsz = (uint32_t)a.rope.grid[ax];
-            coord[ax] = rem % gsz;
-            rem /= gsz;
-        }
-    }
-    float cs_c[4], cs_s[4];
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-        uint32_t j = l * 4 + jj;
-        int ax = 0;
-        while (ax < a.rope.n_axes - 1 && j >= (uint32_t)a.rope.pairs[ax]) {
-            j -= (uint32_t)a.rope.pairs[ax];
-            ++ax;
-        }
-        const float2 v = *reinterpret_cast<const float2*>(
-            a.rope.cs + a.rope.offset[ax] + ((size_t)coord[ax] * a.rope.pairs[ax] + j) * 2);
-        cs_c[jj] = v.x;
-        cs_s[jj] = v.y;
-    }
+    float g[8], cs_c[4], cs_s[4];
+    load_gamma(gamma, l, g);
+    load_cos_sin(a.rope, n, l, cs_c, cs_s);
 
     vec16* row = reinterpret_cast<vec16*>(base) + (size_t)n * a.D8 + v_first;
     // PACK: vector v of token n = r*Ns + m goes to chunk (sender r, receiver p = v / row8), row m, column v % row8
@@ -115,39 +146,141 @@ __global__ void __launch_bounds__(256) norm_rope_kernel(NormRopeArgs a) {
 #pragma unroll
         for (int k = 0; k < UN; ++k) {
             if (!(STEPS || s0 + k < total_steps)) continue;
-            const uint32_t w[4] = {in[k].x, in[k].y, in[k].z, in[k].w};
-            float x[8];
-            float ss = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                x[2 * i] = bf16_lo(w[i]);
-                x[2 * i + 1] = bf16_hi(w[i]);
-                ss += x[2 * i] * x[2 * i] + x[2 * i + 1] * x[2 * i + 1];
-            }
-            ss = group_sum(ss, a.d8);
-            const float rinv = 1.0f / sqrtf(ss * a.inv_d + a.eps);
-            uint32_t o[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float e = x[2 * i] * rinv * g[2 * i];
-                const float od = x[2 * i + 1] * rinv * g[2 * i + 1];
-                o[i] = pack_bf16x2(e * cs_c[i] - od * cs_s[i], e * cs_s[i] + od * cs_c[i]);
-            }
+            const vec16 out = norm_rope_vec(in[k], g, cs_c, cs_s, a.d8, a.inv_d, a.eps);
             if (PACK) {
                 const uint32_t v = v_first + (s0 + k) * 64u;
                 const uint32_t p = v / a.row8, c = v - p * a.row8;
                 const size_t slot = a.recv_major ? (size_t)p * a.P + r_own : (size_t)r_own * a.P + p;
-                st_vec<NT_ST>(pbase + slot * a.chunk8 + (size_t)m_in * a.row8 + c, vec16{o[0], o[1], o[2], o[3]});
+                st_vec<NT_ST>(pbase + slot * a.chunk8 + (size_t)m_in * a.row8 + c, out);
             } else {
-                st_vec<NT_ST>(row + (size_t)(s0 + k) * 64, vec16{o[0], o[1], o[2], o[3]});
+                st_vec<NT_ST>(row + (size_t)(s0 + k) * 64, out);
             }
         }
+    }
+}
+
+// Receiver-side unpack of the first all-to-all with the normalisation and the rotation done on the way: walks the
+// head-parallel tensor [H][N][d] linearly over the head range of the launch, one vector per lane (a head row is d8
+// adjacent lanes), reads the vector from its chunk of the exchange buffer, which holds the projection as it came
+// out of the matrix cores.  The pass is HBM-bound, so the arithmetic rides along for nothing.
+struct UnpackNormArgs {
+    const uint16_t* buf[2];
+    uint16_t* hs[2];
+    const uint16_t* gamma[2];
+    uint32_t N, Ns, P, Hp, d8, row8, chunk8;
+    uint32_t first_head, n_heads;     // head range of the launch
+    int recv_major;
+    float inv_d, eps;
+    RopeDev rope;
+};
+
+constexpr int kUnpackHeads = 6;   // vectors a lane keeps in flight
+
+// A lane owns vector i8 of token n for every head of the launch's range, so gamma and the token's cos / sin are
+// fetched once per lane; kUnpackHeads heads are in flight at a time.
+template <bool NT_LD, bool NT_ST>
+__global__ void __launch_bounds__(256) unpack_norm_rope_kernel(UnpackNormArgs a) {
+    const uint32_t g = blockIdx.x * 256u + threadIdx.x;
+    if (g >= a.N * a.d8) return;           // whole head rows leave together: d8 divides 64
+    const vec16* __restrict__ buf = reinterpret_cast<const vec16*>(a.buf[blockIdx.y]);
+    vec16* __restrict__ hs = reinterpret_cast<vec16*>(a.hs[blockIdx.y]);
+    const uint32_t n = g / a.d8, i8 = g - n * a.d8;
+    const uint32_t r = n / a.Ns, m = n - r * a.Ns;
+    float gm[8], cs_c[4], cs_s[4];
+    load_gamma(a.gamma[blockIdx.y], i8, gm);
+    load_cos_sin(a.rope, n, i8, cs_c, cs_s);
+    const size_t head8 = (size_t)a.N * a.d8;
+    const size_t row_at = (size_t)m * a.row8 + i8;
+    for (uint32_t h0 = 0; h0 < a.n_heads; h0 += kUnpackHeads) {
+        vec16 in[kUnpackHeads];
+#pragma unroll
+        for (int u = 0; u < kUnpackHeads; ++u) {
+            if (h0 + u < a.n_heads) {
+                const uint32_t h = a.first_head + h0 + u;
+                const uint32_t p = h / a.Hp, hl = h - p * a.Hp;
+                const size_t slot = a.recv_major ? (size_t)p * a.P + r : (size_t)r * a.P + p;
+                in[u] = ld_vec<NT_LD>(buf + slot * a.chunk8 + row_at + hl * a.d8);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnpackHeads; ++u)
+            if (h0 + u < a.n_heads)
+                st_vec<NT_ST>(hs + (a.first_head + h0 + u) * head8 + g, norm_rope_vec(in[u], gm, cs_c, cs_s, a.d8, a.inv_d, a.eps));
     }
 }
 
 }  // namespace cocodiff
 
 using namespace cocodiff;
+
+static int fill_rope(const cocodiff_shape* shape, const cocodiff_rope* rope, const char* who, RopeDev* out) {
+    if (!rope || !rope->cs) return fail(COCODIFF_ERR_NULL, "%s: rope description or its table is NULL", who);
+    if (!aligned16(rope->cs)) return fail(COCODIFF_ERR_ALIGN, "%s: the rope table must be 16-byte aligned", who);
+    if (rope->n_axes < 1 || rope->n_axes > 3) return fail(COCODIFF_ERR_SHAPE, "%s: rope n_axes (%d) must be 1..3", who, rope->n_axes);
+    int64_t cells = 1, npairs = 0;
+    for (int ax = 0; ax < rope->n_axes; ++ax) {
+        if (rope->grid[ax] <= 0 || rope->pairs[ax] <= 0)
+            return fail(COCODIFF_ERR_SHAPE, "%s: rope axis %d needs positive grid and pairs", who, ax);
+        cells *= rope->grid[ax];
+        npairs += rope->pairs[ax];
+    }
+    if (cells != shape->N) return fail(COCODIFF_ERR_SHAPE, "%s: grid has %lld cells, N is %d", who, (long long)cells, shape->N);
+    if (npairs * 2 != shape->d) return fail(COCODIFF_ERR_SHAPE, "%s: rope pairs sum to %lld, d/2 is %d", who, (long long)npairs, shape->d / 2);
+    out->n_axes = rope->n_axes;
+    int32_t off = 0;
+    for (int ax = 0; ax < 3; ++ax) {
+        out->grid[ax] = ax < rope->n_axes ? rope->grid[ax] : 1;
+        out->pairs[ax] = ax < rope->n_axes ? rope->pairs[ax] : 0;
+        out->offset[ax] = off;
+        if (ax < rope->n_axes) off += rope->grid[ax] * rope->pairs[ax] * 2;
+    }
+    out->cs = rope->cs;
+    return COCODIFF_OK;
+}
+
+extern "C" int cocodiff_a2a_unpack_norm_rope(const cocodiff_shape* shape, const cocodiff_bf16* qbuf, const cocodiff_bf16* kbuf,
+                                             cocodiff_bf16* q_hs, cocodiff_bf16* k_hs,
+                                             const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                             const cocodiff_rope* rope, int slot_order, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != COCODIFF_OK) return rc;
+    if (!qbuf && !kbuf) return fail(COCODIFF_ERR_NULL, "unpack_norm_rope: qbuf and kbuf are both NULL");
+    if ((qbuf && (!q_hs || !gamma_q)) || (kbuf && (!k_hs || !gamma_k)))
+        return fail(COCODIFF_ERR_NULL, "unpack_norm_rope: a given buffer needs its output tensor and its gamma");
+    if (!aligned16(qbuf) || !aligned16(kbuf) || !aligned16(q_hs) || !aligned16(k_hs) || !aligned16(gamma_q) || !aligned16(gamma_k))
+        return fail(COCODIFF_ERR_ALIGN, "unpack_norm_rope: pointers must be 16-byte aligned");
+    if (slot_order != COCODIFF_SEND_MAJOR && slot_order != COCODIFF_RECV_MAJOR)
+        return fail(COCODIFF_ERR_SHAPE, "unpack_norm_rope: slot_order (%d) must be SEND_MAJOR or RECV_MAJOR", slot_order);
+    const uint32_t d8 = shape->d / 8;
+    if ((d8 & (d8 - 1)) || d8 > 64)
+        return fail(COCODIFF_ERR_SHAPE, "unpack_norm_rope: d (%d) must be 8 times a power of two, at most 512", shape->d);
+    if ((int64_t)shape->N * shape->D / 8 >= (int64_t)1 << 31) return fail(COCODIFF_ERR_SHAPE, "unpack_norm_rope: N*D/8 must be below 2^31");
+    UnpackNormArgs a;
+    rc = fill_rope(shape, rope, "unpack_norm_rope", &a.rope);
+    if (rc != COCODIFF_OK) return rc;
+    int nt = 0;
+    if (qbuf) { a.buf[nt] = qbuf; a.hs[nt] = q_hs; a.gamma[nt] = gamma_q; ++nt; }
+    if (kbuf) { a.buf[nt] = kbuf; a.hs[nt] = k_hs; a.gamma[nt] = gamma_k; ++nt; }
+    if (nt == 1) { a.buf[1] = a.buf[0]; a.hs[1] = a.hs[0]; a.gamma[1] = a.gamma[0]; }
+    a.N = (uint32_t)shape->N;
+    a.Ns = (uint32_t)(shape->N / shape->P);
+    a.P = (uint32_t)shape->P;
+    a.Hp = (uint32_t)(shape->H / shape->P);
+    a.d8 = d8;
+    a.row8 = a.Hp * d8;
+    a.chunk8 = a.Ns * a.row8;
+    a.first_head = (uint32_t)shape->rank_begin * a.Hp;
+    a.n_heads = (uint32_t)shape->rank_count * a.Hp;
+    a.recv_major = slot_order == COCODIFF_RECV_MAJOR;
+    a.inv_d = 1.0f / (float)shape->d;
+    a.eps = eps;
+    const dim3 grid((a.N * d8 + 255u) / 256u, nt), block(256);
+    const size_t touched = (size_t)nt * a.n_heads * a.N * d8 * 32;
+    with_policy(stream_loads_once(touched), stream_stores(touched), [&](auto L, auto S) {
+        hipLaunchKernelGGL((unpack_norm_rope_kernel<decltype(L)::value, decltype(S)::value>), grid, block, 0, as_stream(stream), a);
+    });
+    return check_launch("unpack_norm_rope_kernel");
+}
 
 // pack = false: in place on q / k.  pack = true: q / k are read, the result goes to qbuf / kbuf in chunk order.
 static int norm_rope_launch(const cocodiff_shape* shape, cocodiff_bf16* q, cocodiff_bf16* k,

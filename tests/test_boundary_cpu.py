@@ -159,3 +159,12 @@ def test_fused_entry_points_check_arguments_before_any_launch():
     assert g(ctypes.byref(s), None, None, None, None, 1e-6, ctypes.byref(rope), fake, fake, 0, None) == B.ERR_NULL
     assert g(ctypes.byref(s), fake, None, fake, None, 1e-6, ctypes.byref(rope), odd, None, 0, None) == B.ERR_ALIGN
     assert g(ctypes.byref(s), fake, None, fake, None, 1e-6, ctypes.byref(rope), fake, None, 4, None) == B.ERR_SHAPE
+    h = L.cocodiff_a2a_unpack_norm_rope
+    assert h(ctypes.byref(s), None, None, None, None, None, None, 1e-6, ctypes.byref(rope), 0, None) == B.ERR_NULL
+    assert h(ctypes.byref(s), fake, None, None, None, fake, None, 1e-6, ctypes.byref(rope), 0, None) == B.ERR_NULL    # no output
+    assert h(ctypes.byref(s), fake, None, fake, None, None, None, 1e-6, ctypes.byref(rope), 0, None) == B.ERR_NULL    # no gamma
+    assert h(ctypes.byref(s), fake, None, odd, None, fake, None, 1e-6, ctypes.byref(rope), 0, None) == B.ERR_ALIGN
+    assert h(ctypes.byref(s), fake, None, fake, None, fake, None, 1e-6, ctypes.byref(rope), 3, None) == B.ERR_SHAPE
+    assert h(ctypes.byref(s), fake, None, fake, None, fake, None, 1e-6, None, 0, None) == B.ERR_NULL
+    wrong = cd.Rope.make((16, 8), (16, 16), 10000.0, 0x1000)          # grid does not cover N
+    assert h(ctypes.byref(s), fake, None, fake, None, fake, None, 1e-6, ctypes.byref(wrong), 0, None) == B.ERR_SHAPE

@@ -321,6 +321,53 @@ def test_norm_rope_pack_equals_norm_rope_then_pack(oracle, name, order):
 
 
 @gpu
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C1", 1), ("C2", 1), ("C3", 1), ("C5", 0)])
+def test_unpack_norm_rope_equals_norm_rope_pack_unpack(oracle, name, order):
+    """Normalising on the receiver: raw rows in the exchange buffer, norm + RoPE inside the unpack pass."""
+    import torch
+    cfg = CONFIGS[name]
+    print(f"unpack_norm_rope {name} order {order}", flush=True)
+    from synth import f32_to_bf16_bits
+    rng = np.random.default_rng(cfg.index + 90)
+    N, D, H, d, P = cfg.N, cfg.D, cfg.H, cfg.d, cfg.P
+    q0 = f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32))
+    k0 = f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32) * np.float32(0.25))
+    gq = f32_to_bf16_bits((1 + 0.1 * rng.standard_normal(d)).astype(np.float32))
+    gk = f32_to_bf16_bits((1 + 0.1 * rng.standard_normal(d)).astype(np.float32))
+    table = torch.from_numpy(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta)).to("cuda:0")
+    rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, table.data_ptr())
+    sh = cd.Shape.make(N, D, H, d, P)
+    gqd, gkd = to_dev(gq), to_dev(gk)
+    # reference: the stand-alone calls
+    qd, kd = to_dev(q0), to_dev(k0)
+    bq, bk, hq, hk = dev_empty((N * D,)), dev_empty((N * D,)), dev_empty((H, N, d)), dev_empty((H, N, d))
+    cd.qk_norm_rope(sh, qd, kd, gqd, gkd, cfg.eps, rope)
+    for src, buf, dst in ((qd, bq, hq), (kd, bk, hk)):
+        cd.a2a_pack(sh, src, buf, order)
+        cd.a2a_unpack(sh, buf, dst, order)
+    # receiver side: raw rows packed, normalised while unpacking
+    rq, rk, fq, fk = dev_empty((N * D,)), dev_empty((N * D,)), dev_empty((H, N, d)), dev_empty((H, N, d))
+    cd.a2a_pack(sh, to_dev(q0), rq, order)
+    cd.a2a_pack(sh, to_dev(k0), rk, order)
+    for t in (fq, fk):
+        t.fill_(-1)
+    cd.a2a_unpack_norm_rope(sh, rq, rk, fq, fk, gqd, gkd, cfg.eps, rope, order)
+    _sync()
+    assert np.array_equal(to_host_bits(fq), to_host_bits(hq)) and np.array_equal(to_host_bits(fk), to_host_bits(hk))
+    # one tensor, one receiving rank: only that rank's heads are written
+    fk.fill_(-1)
+    p0 = P - 1
+    cd.a2a_unpack_norm_rope(cd.Shape.make(N, D, H, d, P, p0, 1), None, rk, None, fk, None, gkd, cfg.eps, rope, order)
+    _sync()
+    got = to_host_bits(fk)
+    assert np.array_equal(got[p0 * cfg.Hp:], to_host_bits(hk)[p0 * cfg.Hp:]) and np.all(got[:p0 * cfg.Hp] == 0xFFFF)
+    # the oracle on the first rank's tokens
+    ids = np.arange(cfg.Ns)
+    want = oracle.qk_norm_rope(q0[ids].reshape(-1, H, d), ids, gq, cfg.eps, cfg.grid, cfg.pairs, cfg.theta)
+    assert_float_parity(to_host_bits(fq).transpose(1, 0, 2)[ids], want, f"unpack_norm_rope {name}")
+
+
+@gpu
 @pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C5", 0)])
 def test_unpack_select_equals_unpack_then_select(oracle, name, order):
     import torch
@@ -477,6 +524,33 @@ def test_fused_three_stream_step_equals_standalone_calls_and_oracle(oracle, name
     assert np.array_equal(a["idx"].cpu().numpy()[:n], b["idx"].cpu().numpy()[:n])
     assert np.array_equal(a["idx"].cpu().numpy()[:n], np.sort(changed))
     assert np.array_equal(to_host_bits(a["compact"])[:, :n * T], to_host_bits(b["compact"])[:, :n * T])
+
+    # the benchmark's default: every projection straight into its exchange buffer, norm + RoPE on the receiving side
+    c = fresh()
+    ws3 = torch.empty_like(ws)
+    torch.cuda.synchronize()
+    cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, c["bv"], ORDER, stream=s_v)
+    v_ready = torch.cuda.Event()
+    v_ready.record(s_v)
+    cd.a2a_unpack_select(sh, c["bv"], ORDER, c["hv"], prev, T, cfg.tau, c["flags"], c["idx"], c["n"], c["compact"], NT, ws3, stream=s_v)
+    s_qk.wait_event(v_ready)
+    cd.qkv_proj_pack(sh, X, Wq, None, None, c["bq"], None, None, ORDER, stream=s_qk)
+    q_ready = torch.cuda.Event()
+    q_ready.record(s_qk)
+    cd.qkv_proj_pack(sh, X, None, Wk, None, None, c["bk"], None, ORDER, stream=s_qk)
+    s_q.wait_event(q_ready)
+    cd.a2a_unpack_norm_rope(sh, c["bq"], None, c["hq"], None, gq, None, cfg.eps, rope, ORDER, stream=s_q)
+    cd.a2a_unpack_norm_rope(sh, None, c["bk"], None, c["hk"], None, gk, cfg.eps, rope, ORDER, stream=s_qk)
+    torch.cuda.synchronize()
+    for key in ("bv", "hq", "hk", "hv", "flags"):
+        assert np.array_equal(a[key].cpu().numpy(), c[key].cpu().numpy()), key
+    assert int(c["n"].cpu()[0]) == n and np.array_equal(a["idx"].cpu().numpy()[:n], c["idx"].cpu().numpy()[:n])
+    assert np.array_equal(to_host_bits(a["compact"])[:, :n * T], to_host_bits(c["compact"])[:, :n * T])
+    # here the exchange buffers of Q and K carry the projection itself: pack(q) of the stand-alone projection
+    raw = dev_empty((N, D))
+    cd.a2a_pack(sh, b["q"], raw, ORDER)
+    _sync()
+    assert np.array_equal(to_host_bits(raw), to_host_bits(c["bq"]))
 
     # sampled rows of the fused path's head-parallel Q against the oracle: norm + RoPE of the GPU's own bf16 projection
     ids = np.arange(N) if name == "C2" else sample_token_ids(cfg, random_tiles_per_rank=2)
