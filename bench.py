@@ -413,10 +413,9 @@ def main() -> int:
 
         add("vmajor_select", each(lambda s_: cd.vmajor_select(H, N, d, T, s_["h"], s_["p"], cfg.tau, flags, idx, n_act, compact, cap, ws)),
             nbytes=(2 + f_act) * tensor_bytes)
-        add("a2a_unpack_norm_rope", each(lambda s_: cd.a2a_unpack_norm_rope(sh, s_["h"], s_["p"], s_["a"], s_["b"], gq, gk, cfg.eps, rope, ORDER)),
-            nbytes=4 * tensor_bytes)
         add("a2a_unpack_select", each(lambda s_: cd.a2a_unpack_select(sh, s_["b"], ORDER, s_["a"], s_["p"], T, cfg.tau, flags, idx, n_act, compact, cap, ws)),
             nbytes=(3 + f_act) * tensor_bytes)
+        assert int(n_act.cpu()[0]) == cfg.n_changed, "the breakdown's selection inputs were disturbed"
         add("vmajor_token_metric", each(lambda s_: cd.vmajor_token_metric(H, N, d, s_["h"], s_["p"], metric)), nbytes=2 * tensor_bytes)
         add("vmajor_topk", [lambda: cd.vmajor_topk(P, N // P, metric, k_act, tok_idx, tok_n)])   # every rank ranks its own tokens
         # rows after the hot path: sender-side gather / receiver-side scatter of the active tiles, second all-to-all
@@ -427,6 +426,8 @@ def main() -> int:
         add("a2a_pack", each(lambda s_: cd.a2a_pack(sh, s_["a"], s_["b"], ORDER)), nbytes=2 * tensor_bytes)
         add("a2a_unpack", each(lambda s_: cd.a2a_unpack(sh, s_["b"], s_["a"], ORDER)), nbytes=2 * tensor_bytes)
         add("qk_norm_rope", each(lambda s_: cd.qk_norm_rope(sh, s_["a"], s_["b"], gq, gk, cfg.eps, rope)), nbytes=4 * tensor_bytes)
+        add("a2a_unpack_norm_rope", each(lambda s_: cd.a2a_unpack_norm_rope(sh, s_["h"], s_["p"], s_["a"], s_["b"], gq, gk, cfg.eps, rope, ORDER)),
+            nbytes=4 * tensor_bytes)
         add("qk_norm_rope_pack", each(lambda s_: cd.qk_norm_rope_pack(sh, s_["h"], s_["p"], gq, gk, cfg.eps, rope, s_["a"], s_["b"], ORDER)),
             nbytes=4 * tensor_bytes)
         add("copy_same_bytes", each(lambda s_: cd.util_copy(s_["a"], s_["b"], tensor_bytes)), nbytes=2 * tensor_bytes)
