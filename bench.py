@@ -284,6 +284,29 @@ def main() -> int:
 
     ms_per_step, events = time_schedule(step)
     tokens_per_s = N / (ms_per_step * 1e-3)
+    # the same step replayed from a HIP graph (capture of the three streams): what is left when the host's launch
+    # work is taken out -- a check that the step is GPU-bound, and what a launch-bound small workload gains
+    graph_replay = None
+    if args.schedule == "fused3" and not args.no_breakdown:
+        try:
+            graph = torch.cuda.CUDAGraph()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=s_v):
+                step_fused3()
+            for _ in range(args.warmup):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            ms_g = (time.perf_counter() - t0) * 1e3 / args.steps
+            assert int(n_act.cpu()[0]) == cfg.n_changed
+            graph_replay = {"schedule": "fused3", "ms_per_step": round(ms_g, 4), "value": round(N / (ms_g * 1e-3), 1), "unit": "tokens/s"}
+            log(f"  HIP graph replay of the step: {graph_replay}")
+            del graph
+        except Exception as e:      # reported, never fatal: the headline is the eager step
+            log(f"  HIP graph replay not measured: {e}")
     # the same step through the stand-alone calls only (no fused entry point), reported beside the headline
     standalone = None
     if args.schedule == "fused3" and not args.no_breakdown:
@@ -513,6 +536,7 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
         "standalone_calls_path": standalone,
+        "hip_graph_replay": graph_replay,
         "attainable": attainable,
         "kernels": kernels,
     }

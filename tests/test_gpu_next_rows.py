@@ -588,3 +588,70 @@ def test_unpack_select_degenerate_cases(oracle):
         assert np.array_equal(to_host_bits(compact)[:, :kept * T], o_comp[:, :kept * T])
         assert np.all(to_host_bits(compact)[:, kept * T:] == 0xFFFF)          # nothing written beyond the capacity
         assert np.array_equal(to_host_bits(hs), cur)
+
+
+@gpu
+def test_fused_step_replays_from_a_hip_graph(oracle):
+    """Every call only enqueues on the caller's stream (no allocation, no synchronisation, no memset), so the whole
+    step can be captured into a HIP graph.  Replays, with eager work and synchronisations between them, must give
+    the eager result every time."""
+    import torch
+    from synth import make_layer_inputs, perturb_tiles
+    cfg = CONFIGS["C2"]
+    N, D, H, d, P, T, NT = cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, cfg.tile_tokens, cfg.NT
+    inp = make_layer_inputs(cfg)
+    X, Wq, Wk, Wv = (to_dev(inp[k_]) for k_ in ("X", "Wq", "Wk", "Wv"))
+    gq, gk = to_dev(inp["gamma_q"]), to_dev(inp["gamma_k"])
+    table = torch.from_numpy(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta)).to("cuda:0")
+    rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, table.data_ptr())
+    sh = cd.Shape.make(N, D, H, d, P)
+    ORDER = cd.RECV_MAJOR
+    ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device="cuda:0")
+    bq, bk, bv = (dev_empty((N * D,)) for _ in range(3))
+    hq, hk, hv = (dev_empty((H, N, d)) for _ in range(3))
+    flags, idx, n_act = dev_empty((NT,), "i32"), dev_empty((NT,), "i32"), dev_empty((1,), "i32")
+    compact = dev_empty((H, NT * T, d))
+
+    def step(stream):
+        cd.qkv_proj_pack(sh, X, Wq, Wk, Wv, bq, bk, bv, ORDER, stream=stream)
+        cd.a2a_unpack_select(sh, bv, ORDER, hv, prev, T, cfg.tau, flags, idx, n_act, compact, NT, ws, stream=stream)
+        cd.a2a_unpack_norm_rope(sh, bq, bk, hq, hk, gq, gk, cfg.eps, rope, ORDER, stream=stream)
+
+    def snapshot():
+        _sync()
+        n = int(n_act.cpu()[0])
+        return [to_host_bits(t).copy() for t in (bq, bk, bv, hq, hk, hv)] + [flags.cpu().numpy().copy(), idx.cpu().numpy()[:n].copy(),
+                                                                              n, to_host_bits(compact)[:, :n * T].copy()]
+
+    def clear():
+        for t in (bq, bk, bv, hq, hk, hv, flags, idx, n_act, compact):
+            t.fill_(-1)
+
+    # previous-step V from an eager run of the projection
+    prev = dev_empty((H, N, d))
+    prev.fill_(0)
+    clear()
+    step(None)                                 # eager, current stream: also sets the kernels' LDS attributes before any capture
+    _sync()
+    prev_host, changed = perturb_tiles(to_host_bits(hv), 1, T, cfg.n_changed, np.random.default_rng(5), cfg.noise_sigma)
+    prev.copy_(to_dev(prev_host))
+    clear()
+    step(None)
+    want = snapshot()
+    assert want[8] == cfg.n_changed and np.array_equal(want[7], np.sort(changed))
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        step(None)                             # the binding passes torch's current stream, which is the capturing one
+    for rep in range(3):
+        clear()
+        _sync()
+        graph.replay()
+        got = snapshot()
+        for g_, w_ in zip(got, want):
+            assert np.array_equal(g_, w_) if isinstance(w_, np.ndarray) else g_ == w_, rep
+        # eager work of the same kind between the replays
+        cd.qkv_proj_pack(sh, X, Wv, None, None, bq, None, None, ORDER)
+        _sync()
