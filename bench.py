@@ -366,21 +366,27 @@ def main() -> int:
                     ent["frac_copy_rate"] = round(nbytes / med / 1e3 / attainable["hbm_copy_GB/s"], 4)
             kernels[name] = ent
 
-        def sclk_during(fn, secs=1.2):
-            """Median shader clock (MHz) rocm-smi reports while `fn` keeps the GPU busy; None if it cannot be read."""
+        def chip_state_during(fn, secs=1.2):
+            """Median shader clock (MHz, rocm-smi) and socket power (W, hwmon) while `fn` keeps the GPU busy; a value
+            that cannot be read is None."""
+            import glob
             import re
             import subprocess
             import threading
-            seen, stop = [], threading.Event()
+            clocks, watts, stop = [], [], threading.Event()
+            hw = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")
 
             def sample():
                 while not stop.is_set():
                     try:
+                        if hw:
+                            with open(hw[0]) as f_:
+                                watts.append((time.time(), int(f_.read()) / 1e6))
                         out = subprocess.run(["rocm-smi", "--showclocks", "--csv"], capture_output=True, text=True, timeout=10).stdout
                         row = [l for l in out.strip().splitlines() if l.startswith("card0")]
                         m = re.findall(r"\((\d+)Mhz\)", row[0]) if row else []
                         if len(m) >= 2:
-                            seen.append((time.time(), int(m[1])))      # columns: mclk, sclk
+                            clocks.append((time.time(), int(m[1])))     # columns: mclk, sclk
                     except Exception:
                         return
             th = threading.Thread(target=sample, daemon=True)
@@ -392,8 +398,9 @@ def main() -> int:
                 torch.cuda.synchronize()
             stop.set()
             th.join(timeout=15)
-            mine = [c for (ts, c) in seen if ts > t_begin + 0.3]       # the first samples still see the ramp
-            return int(np.median(mine)) if mine else None
+            late = lambda xs: [v for (ts, v) in xs if ts > t_begin + 0.3]    # the first samples still see the ramp
+            return {"sclk_MHz": int(np.median(late(clocks))) if late(clocks) else None,
+                    "power_W": int(np.median(late(watts))) if late(watts) else None}
 
         # what the chip attains on the two calibration kernels: a 1000 MiB copy and a register-only MFMA loop
         big = 1000 << 20   # not a power of two: source and destination must not alias onto the same HBM banks
@@ -461,11 +468,13 @@ def main() -> int:
         del sets, act
         # the chip does not hold its top clock under matrix-core load: record what it runs at (last: the throttled
         # state lingers and would colour the timings above)
-        attainable["sclk_MHz"] = {"copy": sclk_during(lambda: cd.util_copy(src_big2, dst_big2, 256 << 20)),
-                                  "mfma_loop": sclk_during(lambda: cd.util_mfma_rate(2048, 1024, sink)),
-                                  "projection": sclk_during(lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v))}
+        state = {"copy": chip_state_during(lambda: cd.util_copy(src_big2, dst_big2, 256 << 20)),
+                 "mfma_loop": chip_state_during(lambda: cd.util_mfma_rate(2048, 1024, sink)),
+                 "projection": chip_state_during(lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v))}
+        attainable["sclk_MHz"] = {k_: v_["sclk_MHz"] for k_, v_ in state.items()}
+        attainable["power_W"] = {k_: v_["power_W"] for k_, v_ in state.items()}
         del src_big2, dst_big2
-        log(f"  shader clock under load: {attainable['sclk_MHz']}")
+        log(f"  chip state under load: clocks {attainable['sclk_MHz']} MHz, socket power {attainable['power_W']} W")
         roofline["frac_of_mfma_loop"] = round(achieved_tflops / attainable["mfma_loop_TFLOP/s"], 4)
         if attainable["sclk_MHz"]["projection"]:
             # the published peak is 2.4 GHz x 256 units x 4 SIMDs x 1024 flop/clk; the same at the clock the chip holds

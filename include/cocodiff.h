@@ -286,8 +286,8 @@ COCODIFF_API int cocodiff_rope_table_fill(const cocodiff_rope* rope, float* host
  * HBM-bound steps are priced against; used by the benchmark and the profiler-counter scaling. */
 COCODIFF_API int cocodiff_util_copy(const void* src, void* dst, size_t bytes, void* stream);
 
-/* Register-only matrix-core loop (v_mfma_f32_32x32x16_bf16 on per-lane pseudo-random operands, no memory
- * traffic): the calibration kernel the projection is priced against besides the published peak.  Launches
+/* Register-only matrix-core loop (v_mfma_f32_32x32x16_bf16 on pseudo-random operands that differ per lane and
+ * between consecutive MFMAs, no memory traffic): the calibration kernel the projection is priced against besides the published peak.  Launches
  * `blocks` workgroups of 4 wavefronts, each wavefront issuing iters * 8 MFMAs; `sink` is one DEVICE float that is
  * practically never written.  Returns the floating-point operations of the launch (> 0) or a negative error code;
  * the caller times the launch. */

@@ -64,18 +64,23 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float mfma_acc_t;
 
 constexpr int kMfmaChains = 8;   // independent accumulators per wavefront: hides the matrix core's result latency
 
-// Register-only loop of v_mfma_f32_32x32x16_bf16: no memory traffic, operands are small pseudo-random bf16 values
-// that differ per lane (constant operands draw less power and clock higher than real data does).
+// Register-only loop of v_mfma_f32_32x32x16_bf16: no memory traffic.  Every chain has its own pair of operand
+// registers, filled with small pseudo-random bf16 values that differ per lane and per chain, so consecutive MFMAs
+// see different operands as they do in a real product (with one operand pair for all chains, or constant operands,
+// the matrix cores draw less power and the chip clocks higher than it does on real data).
 __global__ void __launch_bounds__(256) mfma_rate_kernel(uint32_t iters, float* __restrict__ sink) {
     uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
-    union { uint16_t u[8]; mfma_in_t v; } a, b;
+    union Operand { uint16_t u[8]; mfma_in_t v; };
+    Operand a[kMfmaChains], b[kMfmaChains];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        h = h * 1664525u + 1013904223u;
-        a.u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));      // bf16 of magnitude 2^-7 .. 2, either sign
-        h = h * 1664525u + 1013904223u;
-        b.u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));
-    }
+    for (int c = 0; c < kMfmaChains; ++c)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            h = h * 1664525u + 1013904223u;
+            a[c].u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));   // bf16 of magnitude 2^-7 .. 2, either sign
+            h = h * 1664525u + 1013904223u;
+            b[c].u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));
+        }
     mfma_acc_t acc[kMfmaChains];
 #pragma unroll
     for (int c = 0; c < kMfmaChains; ++c)
@@ -83,7 +88,7 @@ __global__ void __launch_bounds__(256) mfma_rate_kernel(uint32_t iters, float* _
         for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
     for (uint32_t it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int c = 0; c < kMfmaChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc[c], 0, 0, 0);
+        for (int c = 0; c < kMfmaChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c].v, b[c].v, acc[c], 0, 0, 0);
     }
     float total = 0.f;
 #pragma unroll
