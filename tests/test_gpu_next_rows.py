@@ -655,3 +655,57 @@ def test_fused_step_replays_from_a_hip_graph(oracle):
         # eager work of the same kind between the replays
         cd.qkv_proj_pack(sh, X, Wv, None, None, bq, None, None, ORDER)
         _sync()
+
+
+@gpu
+def test_vmajor_token_loop_over_denoising_steps(oracle):
+    """The V-Major loop as the paper runs it, token-granular, over a 50-step schedule (5 warm-up steps, full update
+    every 10th): per step the L1 metric of every token against the receiver's cache, the top (1 - r) fraction per
+    rank, gather of the active tokens' values, scatter into the cache.  The cache and the active lists are compared
+    with the oracle's loop step by step (the integer decision on the GPU's own fp32 metric)."""
+    import torch
+    from synth import f32_to_bf16_bits, bf16_bits_to_f32
+    cfg = CONFIGS["C1"]
+    H, N, d, P = cfg.H, cfg.N, cfg.d, cfg.P
+    Ns = N // P
+    rng = np.random.default_rng(77)
+    v = rng.standard_normal((H, N, d), dtype=np.float32)
+    cache_host = np.zeros((H, N, d), dtype=np.uint16)               # the receiver's cached V (oracle's copy)
+    cache_dev = to_dev(cache_host.copy())
+    metric = torch.empty(N, dtype=torch.float32, device="cuda:0")
+    idx = dev_empty((N,), "i32")
+    n_act = dev_empty((P,), "i32")
+    n_steps, warmup, sync = 50, 5, 10
+    for step in list(range(1, 14)) + [20, 29, 30, 49, 50]:
+        # this step's V: the previous one plus a drift that is large on a random quarter of the tokens
+        drift = 0.02 * rng.standard_normal((H, N, d), dtype=np.float32)
+        hot = rng.random(N) < 0.25
+        drift[:, hot, :] *= 20.0
+        v = v + drift
+        cur = f32_to_bf16_bits(v)
+        cur_dev = to_dev(cur)
+        k = cd.cache_active_count(step, n_steps, warmup, sync, Ns)
+        assert k == oracle.active_count(step, n_steps, warmup, sync, Ns)
+        cd.vmajor_token_metric(H, N, d, cur_dev, cache_dev, metric)
+        idx.fill_(-1)
+        cd.vmajor_topk(P, Ns, metric, k, idx, n_act)
+        _sync()
+        got_metric = metric.cpu().numpy()
+        want_metric = oracle.token_l1_metric(cur, cache_host)
+        assert np.all(np.abs(got_metric - want_metric) <= 1e-4 * np.maximum(want_metric, 1e-3))
+        lists = idx.cpu().numpy().reshape(P, Ns)
+        for r in range(P):
+            want_list = oracle.topk_active(got_metric[r * Ns:(r + 1) * Ns], k)
+            assert np.array_equal(lists[r, :k], want_list), (step, r)
+            # the rank's active tokens: gather (sender), scatter into the cache (receiver), token-granular tiles
+            tok = (want_list + r * Ns).astype(np.int32)               # global token ids of this rank's list
+            tok_dev = to_dev(tok) if k else dev_empty((1,), "i32")
+            cnt = to_dev(np.array([k], dtype=np.int32))
+            comp = dev_empty((H, max(k, 1), d))
+            cd.vmajor_gather(H, N, d, 1, cur_dev, tok_dev, cnt, comp, max(k, 1))
+            cd.vmajor_scatter(H, N, d, 1, comp, tok_dev, cnt, cache_dev, max(k, 1))
+            cache_host = oracle.vmajor_scatter(oracle.vmajor_gather(cur, tok, 1, max(k, 1)), tok, cache_host, 1)
+        _sync()
+        assert np.array_equal(to_host_bits(cache_dev), cache_host), step
+        if k == Ns:                                                     # warm-up and every 10th step: full update
+            assert np.array_equal(cache_host, cur)
