@@ -238,12 +238,15 @@ COCODIFF_API int cocodiff_vmajor_token_metric(int32_t S, int32_t N, int32_t W, c
  * in every segment the n_keep tokens with the largest metric are active (the others stay cached).  NaN ranks
  * above every number; among equal metrics the lower token index is taken first, so the answer is unique.
  * metric [n_seg][N] fp32; active_idx [n_seg][N] int32: the first n_keep entries of row g receive segment g's
- * active token ids (local to the segment, ascending), the rest of the row is left alone; n_active [n_seg], every
- * entry = n_keep (all DEVICE; row g is in the form cocodiff_vmajor_gather / _scatter take with tile_tokens = 1).
+ * active token ids in ascending order, the rest of the row is left alone; the ids are local to the segment
+ * (0 .. N-1) when global_ids == 0 and positions in the whole metric array (g*N + local) otherwise; n_active [n_seg],
+ * every entry = n_keep (all DEVICE).  With global ids, (active_idx + g*N, n_active + g) is the list / count pair
+ * cocodiff_vmajor_gather and _scatter take with tile_tokens = 1 on the tensor the metric was computed from, so
+ * the chain metric -> top-k -> gather needs no host step.
  * Rules: n_seg, N > 0, n_seg * N < 2^31, 0 <= n_keep <= N.
  */
-COCODIFF_API int cocodiff_vmajor_topk(int32_t n_seg, int32_t N, const float* metric, int32_t n_keep, int32_t* active_idx,
-                                      int32_t* n_active, void* stream);
+COCODIFF_API int cocodiff_vmajor_topk(int32_t n_seg, int32_t N, const float* metric, int32_t n_keep, int32_t global_ids,
+                                      int32_t* active_idx, int32_t* n_active, void* stream);
 
 /*
  * Time-varying cache schedule (Section III-D), host arithmetic: number of active tokens at denoising step `step`

@@ -78,7 +78,7 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_vmajor_gather.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
         L.cocodiff_vmajor_scatter.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
         L.cocodiff_vmajor_token_metric.argtypes = [i32, i32, i32, vp, vp, vp, vp]
-        L.cocodiff_vmajor_topk.argtypes = [i32, i32, vp, i32, vp, vp, vp]
+        L.cocodiff_vmajor_topk.argtypes = [i32, i32, vp, i32, i32, vp, vp, vp]
         L.cocodiff_cache_active_count.argtypes = [i32, i32, i32, i32, i32]
         L.cocodiff_cache_active_count.restype = i32
         L.cocodiff_a2a_pack_hs.argtypes = [sp, vp, vp, ci, vp]
@@ -212,8 +212,9 @@ def vmajor_token_metric(S: int, N: int, W: int, v_cur, v_prev, metric, stream=No
     _check(lib().cocodiff_vmajor_token_metric(S, N, W, _ptr(v_cur), _ptr(v_prev), _ptr(metric), _stream(stream)))
 
 
-def vmajor_topk(n_seg: int, N: int, metric, n_keep: int, active_idx, n_active, stream=None) -> None:
-    _check(lib().cocodiff_vmajor_topk(int(n_seg), int(N), _ptr(metric), int(n_keep), _ptr(active_idx), _ptr(n_active), _stream(stream)))
+def vmajor_topk(n_seg: int, N: int, metric, n_keep: int, active_idx, n_active, stream=None, global_ids: bool = False) -> None:
+    _check(lib().cocodiff_vmajor_topk(int(n_seg), int(N), _ptr(metric), int(n_keep), int(bool(global_ids)),
+                                      _ptr(active_idx), _ptr(n_active), _stream(stream)))
 
 
 def cache_active_count(step: int, n_steps: int, warmup: int, sync_every: int, n_tokens: int) -> int:

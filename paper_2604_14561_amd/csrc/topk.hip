@@ -91,13 +91,15 @@ __device__ __forceinline__ uint32_t block_scan(uint32_t v, uint32_t* wave_tot, u
 // the metric; otherwise every pass reads the metric again (L2-resident).
 template <bool CACHED>
 __global__ void __launch_bounds__(kTopkThreads) topk_kernel(const float* __restrict__ metric, uint32_t N, uint32_t K,
-                                                            int32_t* __restrict__ idx, int32_t* __restrict__ n_active) {
+                                                            int32_t* __restrict__ idx, int32_t* __restrict__ n_active,
+                                                            uint32_t id_stride) {
     extern __shared__ uint32_t s_keys[];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_tot[kTopkThreads / 64];
     __shared__ uint32_t s_prefix, s_remaining;
     metric += (size_t)blockIdx.x * N;
     idx += (size_t)blockIdx.x * N;
+    const uint32_t id_base = blockIdx.x * id_stride;   // 0: ids local to the segment; N: ids in the whole metric array
     if (threadIdx.x == 0) n_active[blockIdx.x] = (int32_t)K;
     if (K == 0) return;
     if (CACHED) {
@@ -149,7 +151,7 @@ __global__ void __launch_bounds__(kTopkThreads) topk_kernel(const float* __restr
         const uint32_t key = key_at(n);
         const bool take = key > thr || (key == thr && eq_rank < remaining);
         eq_rank += key == thr;
-        if (take) idx[pos++] = (int32_t)n;
+        if (take) idx[pos++] = (int32_t)(id_base + n);
     }
 }
 
@@ -173,8 +175,8 @@ extern "C" int cocodiff_vmajor_token_metric(int32_t S, int32_t N, int32_t W, con
     return check_launch("token_metric_kernel");
 }
 
-extern "C" int cocodiff_vmajor_topk(int32_t n_seg, int32_t N, const float* metric, int32_t n_keep, int32_t* active_idx,
-                                    int32_t* n_active, void* stream) {
+extern "C" int cocodiff_vmajor_topk(int32_t n_seg, int32_t N, const float* metric, int32_t n_keep, int32_t global_ids,
+                                    int32_t* active_idx, int32_t* n_active, void* stream) {
     if (n_seg <= 0 || N <= 0) return fail(COCODIFF_ERR_SHAPE, "topk: n_seg and N must be positive");
     if ((int64_t)n_seg * N >= ((int64_t)1 << 31)) return fail(COCODIFF_ERR_SHAPE, "topk: n_seg * N must be below 2^31");
     if (n_keep < 0 || n_keep > N) return fail(COCODIFF_ERR_SHAPE, "topk: n_keep (%d) must be in [0, N = %d]", n_keep, N);
@@ -186,10 +188,10 @@ extern "C" int cocodiff_vmajor_topk(int32_t n_seg, int32_t N, const float* metri
         }();
         if (lds_ok != (int)hipSuccess) return fail(COCODIFF_ERR_HIP, "topk: cannot raise the kernel's LDS limit");
         hipLaunchKernelGGL(topk_kernel<true>, dim3(n_seg), dim3(kTopkThreads), (size_t)N * sizeof(uint32_t), as_stream(stream),
-                           metric, (uint32_t)N, (uint32_t)n_keep, active_idx, n_active);
+                           metric, (uint32_t)N, (uint32_t)n_keep, active_idx, n_active, global_ids ? (uint32_t)N : 0u);
     } else {
         hipLaunchKernelGGL(topk_kernel<false>, dim3(n_seg), dim3(kTopkThreads), 0, as_stream(stream), metric, (uint32_t)N,
-                           (uint32_t)n_keep, active_idx, n_active);
+                           (uint32_t)n_keep, active_idx, n_active, global_ids ? (uint32_t)N : 0u);
     }
     return check_launch("topk_kernel");
 }

@@ -439,11 +439,11 @@ def test_next_rows_argument_errors():
     assert L.cocodiff_vmajor_token_metric(4, 256, 60, fake, fake, fake, None) == B.ERR_SHAPE
     assert L.cocodiff_vmajor_token_metric(4, 256, 64, fake, None, fake, None) == B.ERR_NULL
     assert L.cocodiff_vmajor_token_metric(4, 256, 64, odd, fake, fake, None) == B.ERR_ALIGN
-    assert L.cocodiff_vmajor_topk(1, 256, fake, 257, fake, fake, None) == B.ERR_SHAPE
-    assert L.cocodiff_vmajor_topk(1, 256, fake, -1, fake, fake, None) == B.ERR_SHAPE
-    assert L.cocodiff_vmajor_topk(0, 256, fake, 5, fake, fake, None) == B.ERR_SHAPE
-    assert L.cocodiff_vmajor_topk(1 << 16, 1 << 16, fake, 5, fake, fake, None) == B.ERR_SHAPE
-    assert L.cocodiff_vmajor_topk(1, 256, None, 5, fake, fake, None) == B.ERR_NULL
+    assert L.cocodiff_vmajor_topk(1, 256, fake, 257, 0, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(1, 256, fake, -1, 0, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(0, 256, fake, 5, 0, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(1 << 16, 1 << 16, fake, 5, 1, fake, fake, None) == B.ERR_SHAPE
+    assert L.cocodiff_vmajor_topk(1, 256, None, 5, 0, fake, fake, None) == B.ERR_NULL
 
 
 # ---------------------------------------------------------------------------
@@ -688,24 +688,23 @@ def test_vmajor_token_loop_over_denoising_steps(oracle):
         assert k == oracle.active_count(step, n_steps, warmup, sync, Ns)
         cd.vmajor_token_metric(H, N, d, cur_dev, cache_dev, metric)
         idx.fill_(-1)
-        cd.vmajor_topk(P, Ns, metric, k, idx, n_act)
+        # device-only chain: global token ids, every rank's list and count handed on by pointer
+        cd.vmajor_topk(P, Ns, metric, k, idx, n_act, global_ids=True)
+        for r in range(P):
+            comp = dev_empty((H, max(k, 1), d))
+            cd.vmajor_gather(H, N, d, 1, cur_dev, idx[r * Ns:], n_act[r:], comp, max(k, 1))
+            cd.vmajor_scatter(H, N, d, 1, comp, idx[r * Ns:], n_act[r:], cache_dev, max(k, 1))
         _sync()
         got_metric = metric.cpu().numpy()
         want_metric = oracle.token_l1_metric(cur, cache_host)
         assert np.all(np.abs(got_metric - want_metric) <= 1e-4 * np.maximum(want_metric, 1e-3))
         lists = idx.cpu().numpy().reshape(P, Ns)
+        assert np.all(n_act.cpu().numpy() == k)
         for r in range(P):
             want_list = oracle.topk_active(got_metric[r * Ns:(r + 1) * Ns], k)
-            assert np.array_equal(lists[r, :k], want_list), (step, r)
-            # the rank's active tokens: gather (sender), scatter into the cache (receiver), token-granular tiles
             tok = (want_list + r * Ns).astype(np.int32)               # global token ids of this rank's list
-            tok_dev = to_dev(tok) if k else dev_empty((1,), "i32")
-            cnt = to_dev(np.array([k], dtype=np.int32))
-            comp = dev_empty((H, max(k, 1), d))
-            cd.vmajor_gather(H, N, d, 1, cur_dev, tok_dev, cnt, comp, max(k, 1))
-            cd.vmajor_scatter(H, N, d, 1, comp, tok_dev, cnt, cache_dev, max(k, 1))
+            assert np.array_equal(lists[r, :k], tok), (step, r)
             cache_host = oracle.vmajor_scatter(oracle.vmajor_gather(cur, tok, 1, max(k, 1)), tok, cache_host, 1)
-        _sync()
         assert np.array_equal(to_host_bits(cache_dev), cache_host), step
         if k == Ns:                                                     # warm-up and every 10th step: full update
             assert np.array_equal(cache_host, cur)
