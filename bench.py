@@ -3,16 +3,15 @@
 
 A step is one pass of the whole hot path over one synthetic layer input, all P logical ranks, in the V-First
 order of the paper's Section III-C (V is projected first and its layout change and selection run under the
-Q and K work).  Default schedule "fused3", three HIP streams, every result of the path produced (exchange buffers,
+Q and K work).  Default schedule "fused2", two HIP streams, every result of the path produced (exchange buffers,
 head-parallel Q, K, V, the selection's list and compact V):
   stream V : qkv_proj_pack(V -> exchange buffer) -> a2a_unpack_select(V, V_prev)
-  stream QK: [after V's projection] qkv_proj_pack(Q) -> qkv_proj_pack(K) -> a2a_unpack_norm_rope(K)
-  stream Q : [after Q's projection] a2a_unpack_norm_rope(Q)
-(norm + RoPE on the receiving side of the exchange; "fused3s" keeps it on the sending side: qkv_proj ->
-qk_norm_rope_pack -> a2a_unpack.)
-"vfirst3" is the same order through the stand-alone calls only (projection, norm+RoPE in place, pack, unpack,
-select as separate launches); the default run times it too and reports it as `standalone_calls_path`.
-"vfirst" projects Q and K in one launch on two streams; "serial" runs the stand-alone calls on one stream.
+  stream QK: [after V's projection] qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K)
+(norm + RoPE on the receiving side of the exchange).  "fused3" projects Q and K by two launches and uses a third
+stream; "fused3s" keeps norm + RoPE on the sending side: qkv_proj -> qk_norm_rope_pack -> a2a_unpack.
+"vfirst" / "vfirst3" are the same orders through the stand-alone calls only (projection, norm+RoPE in place, pack,
+unpack, select as separate launches); the default run times "vfirst" too and reports it as `standalone_calls_path`.
+"serial" runs the stand-alone calls on one stream.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line on stdout.
 """
 import argparse
@@ -55,7 +54,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--schedule", default="fused3", choices=["vfirst", "vfirst3", "serial", "fused3", "fused3s"])
+    ap.add_argument("--schedule", default="fused2", choices=["vfirst", "vfirst3", "serial", "fused2", "fused3", "fused3s"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     args = ap.parse_args()
@@ -201,6 +200,30 @@ def main() -> int:
             cd.a2a_unpack(sh, buf, dst, ORDER, stream=st)
         cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=st)
 
+    def step_fused2(ev=None):
+        """V-First on two streams with the fused calls: V's projection writes its exchange buffer, its unpack carries
+        the selection's flag pass; behind V's projection Q and K are projected by one launch straight into their
+        exchange buffers and normalised and rotated inside one unpack pass (receiving side).  4 launches and 7.2
+        tensor passes over HBM beside the projections, against 13 and 14.2 with the stand-alone calls."""
+        if ev:
+            ev[0].record(s_v)
+        cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
+        if ev:
+            ev[1].record(s_v)
+        v_ready = torch.cuda.Event()
+        v_ready.record(s_v)
+        cd.a2a_unpack_select(sh, bv, ORDER, hv, hv_prev, T, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
+        s_qk.wait_event(v_ready)            # V's projection goes first; its layout change overlaps what follows
+        if ev:
+            ev[2].record(s_qk)
+        cd.qkv_proj_pack(sh, X, Wq, Wk, None, bq, bk, None, ORDER, stream=s_qk)
+        if ev:
+            ev[3].record(s_qk)
+        cd.a2a_unpack_norm_rope(sh, bq, bk, hq, hk, gq, gk, cfg.eps, rope, ORDER, stream=s_qk)
+        done = torch.cuda.Event()
+        done.record(s_qk)
+        s_v.wait_event(done)                # join: the next layer cannot start before Q and K are laid out
+
     def step_fused3(ev=None):
         """V-First order with the fused calls: every projection writes its exchange buffer itself (no [N][D] tensor
         exists), V's unpack carries the selection's flag pass, Q's and K's unpack carries norm + RoPE (done on the
@@ -263,7 +286,8 @@ def main() -> int:
         s_v.wait_event(done_q)
         s_v.wait_event(done_k)
 
-    schedules = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial, "fused3": step_fused3, "fused3s": step_fused3s}
+    schedules = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial, "fused2": step_fused2, "fused3": step_fused3,
+                 "fused3s": step_fused3s}
     step = schedules[args.schedule]
 
     def time_schedule(step_fn):
@@ -287,12 +311,12 @@ def main() -> int:
     # the same step replayed from a HIP graph (capture of the three streams): what is left when the host's launch
     # work is taken out -- a check that the step is GPU-bound, and what a launch-bound small workload gains
     graph_replay = None
-    if args.schedule == "fused3" and not args.no_breakdown:
+    if args.schedule in ("fused2", "fused3") and not args.no_breakdown:
         try:
             graph = torch.cuda.CUDAGraph()
             torch.cuda.synchronize()
             with torch.cuda.graph(graph, stream=s_v):
-                step_fused3()
+                step()
             for _ in range(args.warmup):
                 graph.replay()
             torch.cuda.synchronize()
@@ -302,17 +326,18 @@ def main() -> int:
             torch.cuda.synchronize()
             ms_g = (time.perf_counter() - t0) * 1e3 / args.steps
             assert int(n_act.cpu()[0]) == cfg.n_changed
-            graph_replay = {"schedule": "fused3", "ms_per_step": round(ms_g, 4), "value": round(N / (ms_g * 1e-3), 1), "unit": "tokens/s"}
+            graph_replay = {"schedule": args.schedule, "ms_per_step": round(ms_g, 4), "value": round(N / (ms_g * 1e-3), 1), "unit": "tokens/s"}
             log(f"  HIP graph replay of the step: {graph_replay}")
             del graph
         except Exception as e:      # reported, never fatal: the headline is the eager step
             log(f"  HIP graph replay not measured: {e}")
     # the same step through the stand-alone calls only (no fused entry point), reported beside the headline
     standalone = None
-    if args.schedule == "fused3" and not args.no_breakdown:
-        ms_sa, _ = time_schedule(step_vfirst3)
-        standalone = {"schedule": "vfirst3", "ms_per_step": round(ms_sa, 4), "value": round(N / (ms_sa * 1e-3), 1), "unit": "tokens/s"}
-        log(f"  stand-alone calls (vfirst3 schedule): {standalone}")
+    if args.schedule in ("fused2", "fused3") and not args.no_breakdown:
+        sa_name = "vfirst" if args.schedule == "fused2" else "vfirst3"
+        ms_sa, _ = time_schedule(schedules[sa_name])
+        standalone = {"schedule": sa_name, "ms_per_step": round(ms_sa, 4), "value": round(N / (ms_sa * 1e-3), 1), "unit": "tokens/s"}
+        log(f"  stand-alone calls ({sa_name} schedule): {standalone}")
 
     # dominant kernel: the projection GEMM (launched per step as V, then Q+K -- or V, Q, K in the vfirst3 order)
     n_launch = 3 if args.schedule in ("vfirst3", "fused3", "fused3s") else 2

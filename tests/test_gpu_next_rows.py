@@ -546,6 +546,22 @@ def test_fused_three_stream_step_equals_standalone_calls_and_oracle(oracle, name
         assert np.array_equal(a[key].cpu().numpy(), c[key].cpu().numpy()), key
     assert int(c["n"].cpu()[0]) == n and np.array_equal(a["idx"].cpu().numpy()[:n], c["idx"].cpu().numpy()[:n])
     assert np.array_equal(to_host_bits(a["compact"])[:, :n * T], to_host_bits(c["compact"])[:, :n * T])
+    # the benchmark's default launch configuration: two streams, Q and K projected and unpacked by one launch each
+    e = fresh()
+    ws4 = torch.empty_like(ws)
+    torch.cuda.synchronize()
+    cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, e["bv"], ORDER, stream=s_v)
+    v_ready = torch.cuda.Event()
+    v_ready.record(s_v)
+    cd.a2a_unpack_select(sh, e["bv"], ORDER, e["hv"], prev, T, cfg.tau, e["flags"], e["idx"], e["n"], e["compact"], NT, ws4, stream=s_v)
+    s_qk.wait_event(v_ready)
+    cd.qkv_proj_pack(sh, X, Wq, Wk, None, e["bq"], e["bk"], None, ORDER, stream=s_qk)
+    cd.a2a_unpack_norm_rope(sh, e["bq"], e["bk"], e["hq"], e["hk"], gq, gk, cfg.eps, rope, ORDER, stream=s_qk)
+    torch.cuda.synchronize()
+    for key in ("bq", "bk", "bv", "hq", "hk", "hv", "flags"):
+        assert np.array_equal(c[key].cpu().numpy(), e[key].cpu().numpy()), key
+    assert int(e["n"].cpu()[0]) == n and np.array_equal(a["idx"].cpu().numpy()[:n], e["idx"].cpu().numpy()[:n])
+    assert np.array_equal(to_host_bits(a["compact"])[:, :n * T], to_host_bits(e["compact"])[:, :n * T])
     # here the exchange buffers of Q and K carry the projection itself: pack(q) of the stand-alone projection
     raw = dev_empty((N, D))
     cd.a2a_pack(sh, b["q"], raw, ORDER)
