@@ -25,7 +25,10 @@
  *     unless the comment says "host"; `shape`/`rope` structs are HOST pointers read
  *     during the call;
  *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
- *     stream); the call does not synchronise and does not allocate;
+ *     stream); the call does not synchronise, does not allocate and issues no memset, so a
+ *     sequence of calls can be captured into a HIP graph -- with one exception: the first
+ *     call of the projection entry points and of cocodiff_vmajor_topk in a process sets a
+ *     kernel attribute (LDS above 64 KB) and must happen outside a capture;
  *   - inputs are not modified; outputs must not alias inputs unless "in place" is stated;
  *   - bf16 values are raw 16-bit patterns (cocodiff_bf16); float arithmetic is fp32
  *     inside the kernels with one round-to-nearest-even to bf16 at each kernel's output.
