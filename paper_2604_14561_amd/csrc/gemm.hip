@@ -37,6 +37,7 @@ struct GemmArgs {
     int32_t row_begin, M;      // token rows [row_begin, row_begin + M)
     int32_t D;                 // features per tensor = K
     int32_t tiles_m, tiles_n_per_tensor;
+    int32_t bm, bn;            // tile of the launch: tokens x features
     // outputs in exchange-buffer (chunk) order instead of [N][D]: tokens per rank, ranks, 16-byte vectors per
     // chunk row and per chunk, slot order
     uint32_t Ns, P, row8, chunk8;
@@ -75,8 +76,8 @@ __device__ __forceinline__ TileCoord tile_of_block(const GemmArgs& a) {
     const uint32_t tn = in_grp / rows_here;
     TileCoord t;
     t.tensor = tn / a.tiles_n_per_tensor;
-    t.m0 = tm * BM;
-    t.f0 = (tn - t.tensor * a.tiles_n_per_tensor) * BN;
+    t.m0 = tm * (uint32_t)a.bm;
+    t.f0 = (tn - t.tensor * a.tiles_n_per_tensor) * (uint32_t)a.bn;
     return t;
 }
 
@@ -90,22 +91,24 @@ __device__ __forceinline__ void mfma_slice(f32x16 (&acc)[NI][4], const bf16x8 (&
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
 }
 
-// Round to bf16, transpose through this wavefront's private LDS region (128 token rows of NI*32 features),
+// Round to bf16, transpose through this wavefront's private LDS region (NJ*32 token rows of NI*32 features),
 // write whole rows.  Accumulator element e of lane l in MFMA tile (i, j): feature 32i + 8*(e/4) + 4*(l/32)
-// + e%4, token 32j + l%32.  16-byte column c of LDS row r is stored at column c ^ (r & (columns - 1)).
+// + e%4, token 32j + l%32.  An LDS row has CP >= NI*4 columns of 16 bytes, CP a power of two; column c of row r is
+// stored at column c ^ (r & (CP - 1)).
 // PACKED: the 8 features a lane writes for token n = r*Ns + m go to chunk (sender r, receiver p = feature / (Hp*d))
 // of the exchange buffer Y, row m (Hp*d is a multiple of 8, so a 16-byte vector never straddles two chunks).
-template <int NI, bool PACKED>
-__device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][4], unsigned char* ep, uint32_t lane,
+template <int NI, int NJ, bool PACKED>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane,
                                            uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
                                            uint32_t M, uint32_t D, const GemmArgs& a) {
-    constexpr uint32_t COLS = NI * 4;            // 16-byte columns per row
-    constexpr uint32_t ROWB = COLS * 16;         // bytes per row
+    constexpr uint32_t COLS = NI * 4;                                    // 16-byte columns in use per row
+    constexpr uint32_t CP = COLS <= 4 ? 4 : COLS <= 8 ? 8 : 16;          // columns per LDS row
+    constexpr uint32_t ROWB = CP * 16;                                   // bytes per LDS row
     const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const uint32_t row = 32u * j + frag_row;
@@ -114,19 +117,19 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][4], unsigned 
                 uint2 v;
                 v.x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
                 v.y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-                *reinterpret_cast<uint2*>(ep + row * ROWB + (((c16 ^ (row & (COLS - 1u))) << 4) | (half8 << 3))) = v;
+                *reinterpret_cast<uint2*>(ep + row * ROWB + (((c16 ^ (row & (CP - 1u))) << 4) | (half8 << 3))) = v;
             }
     // the same wavefront reads back what it wrote, and a wavefront's LDS accesses complete in order:
     // no workgroup barrier is needed
-    constexpr uint32_t RPI = 64 / COLS;          // rows per read instruction
-    const uint32_t c16 = lane % COLS, rsub = lane / COLS;
+    constexpr uint32_t RPI = 64 / CP;            // rows per read instruction
+    const uint32_t c16 = lane % CP, rsub = lane / CP;
 #pragma unroll 8
-    for (uint32_t it = 0; it < 128 / RPI; ++it) {
+    for (uint32_t it = 0; it < NJ * 32 / RPI; ++it) {
         const uint32_t row = RPI * it + rsub;
-        const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & (COLS - 1u))) << 4));
         const uint32_t tok = tok0 + row;
         const uint32_t feat = feat0 + c16 * 8u;
-        if (tok < M && feat < D) {
+        if (c16 < COLS && tok < M && feat < D) {
+            const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & (CP - 1u))) << 4));
             if (PACKED) {
                 const uint32_t n = (uint32_t)row0 + tok, r = n / a.Ns, m = n - r * a.Ns;
                 const uint32_t v8 = feat >> 3, p = v8 / a.row8, c = v8 - p * a.row8;
@@ -159,7 +162,8 @@ __device__ __forceinline__ void wait_loads() {
 // Instruction order inside a slice is pinned by a scheduling barrier after every instruction group.
 // ---------------------------------------------------------------------------------------------
 constexpr int kRingSlots = 5;
-constexpr int kRingLdsBytes = kRingSlots * kTileBytes;   // 160 KB
+constexpr int kRingLdsBytes256 = kRingSlots * 256 * BK * 2;   // 160 KB: tiles of 256 x 256
+constexpr int kRingLdsBytes192 = kRingSlots * 192 * BK * 2;   // 120 KB: tiles of 192 x 192
 
 __device__ __forceinline__ uint32_t ring_add(uint32_t slot, uint32_t n) {   // (slot + n) % 5 for n <= 5
     const uint32_t t = slot + n;
@@ -173,12 +177,17 @@ __device__ __forceinline__ void load_to_lds(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
 }
 
-template <int WN, bool PACKED>
+// Tile = (2 * NJ * 32) tokens x (WN * NI * 32) features, square: 256 x 256 with WN = 4, NI = 2, NJ = 4 (8 wavefronts
+// of 128 x 64) or 192 x 192 with WN = 2, NI = 3, NJ = 3 (4 wavefronts of 96 x 96).
+template <int WN, int NI, int NJ, bool PACKED>
 __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     constexpr int WAVES = 2 * WN;
-    constexpr int NI = BN / WN / 32;               // feature tiles per wavefront: 4 or 2
-    constexpr int NMFMA = NI * 4, NREAD = NI + 4;
-    constexpr int LOADS = 32 / WAVES;              // global->LDS instructions per lane per operand per step: 8 or 4
+    constexpr int TILE = 2 * NJ * 32;              // tokens = features per tile
+    static_assert(TILE == WN * NI * 32, "square tiles only: the ring slots of X and W have one size");
+    constexpr int kTileBytes = TILE * BK * 2;      // one operand tile of one K step
+    constexpr int NMFMA = NI * NJ, NREAD = NI + NJ;
+    constexpr int LOADS = TILE / 8 / WAVES;        // global->LDS instructions per lane per operand per step
+    static_assert(LOADS * WAVES * 8 == TILE && NMFMA > NREAD, "tile shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const TileCoord tc = tile_of_block(a);
@@ -186,7 +195,7 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     const uint32_t K = (uint32_t)a.D;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t wave_f = (wave % WN) * (NI * 32u), wave_t = (wave / WN) * 128u;
+    const uint32_t wave_f = (wave % WN) * (NI * 32u), wave_t = (wave / WN) * (NJ * 32u);
 
     // load i of this wavefront fills LDS rows (WAVES*i + wave)*8 .. +8 of a tile: lane -> row lane>>3, stored column lane&7
     const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x + ((size_t)a.row_begin + tc.m0) * K);
@@ -216,21 +225,21 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     const uint32_t x_frag = (wave_t + frag_row) * 128u;
     const uint32_t w_frag = (wave_f + frag_row) * 128u;
     // fragment r of slice kk of the step whose X tile sits in slot_x, in the order the MFMAs consume them:
-    // r = 0: W tile 0; r = 1..4: X tiles 0..3; r = 5..: W tiles 1..
-    auto read_frag = [&](uint32_t slot_x, uint32_t kk, int r, bf16x8 (&wf)[NI], bf16x8 (&xf)[4]) {
+    // r = 0: W tile 0; r = 1..NJ: X tiles; r = NJ+1..: W tiles 1..
+    auto read_frag = [&](uint32_t slot_x, uint32_t kk, int r, bf16x8 (&wf)[NI], bf16x8 (&xf)[NJ]) {
         const uint32_t col = ((2u * kk + frag_half) ^ sw) << 4;
         const unsigned char* xb = smem + slot_x * kTileBytes + x_frag + col;
         const unsigned char* wb = smem + ring_add(slot_x, 1) * kTileBytes + w_frag + col;
         if (r == 0) wf[0] = *reinterpret_cast<const bf16x8*>(wb);
-        else if (r <= 4) xf[r - 1] = *reinterpret_cast<const bf16x8*>(xb + (r - 1) * 4096);
-        else wf[r - 4] = *reinterpret_cast<const bf16x8*>(wb + (r - 4) * 4096);
+        else if (r <= NJ) xf[r - 1] = *reinterpret_cast<const bf16x8*>(xb + (r - 1) * 4096);
+        else wf[r - NJ] = *reinterpret_cast<const bf16x8*>(wb + (r - NJ) * 4096);
     };
 
-    f32x16 acc[NI][4];   // [feature tile][token tile]
+    f32x16 acc[NI][NJ];   // [feature tile][token tile]
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
@@ -243,14 +252,14 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     wait_loads<3 * LOADS>();       // step 0 has landed; X1, W1, X2 may still be in flight
     __syncthreads();
 
-    bf16x8 wf0[NI], xf0[4], wf1[NI], xf1[4];
+    bf16x8 wf0[NI], xf0[NJ], wf1[NI], xf1[NJ];
 #pragma unroll
     for (int r = 0; r < NREAD; ++r) read_frag(0, 0, r, wf0, xf0);
 
     // One slice: NMFMA MFMAs on (wf, xf); after MFMA m < NREAD the m-th fragment of the next slice is read into
     // (wf_n, xf_n); after MFMA NREAD + g the g-th of `n_loads` loads (first_load ...) of `base` is issued.
     // sched_barrier(0) after every instruction group keeps this order.
-    auto slice = [&](const bf16x8 (&wf)[NI], const bf16x8 (&xf)[4], bf16x8 (&wf_n)[NI], bf16x8 (&xf_n)[4], bool read_next,
+    auto slice = [&](const bf16x8 (&wf)[NI], const bf16x8 (&xf)[NJ], bf16x8 (&wf_n)[NI], bf16x8 (&xf_n)[NJ], bool read_next,
                      uint32_t slot_n, uint32_t kk_n, auto n_loads_c, const unsigned char* base,
                      const uint32_t (&off)[LOADS], uint32_t kt_l, uint32_t slot_l, int first_load) {
         constexpr int N_LOADS = decltype(n_loads_c)::value;
@@ -258,7 +267,7 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
         constexpr int PER = N_LOADS ? (N_LOADS + LOAD_SLOTS - 1) / LOAD_SLOTS : 0;
 #pragma unroll
         for (int m = 0; m < NMFMA; ++m) {
-            acc[m / 4][m % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[m / 4], xf[m % 4], acc[m / 4][m % 4], 0, 0, 0);
+            acc[m / NJ][m % NJ] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[m / NJ], xf[m % NJ], acc[m / NJ][m % NJ], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (m < NREAD) {
                 if (read_next) read_frag(slot_n, kk_n, m, wf_n, xf_n);
@@ -317,8 +326,10 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     advance();
     k_step(kt, slot, no{}, no{}, w0, no{});      // step n_k-1
     __syncthreads();
-    store_tile<NI, PACKED>(acc, smem + wave * (128 * NI * 64), lane, a.y[tc.tensor], (size_t)a.row_begin,
-                           tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
+    constexpr int kEpilogueBytes = NJ * 32 * (NI * 4 <= 4 ? 4 : NI * 4 <= 8 ? 8 : 16) * 16;   // per wavefront, see store_tile
+    static_assert(WAVES * kEpilogueBytes <= kRingSlots * kTileBytes, "the epilogue reuses the ring's LDS");
+    store_tile<NI, NJ, PACKED>(acc, smem + wave * kEpilogueBytes, lane, a.y[tc.tensor], (size_t)a.row_begin,
+                               tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -400,11 +411,10 @@ __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArg
         if (kt + 1 < n_k) store_stage(cur ^ 1u);
         __syncthreads();
     }
-    store_tile<4, PACKED>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t,
+    store_tile<4, 4, PACKED>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t,
                           tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
-constexpr int kMainWN = 4;   // 8 wavefronts per workgroup in the main kernel
 
 }  // namespace cocodiff
 
@@ -449,32 +459,58 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.row_begin = shape->rank_begin * Ns;
     a.M = shape->rank_count * Ns;
     a.D = shape->D;
-    a.tiles_m = (a.M + BM - 1) / BM;
-    a.tiles_n_per_tensor = (a.D + BN - 1) / BN;
-    const uint32_t n_tiles = (uint32_t)a.tiles_m * a.tiles_n_per_tensor * a.n_tensors;
     if ((int64_t)BM * a.D * 2 >= ((int64_t)1 << 32)) return fail(COCODIFF_ERR_SHAPE, "qkv_proj: D (%d) too large", a.D);
+    const bool ring_kernel = a.D % BK == 0 && a.D >= 3 * BK;
+
+    // Tile shape: 256 x 256 does the least operand traffic per flop; 192 x 192 is taken when its tile count fills
+    // the compute units so much better that it wins all the same (small token counts).  Cost = rounds x tile area,
+    // x 1.2 for the smaller tile (measured: per flop it is that much slower on this power-limited part, so three
+    // full rounds of it only tie with two ragged rounds of the large one), a round being one tile on every unit.
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, val = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&val, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || val <= 0)
+            return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
+        n_cu = val;
+    }
+    auto tiles_of = [&](int t) { return (int64_t)((a.M + t - 1) / t) * ((a.D + t - 1) / t) * a.n_tensors; };
+    auto rounds_of = [&](int t) { return (tiles_of(t) + n_cu - 1) / n_cu; };
+    const double cost256 = (double)rounds_of(256) * 256.0 * 256.0;
+    const double cost192 = (double)rounds_of(192) * 192.0 * 192.0 * 1.2;
+    static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);      // tuning knob: 192 or 256
+    const bool small_tile = ring_kernel && (forced_tile ? forced_tile == 192 : cost192 < cost256);
+    a.bm = a.bn = small_tile ? 192 : 256;
+    a.tiles_m = (a.M + a.bm - 1) / a.bm;
+    a.tiles_n_per_tensor = (a.D + a.bn - 1) / a.bn;
+    const uint32_t n_tiles = (uint32_t)a.tiles_m * a.tiles_n_per_tensor * a.n_tensors;
 
     static bool attr_set = false;   // dynamic LDS above 64 KB needs the attribute once per process
     if (!attr_set) {
         hipError_t e = hipSuccess;
-        const void* ring[2] = {(const void*)qkv_gemm_direct_kernel<kMainWN, false>, (const void*)qkv_gemm_direct_kernel<kMainWN, true>};
+        const void* big[2] = {(const void*)qkv_gemm_direct_kernel<4, 2, 4, false>, (const void*)qkv_gemm_direct_kernel<4, 2, 4, true>};
+        const void* small[2] = {(const void*)qkv_gemm_direct_kernel<2, 3, 3, false>, (const void*)qkv_gemm_direct_kernel<2, 3, 3, true>};
         const void* staged[2] = {(const void*)qkv_gemm_staged_kernel<false>, (const void*)qkv_gemm_staged_kernel<true>};
         for (int i = 0; i < 2 && e == hipSuccess; ++i) {
-            e = hipFuncSetAttribute(ring[i], hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes);
+            e = hipFuncSetAttribute(big[i], hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes256);
+            if (e == hipSuccess) e = hipFuncSetAttribute(small[i], hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes192);
             if (e == hipSuccess) e = hipFuncSetAttribute(staged[i], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         }
         if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(e));
         attr_set = true;
     }
-    const bool ring_kernel = a.D % BK == 0 && a.D >= 3 * BK;
-    if (ring_kernel && packed)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<kMainWN, true>), dim3(n_tiles), dim3(128 * kMainWN), kRingLdsBytes, as_stream(stream), a);
+    hipStream_t st = as_stream(stream);
+    if (ring_kernel && small_tile && packed)
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 3, 3, true>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
+    else if (ring_kernel && small_tile)
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 3, 3, false>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
+    else if (ring_kernel && packed)
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<4, 2, 4, true>), dim3(n_tiles), dim3(512), kRingLdsBytes256, st, a);
     else if (ring_kernel)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<kMainWN, false>), dim3(n_tiles), dim3(128 * kMainWN), kRingLdsBytes, as_stream(stream), a);
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<4, 2, 4, false>), dim3(n_tiles), dim3(512), kRingLdsBytes256, st, a);
     else if (packed)
-        hipLaunchKernelGGL(qkv_gemm_staged_kernel<true>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, as_stream(stream), a);
+        hipLaunchKernelGGL(qkv_gemm_staged_kernel<true>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, st, a);
     else
-        hipLaunchKernelGGL(qkv_gemm_staged_kernel<false>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, as_stream(stream), a);
+        hipLaunchKernelGGL(qkv_gemm_staged_kernel<false>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, st, a);
     return check_launch("qkv_gemm_kernel");
 }
 
