@@ -1,16 +1,18 @@
 // QKV projection (paper Section II-B): Y[n][o] = sum_k X[n][k] * W[o][k], bf16 in, fp32 accumulate on the
 // gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), one RNE rounding to bf16.
 //
-// Workgroup tile: 256 tokens x 256 features, K step 64 (a row segment of either operand is one whole
-// 128-byte line; half lines halve the L1 fill rate).  W rides the MFMA "A" side, so an accumulator lane
+// Workgroup tile: 256 tokens x 256 features (192 x 192 when that fills the compute units much better: small
+// token counts), K step 64 (a row segment of either operand is one whole 128-byte line; half lines halve the L1
+// fill rate).  W rides the MFMA "A" side, so an accumulator lane
 // holds four consecutive features of one token.  Both operands are K-contiguous; LDS tiles keep rows
 // contiguous and store 16-byte column c of row r at column c ^ swz(r), which makes the 128-bit fragment
 // reads bank-conflict free.
 //
 // Main kernel (K a multiple of 64): global -> LDS directly (no staging registers) through a ring of five
-// 32 KB slots (X and W tiles of a step travel separately).  WN wavefronts along the features x 2 along the
-// tokens: WN = 4 gives 8 wavefronts of 128 x 64 outputs, two per SIMD, so one can multiply while the
-// other waits for LDS, memory or the barrier.
+// slots (X and W tiles of a step travel separately; 32 KB each for the 256 x 256 tile).  WN wavefronts along the
+// features x 2 along the tokens: WN = 4 gives 8 wavefronts of 128 x 64 outputs, two per SIMD, so one can multiply
+// while the other waits for LDS, memory or the barrier.  The epilogue writes [N][D] rows or, for the fused call,
+// the rows' pieces straight into their chunks of the exchange buffer.
 // Fallback kernel (any K that is a multiple of 8): global -> registers -> LDS, zero-filled K tail.
 // The epilogue rounds to bf16, transposes through the (now idle) LDS and writes whole rows.
 #include <type_traits>

@@ -6,6 +6,9 @@
 // D8/64 steps, or 64/D8 short tokens in one step.  In both cases a lane keeps the same position inside
 // its head and the same token for every step, so gamma and the token's cos/sin values are fetched
 // once per lane and reused for every head.  HBM traffic: each element read once and written once.
+// Variants of the same arithmetic (one shared device function): the result stored into the exchange buffer's
+// chunks instead of in place (sender side), or the rows read from the chunks and stored head-parallel (receiver
+// side: the unpack of the first all-to-all with norm + RoPE inside).
 #include "internal.h"
 
 namespace cocodiff {

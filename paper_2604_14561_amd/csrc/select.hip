@@ -10,6 +10,9 @@
 //                   the last tile's workgroup also writes n_active.
 // HBM traffic: 2 tensors read once + the active fraction read once more and written once (the flags,
 // 4 bytes per tile, are re-read by the flagged workgroups out of L2).
+// The flag pass can take the current values from the exchange buffer of the first all-to-all instead and write
+// the head-parallel tensor on the way (the receiver's unpack and the selection in one pass).
+// The same file holds the gather / scatter of listed tiles (sender-side extraction, receiver-side overwrite).
 #include "internal.h"
 
 namespace cocodiff {
