@@ -168,3 +168,14 @@ def test_fused_entry_points_check_arguments_before_any_launch():
     assert h(ctypes.byref(s), fake, None, fake, None, fake, None, 1e-6, None, 0, None) == B.ERR_NULL
     wrong = cd.Rope.make((16, 8), (16, 16), 10000.0, 0x1000)          # grid does not cover N
     assert h(ctypes.byref(s), fake, None, fake, None, fake, None, 1e-6, ctypes.byref(wrong), 0, None) == B.ERR_SHAPE
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No fallback: without the built HIP library the binding raises instead of computing anything elsewhere."""
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libcocodiff.so"))
+    with pytest.raises(Exception) as err:
+        B.lib()
+    assert "libcocodiff.so" in str(err.value)
+    monkeypatch.undo()
+    assert B.lib() is not None

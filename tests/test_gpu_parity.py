@@ -478,3 +478,60 @@ def test_two_runs_are_bit_identical(oracle):
     r2 = _run_select(cur, prev, cfg.tau, cfg.tile_tokens)
     assert r1[2] == r2[2] and np.array_equal(r1[1][:r1[2]], r2[1][:r2[2]]) and np.array_equal(r1[0], r2[0])
     assert np.array_equal(r1[3][:, :r1[2] * cfg.tile_tokens], r2[3][:, :r2[2] * cfg.tile_tokens])
+
+
+# ---------------------------------------------------------------------------
+# no entry point writes outside its outputs
+# ---------------------------------------------------------------------------
+
+def test_outputs_are_written_inside_their_bounds_only(oracle):
+    """Every output sits between two guard bands inside one larger allocation; after the calls the bands still hold
+    their fill pattern.  Shapes off the tile grid (528 tokens, D = 512) and the tiny workload."""
+    import torch
+    GUARD = 4096                                       # int16 elements on either side
+
+    class Guarded:
+        def __init__(self, n_elems, dtype=torch.int16):
+            self.raw = torch.full((n_elems + 2 * GUARD,), 0x5A5A if dtype == torch.int16 else 0x5A5A5A5A, dtype=dtype, device="cuda:0")
+            self.t = self.raw[GUARD:GUARD + n_elems]
+            self.fill = int(self.raw[0].cpu())
+
+        def intact(self):
+            r = self.raw.cpu().numpy()
+            return bool(np.all(r[:GUARD] == self.fill) and np.all(r[-GUARD:] == self.fill))
+
+    for N, H, d, P, grid, pairs in ((528, 8, 64, 1, (22, 24), (16, 16)), (256, 4, 64, 2, (16, 16), (16, 16))):
+        D, T = H * d, 16
+        NT = N // T
+        sh = cd.Shape.make(N, D, H, d, P)
+        rng = np.random.default_rng(N)
+        x = to_dev(f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32)))
+        w = to_dev(f32_to_bf16_bits(rng.standard_normal((D, D), dtype=np.float32) * np.float32(D ** -0.5)))
+        g = to_dev(f32_to_bf16_bits(np.ones(d, dtype=np.float32)))
+        table = torch.from_numpy(cd.rope_table(grid, pairs, 10000.0)).to("cuda:0")
+        rope = cd.Rope.make(grid, pairs, 10000.0, table.data_ptr())
+        outs = {k_: Guarded(N * D) for k_ in ("q", "k", "v", "bq", "bk", "bv", "hq", "hk", "hv", "compact", "seq2")}
+        ints = {k_: Guarded(n_, torch.int32) for k_, n_ in (("flags", NT), ("idx", NT), ("n", 1), ("tok_idx", N), ("tok_n", P))}
+        metric = Guarded(N, torch.float32)
+        ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device="cuda:0")
+        o = {k_: v_.t for k_, v_ in outs.items()}
+        i_ = {k_: v_.t for k_, v_ in ints.items()}
+        cd.qkv_proj(sh, x, w, w, w, o["q"], o["k"], o["v"])
+        cd.qk_norm_rope(sh, o["q"], o["k"], g, g, 1e-6, rope)
+        cd.a2a_pack(sh, o["v"], o["bv"], cd.RECV_MAJOR)
+        cd.a2a_unpack(sh, o["bv"], o["hv"], cd.RECV_MAJOR)
+        cd.qkv_proj_pack(sh, x, w, w, None, o["bq"], o["bk"], None, cd.RECV_MAJOR)
+        cd.a2a_unpack_norm_rope(sh, o["bq"], o["bk"], o["hq"], o["hk"], g, g, 1e-6, rope, cd.RECV_MAJOR)
+        cd.qk_norm_rope_pack(sh, o["q"], o["k"], g, g, 1e-6, rope, o["bq"], o["bk"], cd.SEND_MAJOR)
+        prev = o["hq"]                                  # any tensor of the right shape: most tiles differ
+        cd.vmajor_select(H, N, d, T, o["hv"], prev, 1e-3, i_["flags"], i_["idx"], i_["n"], o["compact"], NT, ws)
+        cd.a2a_unpack_select(sh, o["bv"], cd.RECV_MAJOR, o["hv"], prev, T, 1e-3, i_["flags"], i_["idx"], i_["n"], o["compact"], NT, ws)
+        cd.vmajor_gather(H, N, d, T, o["hv"], i_["idx"], i_["n"], o["compact"], NT)
+        cd.vmajor_scatter(H, N, d, T, o["compact"], i_["idx"], i_["n"], o["hk"], NT)
+        cd.a2a_pack_hs(sh, o["hv"], o["bv"], cd.SEND_MAJOR)
+        cd.a2a_unpack_seq(sh, o["bv"], o["seq2"], cd.SEND_MAJOR)
+        cd.vmajor_token_metric(H, N, d, o["hv"], prev, metric.t)
+        cd.vmajor_topk(P, N // P, metric.t, (N // P) // 3, i_["tok_idx"], i_["tok_n"], global_ids=True)
+        _sync()
+        for name, gd in list(outs.items()) + list(ints.items()) + [("metric", metric)]:
+            assert gd.intact(), (N, name)
