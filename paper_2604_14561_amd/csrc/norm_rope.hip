@@ -172,6 +172,7 @@ struct UnpackNormArgs {
     const uint16_t* gamma[2];
     uint32_t N, Ns, P, Hp, d8, row8, chunk8;
     uint32_t first_head, n_heads;     // head range of the launch
+    uint32_t heads_per_z;             // heads one workgroup handles (blockIdx.z walks the range in such groups)
     int recv_major;
     float inv_d, eps;
     RopeDev rope;
@@ -194,11 +195,12 @@ __global__ void __launch_bounds__(256) unpack_norm_rope_kernel(UnpackNormArgs a)
     load_cos_sin(a.rope, n, i8, cs_c, cs_s);
     const size_t head8 = (size_t)a.N * a.d8;
     const size_t row_at = (size_t)m * a.row8 + i8;
-    for (uint32_t h0 = 0; h0 < a.n_heads; h0 += kUnpackHeads) {
+    const uint32_t h_end = min(a.n_heads, (blockIdx.z + 1u) * a.heads_per_z);
+    for (uint32_t h0 = blockIdx.z * a.heads_per_z; h0 < h_end; h0 += kUnpackHeads) {
         vec16 in[kUnpackHeads];
 #pragma unroll
         for (int u = 0; u < kUnpackHeads; ++u) {
-            if (h0 + u < a.n_heads) {
+            if (h0 + u < h_end) {
                 const uint32_t h = a.first_head + h0 + u;
                 const uint32_t p = h / a.Hp, hl = h - p * a.Hp;
                 const size_t slot = a.recv_major ? (size_t)p * a.P + r : (size_t)r * a.P + p;
@@ -207,7 +209,7 @@ __global__ void __launch_bounds__(256) unpack_norm_rope_kernel(UnpackNormArgs a)
         }
 #pragma unroll
         for (int u = 0; u < kUnpackHeads; ++u)
-            if (h0 + u < a.n_heads)
+            if (h0 + u < h_end)
                 st_vec<NT_ST>(hs + (a.first_head + h0 + u) * head8 + g, norm_rope_vec(in[u], gm, cs_c, cs_s, a.d8, a.inv_d, a.eps));
     }
 }
@@ -277,7 +279,9 @@ extern "C" int cocodiff_a2a_unpack_norm_rope(const cocodiff_shape* shape, const 
     a.recv_major = slot_order == COCODIFF_RECV_MAJOR;
     a.inv_d = 1.0f / (float)shape->d;
     a.eps = eps;
-    const dim3 grid((a.N * d8 + 255u) / 256u, nt), block(256);
+    static const uint32_t hpz = (uint32_t)tune_value("COCODIFF_UNPACK_HPZ", kUnpackHeads);   // measured best: one batch per lane
+    a.heads_per_z = hpz < 1 ? 1 : hpz;
+    const dim3 grid((a.N * d8 + 255u) / 256u, nt, (a.n_heads + a.heads_per_z - 1) / a.heads_per_z), block(256);
     const size_t touched = (size_t)nt * a.n_heads * a.N * d8 * 32;
     with_policy(stream_loads_once(touched), stream_stores(touched), [&](auto L, auto S) {
         hipLaunchKernelGGL((unpack_norm_rope_kernel<decltype(L)::value, decltype(S)::value>), grid, block, 0, as_stream(stream), a);
