@@ -468,13 +468,13 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     // the compute units so much better that it wins all the same (small token counts).  Cost = rounds x tile area,
     // x 1.2 for the smaller tile (measured: per flop it is that much slower on this power-limited part, so three
     // full rounds of it only tie with two ragged rounds of the large one), a round being one tile on every unit.
-    static int n_cu = 0;
-    if (n_cu == 0) {
+    static const int n_cu = [] {     // asked once (thread-safe initialisation); 0 = could not be read
         int dev = 0, val = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&val, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || val <= 0)
-            return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
-        n_cu = val;
-    }
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&val, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        return val;
+    }();
+    if (n_cu <= 0) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
     auto tiles_of = [&](int t) { return (int64_t)((a.M + t - 1) / t) * ((a.D + t - 1) / t) * a.n_tensors; };
     auto rounds_of = [&](int t) { return (tiles_of(t) + n_cu - 1) / n_cu; };
     const double cost256 = (double)rounds_of(256) * 256.0 * 256.0;
@@ -486,8 +486,8 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.tiles_n_per_tensor = (a.D + a.bn - 1) / a.bn;
     const uint32_t n_tiles = (uint32_t)a.tiles_m * a.tiles_n_per_tensor * a.n_tensors;
 
-    static bool attr_set = false;   // dynamic LDS above 64 KB needs the attribute once per process
-    if (!attr_set) {
+    // dynamic LDS above 64 KB needs the attribute, once per process (thread-safe initialisation)
+    static const hipError_t attr_rc = [] {
         hipError_t e = hipSuccess;
         const void* big[2] = {(const void*)qkv_gemm_direct_kernel<4, 2, 4, false>, (const void*)qkv_gemm_direct_kernel<4, 2, 4, true>};
         const void* small[2] = {(const void*)qkv_gemm_direct_kernel<2, 3, 3, false>, (const void*)qkv_gemm_direct_kernel<2, 3, 3, true>};
@@ -497,9 +497,9 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
             if (e == hipSuccess) e = hipFuncSetAttribute(small[i], hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes192);
             if (e == hipSuccess) e = hipFuncSetAttribute(staged[i], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         }
-        if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(e));
-        attr_set = true;
-    }
+        return e;
+    }();
+    if (attr_rc != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(attr_rc));
     hipStream_t st = as_stream(stream);
     if (ring_kernel && small_tile && packed)
         hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 3, 3, true>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
