@@ -3,12 +3,15 @@
 //   idx     = ascending list of flagged tiles, n_active = its length
 //   compact = v_cur of the flagged tiles gathered densely in list order.
 //
-// Two launches on the caller's stream, one workgroup per tile in both:
-//   1. flag pass -- streams the tile's S segments of v_cur and v_prev once and writes the tile's flag;
-//   2. gather    -- a flagged tile's workgroup counts the flags before it (its slot in the list), writes its
-//                   id there and copies its v_cur segments into `compact`; unflagged tiles leave at once;
-//                   the last tile's workgroup also writes n_active.
-// HBM traffic: 2 tensors read once + the active fraction read once more and written once (the flags,
+// Two launches on the caller's stream:
+//   1. flag pass -- up to four workgroups of 256 lanes per tile, each streaming a contiguous share of the tile's
+//                   S segments of v_cur and v_prev once and writing its verdict into its own byte of the tile's
+//                   4-byte flag word (small workgroups: many fit a compute unit, so loads of one overlap the
+//                   stores and the tail of another, and a launch of a few hundred tiles still spreads evenly);
+//   2. gather    -- one workgroup per tile: a flagged tile's workgroup counts the flagged words before it (its
+//                   slot in the list), writes its id there and copies its v_cur segments into `compact`;
+//                   unflagged tiles leave at once; the last tile's workgroup also writes n_active.
+// HBM traffic: 2 tensors read once + the active fraction read once more and written once (the flag words,
 // 4 bytes per tile, are re-read by the flagged workgroups out of L2).
 // The flag pass can take the current values from the exchange buffer of the first all-to-all instead and write
 // the head-parallel tensor on the way (the receiver's unpack and the selection in one pass).
@@ -49,23 +52,26 @@ struct UnpackSource {
     int recv_major;
 };
 
-// Workgroup t: flag of tile t.  FROM_BUF: the current values are read from the exchange buffer (and written to
-// their place in the head-parallel tensor on the way) instead of from `cur`.
-template <bool NT_CUR, bool NT_PREV, int THREADS, bool FROM_BUF>
-__global__ void __launch_bounds__(THREADS) select_flag_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
-                                                              float tau, int32_t* __restrict__ tile_flag,
-                                                              int32_t* __restrict__ user_flags, SelectShape sh, UnpackSource u) {
-    const uint32_t t = blockIdx.x;
-    bool changed = false;
-    // the tile's S segments form one index space g = s*seg8 + v; a lane keeps kSelUnroll vectors of each tensor in flight
+// Workgroup (t, part): verdict over vectors [part * share, (part + 1) * share) of tile t's index space
+// g = s * seg8 + v (S segments of seg8 vectors), written to byte `part` of the tile's flag word.
+// FROM_BUF: the current values are read from the exchange buffer (and written to their place in the
+// head-parallel tensor on the way) instead of from `cur`.
+template <bool NT_CUR, bool NT_PREV, bool FROM_BUF>
+__global__ void __launch_bounds__(kSelThreads) select_flag_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
+                                                                  float tau, uint8_t* __restrict__ flag_bytes, SelectShape sh,
+                                                                  uint32_t share, UnpackSource u) {
+    const uint32_t t = blockIdx.x, part = blockIdx.y;
     const uint32_t total = sh.S * sh.seg8;
-    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * THREADS) {
+    const uint32_t begin = part * share, end = min(total, begin + share);
+    bool changed = false;
+    // a lane keeps kSelUnroll vectors of each tensor in flight
+    for (uint32_t g0 = begin + threadIdx.x; g0 < end; g0 += kSelUnroll * kSelThreads) {
         vec16 c[kSelUnroll], p[kSelUnroll];
         uint64_t hs_at[kSelUnroll];
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k) {
-            const uint32_t g = g0 + k * THREADS;
-            if (g < total) {
+            const uint32_t g = g0 + k * kSelThreads;
+            if (g < end) {
                 const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
                 const uint64_t at = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v;
                 if (FROM_BUF) {
@@ -84,16 +90,13 @@ __global__ void __launch_bounds__(THREADS) select_flag_kernel(const vec16* __res
         }
 #pragma unroll
         for (int k = 0; k < kSelUnroll; ++k)
-            if (g0 + k * THREADS < total) {
+            if (g0 + k * kSelThreads < end) {
                 changed |= vec_changed(c[k], p[k], tau);
                 if (FROM_BUF) u.hs_out[hs_at[k]] = c[k];      // cached store: the gather pass reads the active tiles again
             }
     }
     const int any = __syncthreads_or(changed ? 1 : 0) ? 1 : 0;
-    if (threadIdx.x == 0) {
-        tile_flag[t] = any;
-        if (user_flags) user_flags[t] = any;
-    }
+    if (threadIdx.x == 0) flag_bytes[4u * t + part] = (uint8_t)any;
 }
 
 // Sum over the workgroup of one count per lane; every lane gets the total.
@@ -109,18 +112,21 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* wave_tot) {
     return tot;
 }
 
-// Workgroup t: if tile t is flagged, its list slot is the number of flagged tiles before it.
+// Workgroup t: if tile t is flagged (any of the bytes of its flag word that the flag pass wrote, `mask`), its
+// list slot is the number of flagged tiles before it.
 template <int THREADS>
-__global__ void __launch_bounds__(THREADS) select_gather_kernel(const vec16* __restrict__ cur, const int32_t* __restrict__ tile_flag,
+__global__ void __launch_bounds__(THREADS) select_gather_kernel(const vec16* __restrict__ cur, const uint32_t* __restrict__ tile_flag,
+                                                                    uint32_t mask, int32_t* __restrict__ user_flags,
                                                                     int32_t* __restrict__ idx, int32_t* __restrict__ n_active,
                                                                     vec16* __restrict__ compact, SelectShape sh, uint32_t cap_tiles) {
     __shared__ uint32_t wave_tot[THREADS / 64];
     const uint32_t t = blockIdx.x;
-    const bool mine = tile_flag[t] != 0;
+    const bool mine = (tile_flag[t] & mask) != 0;
     const bool last = t + 1 == sh.NT;
+    if (user_flags && threadIdx.x == 0) user_flags[t] = mine ? 1 : 0;
     if (!mine && !last) return;
     uint32_t before = 0;
-    for (uint32_t u = threadIdx.x; u < t; u += THREADS) before += tile_flag[u] != 0 ? 1u : 0u;
+    for (uint32_t u = threadIdx.x; u < t; u += THREADS) before += (tile_flag[u] & mask) != 0 ? 1u : 0u;
     const uint32_t slot = block_sum<THREADS>(before, wave_tot);
     if (threadIdx.x == 0) {
         if (mine) idx[slot] = (int32_t)t;
@@ -222,38 +228,37 @@ static int select_launch(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
     if (workspace_bytes < need)
         return fail(COCODIFF_ERR_CAPACITY, "select: workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
     hipStream_t st = as_stream(stream);
-    int32_t* tile_flag = (int32_t*)workspace;
+    uint32_t* tile_flag = (uint32_t*)workspace;    // one word per tile, a byte per workgroup of the flag pass
 
     const size_t touched = (size_t)S * sh.slab8 * 32;
-    // workgroup size: a tile in as few passes as possible (kSelUnroll vectors per lane and pass), 256..1024 lanes
+    // flag pass: a tile is cut into at most 4 shares of whole 256-vector rows, about kSelUnroll vectors per lane
     const uint32_t per_tile = sh.S * sh.seg8;
-    const int threads = per_tile > 512 * kSelUnroll ? 1024 : per_tile > 256 * kSelUnroll ? 512 : 256;
+    const uint32_t want = (per_tile + kSelUnroll * kSelThreads - 1) / (kSelUnroll * kSelThreads);
+    const uint32_t parts_max = want < 1 ? 1 : want > 4 ? 4 : want;
+    const uint32_t share = ((per_tile + parts_max - 1) / parts_max + kSelThreads - 1) / kSelThreads * kSelThreads;
+    const uint32_t parts = (per_tile + share - 1) / share;                  // every share non-empty
+    const uint32_t mask = parts >= 4 ? 0xffffffffu : (1u << (8 * parts)) - 1u;
     // v_cur stays cached: the second launch reads the active tiles again
     const UnpackSource src = from_buf ? *from_buf : UnpackSource{};
     with_policy(from_buf != nullptr, stream_loads_once(touched), [&](auto F, auto Pv) {
         constexpr bool fb = decltype(F)::value, pv = decltype(Pv)::value;
-        if (threads == 1024)
-            hipLaunchKernelGGL((select_flag_kernel<false, pv, 1024, fb>), dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur,
-                               (const vec16*)v_prev, tau, tile_flag, flags, sh, src);
-        else if (threads == 512)
-            hipLaunchKernelGGL((select_flag_kernel<false, pv, 512, fb>), dim3(sh.NT), dim3(512), 0, st, (const vec16*)v_cur,
-                               (const vec16*)v_prev, tau, tile_flag, flags, sh, src);
-        else
-            hipLaunchKernelGGL((select_flag_kernel<false, pv, 256, fb>), dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur,
-                               (const vec16*)v_prev, tau, tile_flag, flags, sh, src);
+        hipLaunchKernelGGL((select_flag_kernel<false, pv, fb>), dim3(sh.NT, parts), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
+                           (const vec16*)v_prev, tau, (uint8_t*)tile_flag, sh, share, src);
     });
     rc = check_launch("select_flag_kernel");
     if (rc != COCODIFF_OK) return rc;
+    // gather pass: one workgroup per tile, a tile in as few passes as possible (kSelUnroll vectors per lane and pass)
+    const int threads = per_tile > 512 * kSelUnroll ? 1024 : per_tile > 256 * kSelUnroll ? 512 : 256;
     const uint32_t cap = compact ? (uint32_t)cap_tiles : 0u;
     if (threads == 1024)
         hipLaunchKernelGGL(select_gather_kernel<1024>, dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur,
-                           (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh, cap);
+                           (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
     else if (threads == 512)
         hipLaunchKernelGGL(select_gather_kernel<512>, dim3(sh.NT), dim3(512), 0, st, (const vec16*)v_cur,
-                           (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh, cap);
+                           (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
     else
         hipLaunchKernelGGL(select_gather_kernel<256>, dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur,
-                           (const int32_t*)tile_flag, active_idx, n_active, (vec16*)compact, sh, cap);
+                           (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
     return check_launch("select_gather_kernel");
 }
 
