@@ -339,6 +339,56 @@ def main() -> int:
         standalone = {"schedule": sa_name, "ms_per_step": round(ms_sa, 4), "value": round(N / (ms_sa * 1e-3), 1), "unit": "tokens/s"}
         log(f"  stand-alone calls ({sa_name} schedule): {standalone}")
 
+    # The sender's share alone -- projection of Q, K, V + norm and RoPE of Q and K + the three packs, up to the
+    # filled exchange buffers (the layer's work before the all-to-all) -- in three forms; `value` above is the longer
+    # path that also holds the receiver's unpack and the selection.
+    layer_only = None
+    if not args.no_breakdown:
+        def sender_serial():
+            cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v, stream=s_v)
+            cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=s_v)
+            for src, buf in ((v, bv), (q, bq), (k, bk)):
+                cd.a2a_pack(sh, src, buf, ORDER, stream=s_v)
+
+        def sender_vfirst():
+            cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=s_v)
+            v_ready = torch.cuda.Event()
+            v_ready.record(s_v)
+            cd.a2a_pack(sh, v, bv, ORDER, stream=s_v)
+            s_qk.wait_event(v_ready)
+            cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=s_qk)
+            cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=s_qk)
+            cd.a2a_pack(sh, q, bq, ORDER, stream=s_qk)
+            cd.a2a_pack(sh, k, bk, ORDER, stream=s_qk)
+            done = torch.cuda.Event()
+            done.record(s_qk)
+            s_v.wait_event(done)
+
+        def sender_fused():
+            cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
+            v_ready = torch.cuda.Event()
+            v_ready.record(s_v)
+            s_qk.wait_event(v_ready)
+            cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=s_qk)
+            cd.qk_norm_rope_pack(sh, q, k, gq, gk, cfg.eps, rope, bq, bk, ORDER, stream=s_qk)
+            done = torch.cuda.Event()
+            done.record(s_qk)
+            s_v.wait_event(done)
+
+        layer_only = {}
+        for label, fn in (("serial_one_stream", sender_serial), ("vfirst_two_streams", sender_vfirst),
+                          ("vfirst_fused_calls", sender_fused)):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            ms_l = (time.perf_counter() - t0) * 1e3 / args.steps
+            layer_only[label] = {"ms": round(ms_l, 4), "tokens/s": round(N / (ms_l * 1e-3), 1)}
+        log(f"  sender's share alone (projection + norm + RoPE + pack): {layer_only}")
+
     # dominant kernel: the projection GEMM (launched per step as V, then Q+K -- or V, Q, K in the vfirst3 order)
     n_launch = 3 if args.schedule in ("vfirst3", "fused3", "fused3s") else 2
     gemm_ms = [(e[0].elapsed_time(e[1]), e[2].elapsed_time(e[3])) for e in events]
@@ -571,6 +621,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "standalone_calls_path": standalone,
         "hip_graph_replay": graph_replay,
+        "sender_share_only": layer_only,
         "attainable": attainable,
         "kernels": kernels,
     }
