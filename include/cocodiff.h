@@ -196,7 +196,8 @@ COCODIFF_API int cocodiff_a2a_unpack(const cocodiff_shape* shape, const cocodiff
  * Entries of active_idx and compact beyond n_active are unspecified.  v_prev is read-only.
  * Rules: S, N, W, tile_tokens > 0; W % 8 == 0; N % tile_tokens == 0 (else COCODIFF_ERR_SHAPE);
  * cap_tiles >= 1 when compact != NULL (else COCODIFF_ERR_CAPACITY).
- * workspace: device scratch of at least cocodiff_vmajor_select_workspace_bytes(...) bytes.
+ * workspace: device scratch of at least cocodiff_vmajor_select_workspace_bytes(...) bytes; its contents on entry
+ * are ignored (no clearing needed) and it may be reused by the next call on the same stream.
  */
 COCODIFF_API int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
                            const cocodiff_bf16* v_cur, const cocodiff_bf16* v_prev, float tau,
