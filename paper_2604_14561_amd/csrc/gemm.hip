@@ -1,5 +1,7 @@
 // QKV projection (paper Section II-B): Y[n][o] = sum_k X[n][k] * W[o][k], bf16 in, fp32 accumulate on the
-// gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), one RNE rounding to bf16.
+// gfx950 matrix cores, one RNE rounding to bf16.  The main kernel multiplies with v_mfma_f32_16x16x32_bf16: on this
+// power-limited part it sustains 1.91 PFLOP/s at 0.70 pJ/flop in a register-only loop against 1.72 PFLOP/s at
+// 0.77 pJ/flop for v_mfma_f32_32x32x16_bf16, for the same LDS traffic per flop (a wavefront's tile decides that).
 //
 // Workgroup tile: 256 tokens x 256 features (192 x 192 when that fills the compute units much better: small
 // token counts), K step 64 (a row segment of either operand is one whole 128-byte line; half lines halve the L1
@@ -23,6 +25,7 @@ namespace cocodiff {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int BM = 256;          // tokens per workgroup tile
 constexpr int BN = 256;          // features per workgroup tile
@@ -93,40 +96,35 @@ __device__ __forceinline__ void mfma_slice(f32x16 (&acc)[NI][4], const bf16x8 (&
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
 }
 
-// Round to bf16, transpose through this wavefront's private LDS region (NJ*32 token rows of NI*32 features),
-// write whole rows.  Accumulator element e of lane l in MFMA tile (i, j): feature 32i + 8*(e/4) + 4*(l/32)
-// + e%4, token 32j + l%32.  An LDS row has CP >= NI*4 columns of 16 bytes, CP a power of two; column c of row r is
+// Epilogue: round to bf16, transpose through this wavefront's private LDS region (ROWS token rows of COLS 16-byte
+// feature columns), write whole rows.  An LDS row has CP >= COLS columns, CP a power of two; column c of row r is
 // stored at column c ^ (r & (CP - 1)).
+template <uint32_t COLS>
+struct EpilogueRows {
+    static constexpr uint32_t CP = COLS <= 4 ? 4 : COLS <= 8 ? 8 : 16;   // columns per LDS row
+    static constexpr uint32_t ROWB = CP * 16;                            // bytes per LDS row
+    // four consecutive features (feat a multiple of 4) of LDS row `row`
+    static __device__ __forceinline__ void put4(unsigned char* ep, uint32_t row, uint32_t feat, float f0, float f1, float f2, float f3) {
+        const uint32_t c16 = feat >> 3, half8 = (feat >> 2) & 1u;
+        uint2 v;
+        v.x = pack_bf16x2(f0, f1);
+        v.y = pack_bf16x2(f2, f3);
+        *reinterpret_cast<uint2*>(ep + row * ROWB + (((c16 ^ (row & (CP - 1u))) << 4) | (half8 << 3))) = v;
+    }
+};
+
+// Second half of the epilogue: the wavefront reads back the rows it staged (a wavefront's LDS accesses complete in
+// order: no workgroup barrier is needed) and writes them out.
 // PACKED: the 8 features a lane writes for token n = r*Ns + m go to chunk (sender r, receiver p = feature / (Hp*d))
 // of the exchange buffer Y, row m (Hp*d is a multiple of 8, so a 16-byte vector never straddles two chunks).
-template <int NI, int NJ, bool PACKED>
-__device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane,
-                                           uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
-                                           uint32_t M, uint32_t D, const GemmArgs& a) {
-    constexpr uint32_t COLS = NI * 4;                                    // 16-byte columns in use per row
-    constexpr uint32_t CP = COLS <= 4 ? 4 : COLS <= 8 ? 8 : 16;          // columns per LDS row
-    constexpr uint32_t ROWB = CP * 16;                                   // bytes per LDS row
-    const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const uint32_t row = 32u * j + frag_row;
-                const uint32_t feat = 32u * i + 8u * g + 4u * frag_half;   // multiple of 4
-                const uint32_t c16 = feat >> 3, half8 = (feat >> 2) & 1u;
-                uint2 v;
-                v.x = pack_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]);
-                v.y = pack_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-                *reinterpret_cast<uint2*>(ep + row * ROWB + (((c16 ^ (row & (CP - 1u))) << 4) | (half8 << 3))) = v;
-            }
-    // the same wavefront reads back what it wrote, and a wavefront's LDS accesses complete in order:
-    // no workgroup barrier is needed
+template <uint32_t COLS, uint32_t ROWS, bool PACKED>
+__device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lane, uint16_t* __restrict__ Y, size_t row0,
+                                           uint32_t tok0, uint32_t feat0, uint32_t M, uint32_t D, const GemmArgs& a) {
+    constexpr uint32_t CP = EpilogueRows<COLS>::CP, ROWB = EpilogueRows<COLS>::ROWB;
     constexpr uint32_t RPI = 64 / CP;            // rows per read instruction
     const uint32_t c16 = lane % CP, rsub = lane / CP;
 #pragma unroll 8
-    for (uint32_t it = 0; it < NJ * 32 / RPI; ++it) {
+    for (uint32_t it = 0; it < ROWS / RPI; ++it) {
         const uint32_t row = RPI * it + rsub;
         const uint32_t tok = tok0 + row;
         const uint32_t feat = feat0 + c16 * 8u;
@@ -144,6 +142,40 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], unsigned
     }
 }
 
+// 32 x 32 accumulator tiles (v_mfma_f32_32x32x16_bf16): element e of lane l in tile (i, j) is feature
+// 32i + 8*(e/4) + 4*(l/32) + e%4 of token 32j + l%32.
+template <int NI, int NJ, bool PACKED>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane,
+                                           uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
+                                           uint32_t M, uint32_t D, const GemmArgs& a) {
+    const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                EpilogueRows<NI * 4>::put4(ep, 32u * j + frag_row, 32u * i + 8u * g + 4u * frag_half, acc[i][j][4 * g + 0],
+                                           acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+    store_rows<NI * 4, NJ * 32, PACKED>(ep, lane, Y, row0, tok0, feat0, M, D, a);
+}
+
+// 16 x 16 accumulator tiles (v_mfma_f32_16x16x32_bf16): element e of lane l in tile (i, j) is feature
+// 16i + 4*(l/16) + e of token 16j + l%16.
+template <int NI, int NJ, bool PACKED>
+__device__ __forceinline__ void store_tile16(const f32x4 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane,
+                                             uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
+                                             uint32_t M, uint32_t D, const GemmArgs& a) {
+    const uint32_t frag_row = lane & 15u, frag_q = lane >> 4;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            EpilogueRows<NI * 2>::put4(ep, 16u * j + frag_row, 16u * i + 4u * frag_q, acc[i][j][0], acc[i][j][1], acc[i][j][2],
+                                       acc[i][j][3]);
+    store_rows<NI * 2, NJ * 16, PACKED>(ep, lane, Y, row0, tok0, feat0, M, D, a);
+}
+
 // s_waitcnt: at most WAIT global->LDS loads of this wavefront still in flight (LDS-read counter untouched)
 template <int WAIT>
 __device__ __forceinline__ void wait_loads() {
@@ -153,15 +185,18 @@ __device__ __forceinline__ void wait_loads() {
 
 // ---------------------------------------------------------------------------------------------
 // Main kernel.  A step's X tile and W tile (32 KB each) travel separately through a ring of five LDS
-// slots: X of K step kt lives in slot (2kt) % 5, W in slot (2kt + 1) % 5.  In step kt a wavefront
-// multiplies slices 0..2 (each while reading the next slice's fragments), waits until step kt+1 has landed
-// (its own loads; the barrier covers the other wavefronts'), then multiplies slice 3 while reading slice 0
-// of step kt+1.  After that barrier every wavefront is past its last read of step kt, so W of step kt+2
-// goes into the slot X of step kt used (one step to land) and X of step kt+3 into the slot W of step kt
-// used (two steps to land).  The W loads are issued in slice 3 of step kt, the X loads one or two per
-// slice over step kt+1: a wavefront that issues its eight loads of a step in one burst stalls on the
-// address unit, and the MFMAs behind them in program order with it (measured: +340 cycles per step).
-// Instruction order inside a slice is pinned by a scheduling barrier after every instruction group.
+// slots: X of K step kt lives in slot (2kt) % 5, W in slot (2kt + 1) % 5.  A K step is two halves of 32 K
+// elements, one v_mfma_f32_16x16x32_bf16 per 16 x 16 output tile and half.  In step kt a wavefront multiplies half 0
+// while reading the fragments of half 1, waits until step kt+1 has landed (its own loads; the barrier covers the
+// other wavefronts'), then multiplies half 1 while reading half 0 of step kt+1.  After that barrier every
+// wavefront is past its last read of step kt, so W of step kt+2 goes into the slot X of step kt used and X of
+// step kt+3 into the slot W of step kt used.  The X loads are issued one at a time during half 0, the W loads
+// during half 1: a wavefront that issues its eight loads of a step in one burst stalls on the address unit, and the
+// MFMAs behind them in program order with it (measured: +340 cycles per step).
+// The MFMAs of a half run token tile by token tile: the X fragment of a token tile is dead after NI MFMAs and is
+// read again for the next half right there (X fragments need one register set), the NI W fragments live through
+// the half and have two sets.  Instruction order inside a half is pinned by a scheduling barrier after every
+// instruction group.
 // ---------------------------------------------------------------------------------------------
 constexpr int kRingSlots = 5;
 constexpr int kRingLdsBytes256 = kRingSlots * 256 * BK * 2;   // 160 KB: tiles of 256 x 256
@@ -179,17 +214,17 @@ __device__ __forceinline__ void load_to_lds(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
 }
 
-// Tile = (2 * NJ * 32) tokens x (WN * NI * 32) features, square: 256 x 256 with WN = 4, NI = 2, NJ = 4 (8 wavefronts
-// of 128 x 64) or 192 x 192 with WN = 2, NI = 3, NJ = 3 (4 wavefronts of 96 x 96).
+// Tile = (2 * NJ * 16) tokens x (WN * NI * 16) features, square: 256 x 256 with WN = 4, NI = 4, NJ = 8 (8 wavefronts
+// of 64 features x 128 tokens) or 192 x 192 with WN = 2, NI = 6, NJ = 6 (4 wavefronts of 96 x 96).
 template <int WN, int NI, int NJ, bool PACKED>
 __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     constexpr int WAVES = 2 * WN;
-    constexpr int TILE = 2 * NJ * 32;              // tokens = features per tile
-    static_assert(TILE == WN * NI * 32, "square tiles only: the ring slots of X and W have one size");
+    constexpr int TILE = 2 * NJ * 16;              // tokens = features per tile
+    static_assert(TILE == WN * NI * 16, "square tiles only: the ring slots of X and W have one size");
     constexpr int kTileBytes = TILE * BK * 2;      // one operand tile of one K step
-    constexpr int NMFMA = NI * NJ, NREAD = NI + NJ;
+    constexpr int NMFMA = NI * NJ;
     constexpr int LOADS = TILE / 8 / WAVES;        // global->LDS instructions per lane per operand per step
-    static_assert(LOADS * WAVES * 8 == TILE && NMFMA > NREAD, "tile shape");
+    static_assert(LOADS * WAVES * 8 == TILE && NI >= 3 && LOADS <= 2 * NJ && NI <= NJ, "tile shape");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const TileCoord tc = tile_of_block(a);
@@ -197,7 +232,7 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     const uint32_t K = (uint32_t)a.D;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t wave_f = (wave % WN) * (NI * 32u), wave_t = (wave / WN) * (NJ * 32u);
+    const uint32_t wave_f = (wave % WN) * (NI * 16u), wave_t = (wave / WN) * (NJ * 16u);
 
     // load i of this wavefront fills LDS rows (WAVES*i + wave)*8 .. +8 of a tile: lane -> row lane>>3, stored column lane&7
     const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x + ((size_t)a.row_begin + tc.m0) * K);
@@ -221,91 +256,81 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
         for (int i = 0; i < LOADS; ++i) issue_one(base, off, kt, slot, i);
     };
 
-    // fragment addresses: row = wave offset + 32i + (lane & 31); the swizzle depends on the lane only
-    const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
+    // MFMA operand layout: lane l holds K elements 8*(l/16) .. +7 (of the half's 32) of row l%16 of a 16-row fragment.
+    // Fragment addresses: row = wave offset + 16 i + (lane & 15); the swizzle depends on the lane only.
+    const uint32_t frag_row = lane & 15u, frag_kg = lane >> 4;
     const uint32_t sw = swz(frag_row);
     const uint32_t x_frag = (wave_t + frag_row) * 128u;
     const uint32_t w_frag = (wave_f + frag_row) * 128u;
-    // fragment r of slice kk of the step whose X tile sits in slot_x, in the order the MFMAs consume them:
-    // r = 0: W tile 0; r = 1..NJ: X tiles; r = NJ+1..: W tiles 1..
-    auto read_frag = [&](uint32_t slot_x, uint32_t kk, int r, bf16x8 (&wf)[NI], bf16x8 (&xf)[NJ]) {
-        const uint32_t col = ((2u * kk + frag_half) ^ sw) << 4;
-        const unsigned char* xb = smem + slot_x * kTileBytes + x_frag + col;
-        const unsigned char* wb = smem + ring_add(slot_x, 1) * kTileBytes + w_frag + col;
-        if (r == 0) wf[0] = *reinterpret_cast<const bf16x8*>(wb);
-        else if (r <= NJ) xf[r - 1] = *reinterpret_cast<const bf16x8*>(xb + (r - 1) * 4096);
-        else wf[r - NJ] = *reinterpret_cast<const bf16x8*>(wb + (r - NJ) * 4096);
+    // X fragment j / W fragment i of half kk of the step whose X tile sits in slot_x (W: the next slot)
+    auto read_x = [&](uint32_t slot_x, uint32_t kk, int j) {
+        return *reinterpret_cast<const bf16x8*>(smem + slot_x * kTileBytes + x_frag + (((4u * kk + frag_kg) ^ sw) << 4) + j * 2048);
+    };
+    auto read_w = [&](uint32_t slot_x, uint32_t kk, int i) {
+        return *reinterpret_cast<const bf16x8*>(smem + ring_add(slot_x, 1) * kTileBytes + w_frag + (((4u * kk + frag_kg) ^ sw) << 4) + i * 2048);
     };
 
-    f32x16 acc[NI][NJ];   // [feature tile][token tile]
+    f32x4 acc[NI][NJ];   // [feature tile][token tile]
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
     const uint32_t n_k = K / BK;   // >= 3 (the host sends shorter K to the fallback kernel)
     issue_tile(xbase, xoff, 0, 0);
     issue_tile(wbase, woff, 0, 1);
     issue_tile(xbase, xoff, 1, 2);
     issue_tile(wbase, woff, 1, 3);
-    issue_tile(xbase, xoff, 2, 4);
-    wait_loads<3 * LOADS>();       // step 0 has landed; X1, W1, X2 may still be in flight
+    wait_loads<2 * LOADS>();       // step 0 has landed; X1, W1 may still be in flight
     __syncthreads();
 
-    bf16x8 wf0[NI], xf0[NJ], wf1[NI], xf1[NJ];
+    bf16x8 wf0[NI], wf1[NI], xf[NJ];
 #pragma unroll
-    for (int r = 0; r < NREAD; ++r) read_frag(0, 0, r, wf0, xf0);
+    for (int i = 0; i < NI; ++i) wf0[i] = read_w(0, 0, i);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) xf[j] = read_x(0, 0, j);
 
-    // One slice: NMFMA MFMAs on (wf, xf); after MFMA m < NREAD the m-th fragment of the next slice is read into
-    // (wf_n, xf_n); after MFMA NREAD + g the g-th of `n_loads` loads (first_load ...) of `base` is issued.
-    // sched_barrier(0) after every instruction group keeps this order.
-    auto slice = [&](const bf16x8 (&wf)[NI], const bf16x8 (&xf)[NJ], bf16x8 (&wf_n)[NI], bf16x8 (&xf_n)[NJ], bool read_next,
-                     uint32_t slot_n, uint32_t kk_n, auto n_loads_c, const unsigned char* base,
-                     const uint32_t (&off)[LOADS], uint32_t kt_l, uint32_t slot_l, int first_load) {
+    // One half: MFMA m multiplies W fragment i = m % NI with X fragment j = m / NI.  After the first MFMA of token
+    // tile j < NI, W fragment j of the next half is read into wf_n; after the last MFMA of token tile j its X
+    // fragment is read again for the next half; after the second (then the third) MFMA of token tile j load
+    // number j (NJ + j) of the N_LOADS loads of `base` is issued.  sched_barrier(0) after every group keeps the order.
+    auto half = [&](const bf16x8 (&wf)[NI], bf16x8 (&wf_n)[NI], bool read_next, uint32_t slot_n, uint32_t kk_n, auto n_loads_c,
+                    const unsigned char* base, const uint32_t (&off)[LOADS], uint32_t kt_l, uint32_t slot_l) {
         constexpr int N_LOADS = decltype(n_loads_c)::value;
-        constexpr int LOAD_SLOTS = NMFMA - NREAD;                         // MFMAs after the reads
-        constexpr int PER = N_LOADS ? (N_LOADS + LOAD_SLOTS - 1) / LOAD_SLOTS : 0;
 #pragma unroll
         for (int m = 0; m < NMFMA; ++m) {
-            acc[m / NJ][m % NJ] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[m / NJ], xf[m % NJ], acc[m / NJ][m % NJ], 0, 0, 0);
+            const int i = m % NI, j = m / NI;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (m < NREAD) {
-                if (read_next) read_frag(slot_n, kk_n, m, wf_n, xf_n);
-            } else {
-#pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int l = (m - NREAD) * PER + q;
-                    if (l < N_LOADS) issue_one(base, off, kt_l, slot_l, first_load + l);
-                }
+            if (i == 0) {
+                if (j < NI && read_next) wf_n[j] = read_w(slot_n, kk_n, j);
+            } else if (i == NI - 1) {
+                if (read_next) xf[j] = read_x(slot_n, kk_n, j);
+            } else if (i <= 2) {
+                const int l = (i - 1) * NJ + j;
+                if (l < N_LOADS) issue_one(base, off, kt_l, slot_l, l);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // X loads of a later step, spread over slices 0..2: counts per slice
-    constexpr int XA = (LOADS + 2) / 3, XB = (LOADS - XA + 1) / 2, XC = LOADS - XA - XB;
     // `slot` is the ring slot of X of step kt; W of step kt sits in the next slot.
-    // LOAD_X: X of step kt+2 is issued during slices 0..2 (into the slot W of step kt-1 used);
-    // LOAD_W: W of step kt+2 is issued during slice 3 (into the slot X of step kt used).
+    // LOAD_X: X of step kt+2 is issued during half 0 (into the slot W of step kt-1 used);
+    // LOAD_W: W of step kt+2 is issued during half 1 (into the slot X of step kt used).
     auto k_step = [&](uint32_t kt, uint32_t slot, auto load_x, auto load_w, auto wait, auto next) {
         constexpr bool LOAD_X = decltype(load_x)::value, LOAD_W = decltype(load_w)::value, NEXT = decltype(next)::value;
         constexpr int WAIT = decltype(wait)::value;
-        const uint32_t slot_x2 = ring_add(slot, 4);     // (2(kt+2)) % 5
-        using xa = std::integral_constant<int, LOAD_X ? XA : 0>;
-        using xb = std::integral_constant<int, LOAD_X ? XB : 0>;
-        using xc = std::integral_constant<int, LOAD_X ? XC : 0>;
+        using xl = std::integral_constant<int, LOAD_X ? LOADS : 0>;
         using wl = std::integral_constant<int, LOAD_W ? LOADS : 0>;
-        slice(wf0, xf0, wf1, xf1, true, slot, 1, xa{}, xbase, xoff, kt + 2, slot_x2, 0);
-        slice(wf1, xf1, wf0, xf0, true, slot, 2, xb{}, xbase, xoff, kt + 2, slot_x2, XA);
-        slice(wf0, xf0, wf1, xf1, true, slot, 3, xc{}, xbase, xoff, kt + 2, slot_x2, XA + XB);
+        half(wf0, wf1, true, slot, 1, xl{}, xbase, xoff, kt + 2, ring_add(slot, 4));
         if constexpr (NEXT) {
             wait_loads<WAIT>();
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);
-        slice(wf1, xf1, wf0, xf0, NEXT, ring_add(slot, 2), 0, wl{}, wbase, woff, kt + 2, slot, 0);
+        half(wf1, wf0, NEXT, ring_add(slot, 2), 0, wl{}, wbase, woff, kt + 2, slot);
     };
     using yes = std::true_type;
     using no = std::false_type;
@@ -316,9 +341,6 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
         ++kt;
         slot = ring_add(slot, 2);
     };
-    // step 0: X of step 2 is already on its way (issued above); only W of step 2 is issued here
-    k_step(kt, slot, no{}, yes{}, w1, yes{});
-    advance();
     // At the barrier of step kt the loads in flight, oldest first, are X(kt+1), W(kt+1), X(kt+2): the last may stay.
     while (kt + 2 < n_k) {
         k_step(kt, slot, yes{}, yes{}, w1, yes{});
@@ -328,10 +350,10 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     advance();
     k_step(kt, slot, no{}, no{}, w0, no{});      // step n_k-1
     __syncthreads();
-    constexpr int kEpilogueBytes = NJ * 32 * (NI * 4 <= 4 ? 4 : NI * 4 <= 8 ? 8 : 16) * 16;   // per wavefront, see store_tile
+    constexpr int kEpilogueBytes = NJ * 16 * EpilogueRows<NI * 2>::ROWB;   // per wavefront, see store_tile16
     static_assert(WAVES * kEpilogueBytes <= kRingSlots * kTileBytes, "the epilogue reuses the ring's LDS");
-    store_tile<NI, NJ, PACKED>(acc, smem + wave * kEpilogueBytes, lane, a.y[tc.tensor], (size_t)a.row_begin,
-                               tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
+    store_tile16<NI, NJ, PACKED>(acc, smem + wave * kEpilogueBytes, lane, a.y[tc.tensor], (size_t)a.row_begin,
+                                 tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -489,8 +511,8 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     // dynamic LDS above 64 KB needs the attribute, once per process (thread-safe initialisation)
     static const hipError_t attr_rc = [] {
         hipError_t e = hipSuccess;
-        const void* big[2] = {(const void*)qkv_gemm_direct_kernel<4, 2, 4, false>, (const void*)qkv_gemm_direct_kernel<4, 2, 4, true>};
-        const void* small[2] = {(const void*)qkv_gemm_direct_kernel<2, 3, 3, false>, (const void*)qkv_gemm_direct_kernel<2, 3, 3, true>};
+        const void* big[2] = {(const void*)qkv_gemm_direct_kernel<4, 4, 8, false>, (const void*)qkv_gemm_direct_kernel<4, 4, 8, true>};
+        const void* small[2] = {(const void*)qkv_gemm_direct_kernel<2, 6, 6, false>, (const void*)qkv_gemm_direct_kernel<2, 6, 6, true>};
         const void* staged[2] = {(const void*)qkv_gemm_staged_kernel<false>, (const void*)qkv_gemm_staged_kernel<true>};
         for (int i = 0; i < 2 && e == hipSuccess; ++i) {
             e = hipFuncSetAttribute(big[i], hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes256);
@@ -502,13 +524,13 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     if (attr_rc != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(attr_rc));
     hipStream_t st = as_stream(stream);
     if (ring_kernel && small_tile && packed)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 3, 3, true>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 6, 6, true>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
     else if (ring_kernel && small_tile)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 3, 3, false>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 6, 6, false>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
     else if (ring_kernel && packed)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<4, 2, 4, true>), dim3(n_tiles), dim3(512), kRingLdsBytes256, st, a);
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<4, 4, 8, true>), dim3(n_tiles), dim3(512), kRingLdsBytes256, st, a);
     else if (ring_kernel)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<4, 2, 4, false>), dim3(n_tiles), dim3(512), kRingLdsBytes256, st, a);
+        hipLaunchKernelGGL((qkv_gemm_direct_kernel<4, 4, 8, false>), dim3(n_tiles), dim3(512), kRingLdsBytes256, st, a);
     else if (packed)
         hipLaunchKernelGGL(qkv_gemm_staged_kernel<true>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, st, a);
     else
