@@ -487,8 +487,8 @@ def main() -> int:
         src_big2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst_big2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         sink = torch.zeros(1, dtype=torch.float32, device=dev)
-        mfma_flops = cd.util_mfma_rate(2048, 4096, sink)
-        mfma_us = timed([lambda: cd.util_mfma_rate(2048, 4096, sink)])[0]
+        mfma_flops = cd.util_mfma_rate(1024, 2048, sink)
+        mfma_us = timed([lambda: cd.util_mfma_rate(1024, 2048, sink)])[0]
         attainable = {"hbm_copy_GB/s": round(2 * big / copy_us / 1e3, 1), "runtime_memcpy_GB/s": round(2 * big / memcpy_us / 1e3, 1),
                       "mfma_loop_TFLOP/s": round(mfma_flops / mfma_us / 1e6, 1)}
         log(f"  attainable on this GPU: {attainable}")
@@ -544,7 +544,7 @@ def main() -> int:
         # the chip does not hold its top clock under matrix-core load: record what it runs at (last: the throttled
         # state lingers and would colour the timings above)
         state = {"copy": chip_state_during(lambda: cd.util_copy(src_big2, dst_big2, 256 << 20)),
-                 "mfma_loop": chip_state_during(lambda: cd.util_mfma_rate(2048, 1024, sink)),
+                 "mfma_loop": chip_state_during(lambda: cd.util_mfma_rate(1024, 512, sink)),
                  "projection": chip_state_during(lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v))}
         attainable["sclk_MHz"] = {k_: v_["sclk_MHz"] for k_, v_ in state.items()}
         attainable["power_W"] = {k_: v_["power_W"] for k_, v_ in state.items()}

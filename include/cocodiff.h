@@ -293,11 +293,11 @@ COCODIFF_API int cocodiff_rope_table_fill(const cocodiff_rope* rope, float* host
  * HBM-bound steps are priced against; used by the benchmark and the profiler-counter scaling. */
 COCODIFF_API int cocodiff_util_copy(const void* src, void* dst, size_t bytes, void* stream);
 
-/* Register-only matrix-core loop (v_mfma_f32_32x32x16_bf16 on pseudo-random operands that differ per lane and
- * between consecutive MFMAs, no memory traffic): the calibration kernel the projection is priced against besides the published peak.  Launches
- * `blocks` workgroups of 4 wavefronts, each wavefront issuing iters * 8 MFMAs; `sink` is one DEVICE float that is
- * practically never written.  Returns the floating-point operations of the launch (> 0) or a negative error code;
- * the caller times the launch. */
+/* Register-only matrix-core loop (v_mfma_f32_16x16x32_bf16, the projection kernel's instruction, on a 4 x 8 outer
+ * product of pseudo-random operand fragments as in that kernel; no memory traffic): the calibration kernel the
+ * projection is priced against besides the published peak.  Launches `blocks` workgroups of 8 wavefronts, each
+ * wavefront issuing iters * 32 MFMAs; `sink` is one DEVICE float that is practically never written.  Returns the
+ * floating-point operations of the launch (> 0) or a negative error code; the caller times the launch. */
 COCODIFF_API int64_t cocodiff_util_mfma_rate(int32_t blocks, int32_t iters, float* sink, void* stream);
 
 COCODIFF_API const char* cocodiff_version(void);

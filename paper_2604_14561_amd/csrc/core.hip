@@ -60,41 +60,52 @@ __global__ void __launch_bounds__(256) copy_kernel(const vec16* __restrict__ src
 }
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 mfma_in_t;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float mfma_acc_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float mfma_acc_t;
 
-constexpr int kMfmaChains = 8;   // independent accumulators per wavefront: hides the matrix core's result latency
+constexpr int kRateNI = 4, kRateNJ = 8;   // the projection kernel's wavefront tile: 4 x 8 accumulator tiles of 16 x 16
 
-// Register-only loop of v_mfma_f32_32x32x16_bf16: no memory traffic.  Every chain has its own pair of operand
-// registers, filled with small pseudo-random bf16 values that differ per lane and per chain, so consecutive MFMAs
-// see different operands as they do in a real product (with one operand pair for all chains, or constant operands,
-// the matrix cores draw less power and the chip clocks higher than it does on real data).
-__global__ void __launch_bounds__(256) mfma_rate_kernel(uint32_t iters, float* __restrict__ sink) {
-    uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+// Register-only loop of the projection kernel's matrix-core work: v_mfma_f32_16x16x32_bf16 on a 4 x 8 outer product
+// of operand fragments, token tile by token tile, 8 wavefronts per workgroup (two per SIMD), no memory traffic.  The fragments hold small pseudo-random bf16
+// values that differ per lane and per fragment, so consecutive MFMAs see different operands as they do in a real
+// product (with constant operands the matrix cores draw less power and the chip clocks higher than on real data).
+__global__ void __launch_bounds__(512) mfma_rate_kernel(uint32_t iters, float* __restrict__ sink) {
+    uint32_t h = (blockIdx.x * 512u + threadIdx.x) * 2654435761u + 12345u;
     union Operand { uint16_t u[8]; mfma_in_t v; };
-    Operand a[kMfmaChains], b[kMfmaChains];
-#pragma unroll
-    for (int c = 0; c < kMfmaChains; ++c)
+    Operand a[kRateNI], b[kRateNJ];
+    auto fill = [&](Operand& o) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             h = h * 1664525u + 1013904223u;
-            a[c].u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));   // bf16 of magnitude 2^-7 .. 2, either sign
-            h = h * 1664525u + 1013904223u;
-            b[c].u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));
+            o.u[i] = (uint16_t)(0x3C00u | ((h >> 9) & 0x83FFu));   // bf16 of magnitude 2^-7 .. 2, either sign
         }
-    mfma_acc_t acc[kMfmaChains];
+    };
 #pragma unroll
-    for (int c = 0; c < kMfmaChains; ++c)
+    for (int i = 0; i < kRateNI; ++i) fill(a[i]);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[c][e] = 0.f;
+    for (int j = 0; j < kRateNJ; ++j) fill(b[j]);
+    mfma_acc_t acc[kRateNI][kRateNJ];
+#pragma unroll
+    for (int i = 0; i < kRateNI; ++i)
+#pragma unroll
+        for (int j = 0; j < kRateNJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
     for (uint32_t it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int c = 0; c < kMfmaChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c].v, b[c].v, acc[c], 0, 0, 0);
+        for (int j = 0; j < kRateNJ; ++j)
+#pragma unroll
+            for (int i = 0; i < kRateNI; ++i) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i].v, b[j].v, acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);      // the order as written, as in the projection kernel
+            }
     }
     float total = 0.f;
 #pragma unroll
-    for (int c = 0; c < kMfmaChains; ++c)
+    for (int i = 0; i < kRateNI; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) total += acc[c][e];
+        for (int j = 0; j < kRateNJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) total += acc[i][j][e];
     if (total == 123.456f) sink[0] = total;   // keeps the loop alive; practically never true
 }
 
@@ -151,10 +162,10 @@ int cocodiff_util_copy(const void* src, void* dst, size_t bytes, void* stream) {
 int64_t cocodiff_util_mfma_rate(int32_t blocks, int32_t iters, float* sink, void* stream) {
     if (blocks <= 0 || iters <= 0) return fail(COCODIFF_ERR_SHAPE, "mfma_rate: blocks and iters must be positive");
     if (!sink) return fail(COCODIFF_ERR_NULL, "mfma_rate: NULL sink");
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)blocks), dim3(256), 0, as_stream(stream), (uint32_t)iters, sink);
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)blocks), dim3(512), 0, as_stream(stream), (uint32_t)iters, sink);
     const int rc = check_launch("mfma_rate_kernel");
     if (rc != COCODIFF_OK) return rc;
-    return (int64_t)blocks * 4 * iters * kMfmaChains * (2LL * 32 * 32 * 16);
+    return (int64_t)blocks * 8 * iters * (kRateNI * kRateNJ) * (2LL * 16 * 16 * 32);
 }
 
 }  // extern "C"

@@ -256,9 +256,13 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
         for (int i = 0; i < LOADS; ++i) issue_one(base, off, kt, slot, i);
     };
 
-    // MFMA operand layout: lane l holds K elements 8*(l/16) .. +7 (of the half's 32) of row l%16 of a 16-row fragment.
+    // MFMA operand layout: lane l holds 8 K elements (one 16-byte LDS column) of row l%16 of a 16-row fragment, lane
+    // group l/16 the g-th eight of the instruction's 32.  Which column of the half a lane group takes is free as long as
+    // W and X agree: groups 0, 1, 2, 3 take columns 0, 2, 1, 3, because a 128-bit LDS read serves lanes 8p .. 8p+7
+    // together with lanes 32+8p .. 32+8p+7 (groups g and g+2), and rows 0 .. 7 of two columns share no bank only when
+    // the columns differ in their lowest bit (measured: 4 conflict cycles per read with columns 0, 1, 2, 3).
     // Fragment addresses: row = wave offset + 16 i + (lane & 15); the swizzle depends on the lane only.
-    const uint32_t frag_row = lane & 15u, frag_kg = lane >> 4;
+    const uint32_t frag_row = lane & 15u, frag_kg = ((lane >> 3) & 2u) | (lane >> 5);
     const uint32_t sw = swz(frag_row);
     const uint32_t x_frag = (wave_t + frag_row) * 128u;
     const uint32_t w_frag = (wave_f + frag_row) * 128u;
@@ -301,15 +305,16 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
         constexpr int N_LOADS = decltype(n_loads_c)::value;
 #pragma unroll
         for (int m = 0; m < NMFMA; ++m) {
-            const int i = m % NI, j = m / NI;
+            const int q = m % NI, j = m / NI;                 // q-th MFMA of token tile j
+            const int i = (j & 1) ? NI - 1 - q : q;           // W fragments up, then down: one operand is kept at every turn
             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (i == 0) {
+            if (q == 0) {
                 if (j < NI && read_next) wf_n[j] = read_w(slot_n, kk_n, j);
-            } else if (i == NI - 1) {
+            } else if (q == NI - 1) {
                 if (read_next) xf[j] = read_x(slot_n, kk_n, j);
-            } else if (i <= 2) {
-                const int l = (i - 1) * NJ + j;
+            } else if (q <= 2) {
+                const int l = (q - 1) * NJ + j;
                 if (l < N_LOADS) issue_one(base, off, kt_l, slot_l, l);
             }
             __builtin_amdgcn_sched_barrier(0);
