@@ -18,6 +18,7 @@
 // Fallback kernel (any K that is a multiple of 8): global -> registers -> LDS, zero-filled K tail.
 // The epilogue rounds to bf16, transposes through the (now idle) LDS and writes whole rows.
 #include <type_traits>
+#include <utility>
 
 #include "internal.h"
 
@@ -28,9 +29,8 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int BM = 256;          // tokens per workgroup tile
-constexpr int BN = 256;          // features per workgroup tile
 constexpr int BK = 64;           // K elements per step
-constexpr int kTileBytes = BM * BK * 2;                  // one operand tile of one K step: 32 KB (BM == BN)
+constexpr int kTileBytes = BM * BK * 2;                  // one operand tile of one K step of the fallback kernel: 32 KB
 constexpr int kStageBytes = 2 * kTileBytes;              // 64 KB
 constexpr int kLdsBytes = 2 * kStageBytes;               // 128 KB
 
@@ -184,28 +184,24 @@ __device__ __forceinline__ void wait_loads() {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Main kernel.  A step's X tile and W tile (32 KB each) travel separately through a ring of five LDS
-// slots: X of K step kt lives in slot (2kt) % 5, W in slot (2kt + 1) % 5.  A K step is two halves of 32 K
-// elements, one v_mfma_f32_16x16x32_bf16 per 16 x 16 output tile and half.  In step kt a wavefront multiplies half 0
-// while reading the fragments of half 1, waits until step kt+1 has landed (its own loads; the barrier covers the
-// other wavefronts'), then multiplies half 1 while reading half 0 of step kt+1.  After that barrier every
-// wavefront is past its last read of step kt, so W of step kt+2 goes into the slot X of step kt used and X of
-// step kt+3 into the slot W of step kt used.  The X loads are issued one at a time during half 0, the W loads
-// during half 1: a wavefront that issues its eight loads of a step in one burst stalls on the address unit, and the
-// MFMAs behind them in program order with it (measured: +340 cycles per step).
+// Main kernel.  A step's X tile and W tile travel through two rings in LDS: three slots for X (X of K step kt in
+// slot kt % 3) and two for W (slot kt % 2) -- 160 KB for a 256 x 256 tile (five times 32 KB), 156 KB for 288 tokens x
+// 192 features (3 x 36 + 2 x 24 KB).  A K step is two halves of 32 K elements, one v_mfma_f32_16x16x32_bf16 per
+// 16 x 16 output tile and half.  In step kt a wavefront multiplies half 0 while reading the fragments of half 1,
+// waits until step kt+1 has landed (its own loads; the barrier covers the other wavefronts'), then multiplies half 1
+// while reading half 0 of step kt+1.  After that barrier every wavefront is past its last read of step kt, so W of
+// step kt+2 goes into the W slot of step kt (during half 1 of step kt) and X of step kt+3 into its X slot (during
+// half 0 of step kt+1).  The loads are issued one at a time between the MFMAs: a wavefront that issues its eight
+// loads of a step in one burst stalls on the address unit, and the MFMAs behind them in program order with it
+// (measured: +340 cycles per step).
 // The MFMAs of a half run token tile by token tile: the X fragment of a token tile is dead after NI MFMAs and is
 // read again for the next half right there (X fragments need one register set), the NI W fragments live through
 // the half and have two sets.  Instruction order inside a half is pinned by a scheduling barrier after every
 // instruction group.
 // ---------------------------------------------------------------------------------------------
-constexpr int kRingSlots = 5;
-constexpr int kRingLdsBytes256 = kRingSlots * 256 * BK * 2;   // 160 KB: tiles of 256 x 256
-constexpr int kRingLdsBytes192 = kRingSlots * 192 * BK * 2;   // 120 KB: tiles of 192 x 192
-
-__device__ __forceinline__ uint32_t ring_add(uint32_t slot, uint32_t n) {   // (slot + n) % 5 for n <= 5
-    const uint32_t t = slot + n;
-    return t >= kRingSlots ? t - kRingSlots : t;
-}
+constexpr int kXSlots = 3, kWSlots = 2;
+constexpr double kPenalty288 = 1.07;   // measured per-flop cost of the 288 x 192 tile against 256 x 256 (4.5 - 8 %)
+constexpr int ring_lds_bytes(int bm, int bn) { return (kXSlots * bm + kWSlots * bn) * BK * 2; }
 
 // One global -> LDS load of 16 bytes per lane: lane l's vector lands at lds_addr + 16*l.  Written as inline
 // assembly so that the compiler does not tie later LDS reads to it with a full vmcnt wait (it cannot tell
@@ -214,19 +210,26 @@ __device__ __forceinline__ void load_to_lds(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory", "m0");
 }
 
-// Tile = (2 * NJ * 16) tokens x (WN * NI * 16) features, square: 256 x 256 with WN = 4, NI = 4, NJ = 8 (8 wavefronts
-// of 64 features x 128 tokens) or 192 x 192 with WN = 2, NI = 6, NJ = 6 (4 wavefronts of 96 x 96).
+// Tile = (2 * NJ * 16) tokens x (WN * NI * 16) features, WN wavefronts along the features x 2 along the tokens:
+//   256 x 256: WN = 4, NI = 4, NJ = 8 (8 wavefronts of 64 features x 128 tokens);
+//   288 x 192: WN = 4, NI = 3, NJ = 9 (8 wavefronts of 48 x 144) -- 9216 tokens x 3072 features are exactly 512 such
+//              tiles, two rounds of 256 compute units, where 432 square tiles are 1.69;
+//   192 x 192: WN = 2, NI = 6, NJ = 6 (4 wavefronts of 96 x 96).
 template <int WN, int NI, int NJ, bool PACKED>
 __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     constexpr int WAVES = 2 * WN;
-    constexpr int TILE = 2 * NJ * 16;              // tokens = features per tile
-    static_assert(TILE == WN * NI * 16, "square tiles only: the ring slots of X and W have one size");
-    constexpr int kTileBytes = TILE * BK * 2;      // one operand tile of one K step
+    constexpr int TM = 2 * NJ * 16, TN = WN * NI * 16;      // tokens, features per tile
+    constexpr int kXBytes = TM * BK * 2, kWBytes = TN * BK * 2;   // one operand tile of one K step
     constexpr int NMFMA = NI * NJ;
-    constexpr int LOADS = TILE / 8 / WAVES;        // global->LDS instructions per lane per operand per step
-    static_assert(LOADS * WAVES * 8 == TILE && NI >= 3 && LOADS <= 2 * NJ && NI <= NJ, "tile shape");
+    // global->LDS instructions per lane and step: a load fills 8 tile rows; the last one of X may exist only for the
+    // first wavefronts (288 rows = 36 loads over 8 wavefronts)
+    constexpr int XLOADS = (TM / 8 + WAVES - 1) / WAVES, WLOADS = TN / 8 / WAVES;
+    constexpr int XLOADS_ALL = TM / 8 / WAVES;              // loads every wavefront issues
+    static_assert(WLOADS * WAVES * 8 == TN && NI >= 3 && NI <= NJ && TM % 8 == 0, "tile shape");
+    static_assert(XLOADS <= (NI > 3 ? 2 : 1) * NJ && WLOADS <= (NI > 3 ? 2 : 1) * NJ, "not enough MFMAs in a half to issue the loads between");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    constexpr uint32_t kWRing = kXSlots * kXBytes;          // the W slots follow the X slots
     const TileCoord tc = tile_of_block(a);
     const uint16_t* __restrict__ W = a.w[tc.tensor];
     const uint32_t K = (uint32_t)a.D;
@@ -237,23 +240,29 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     // load i of this wavefront fills LDS rows (WAVES*i + wave)*8 .. +8 of a tile: lane -> row lane>>3, stored column lane&7
     const unsigned char* xbase = reinterpret_cast<const unsigned char*>(a.x + ((size_t)a.row_begin + tc.m0) * K);
     const unsigned char* wbase = reinterpret_cast<const unsigned char*>(W + (size_t)tc.f0 * K);
-    uint32_t xoff[LOADS], woff[LOADS];
+    uint32_t xoff[XLOADS], woff[WLOADS];
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
+    for (int i = 0; i < XLOADS; ++i) {
         const uint32_t r = (WAVES * i + wave) * 8u + (lane >> 3);
         const uint32_t c = (lane & 7u) ^ swz(r);
         const uint32_t xr = min(r, (uint32_t)a.M - 1u - tc.m0);     // rows past the end re-read the last row; never stored
-        const uint32_t wr = min(r, (uint32_t)a.D - 1u - tc.f0);
         xoff[i] = xr * K * 2u + c * 16u;
+    }
+#pragma unroll
+    for (int i = 0; i < WLOADS; ++i) {
+        const uint32_t r = (WAVES * i + wave) * 8u + (lane >> 3);
+        const uint32_t c = (lane & 7u) ^ swz(r);
+        const uint32_t wr = min(r, (uint32_t)a.D - 1u - tc.f0);
         woff[i] = wr * K * 2u + c * 16u;
     }
-    // load i of one operand tile of K step kt into ring slot `slot`
-    auto issue_one = [&](const unsigned char* base, const uint32_t (&off)[LOADS], uint32_t kt, uint32_t slot, int i) {
-        load_to_lds(base + (size_t)kt * (BK * 2) + off[i], lds0 + slot * kTileBytes + (WAVES * i + wave) * 1024u);
+    const bool last_x_load = XLOADS == XLOADS_ALL || (WAVES * (XLOADS - 1) + wave) * 8u < (uint32_t)TM;   // per wavefront
+    // load i of the X / W tile of K step kt into slot `slot` of its ring
+    auto issue_x = [&](uint32_t kt, uint32_t slot, int i) {
+        if (i < XLOADS_ALL || last_x_load)
+            load_to_lds(xbase + (size_t)kt * (BK * 2) + xoff[i], lds0 + slot * kXBytes + (WAVES * i + wave) * 1024u);
     };
-    auto issue_tile = [&](const unsigned char* base, const uint32_t (&off)[LOADS], uint32_t kt, uint32_t slot) {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) issue_one(base, off, kt, slot, i);
+    auto issue_w = [&](uint32_t kt, uint32_t slot, int i) {
+        load_to_lds(wbase + (size_t)kt * (BK * 2) + woff[i], lds0 + kWRing + slot * kWBytes + (WAVES * i + wave) * 1024u);
     };
 
     // MFMA operand layout: lane l holds 8 K elements (one 16-byte LDS column) of row l%16 of a 16-row fragment, lane
@@ -265,13 +274,13 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     const uint32_t frag_row = lane & 15u, frag_kg = ((lane >> 3) & 2u) | (lane >> 5);
     const uint32_t sw = swz(frag_row);
     const uint32_t x_frag = (wave_t + frag_row) * 128u;
-    const uint32_t w_frag = (wave_f + frag_row) * 128u;
-    // X fragment j / W fragment i of half kk of the step whose X tile sits in slot_x (W: the next slot)
-    auto read_x = [&](uint32_t slot_x, uint32_t kk, int j) {
-        return *reinterpret_cast<const bf16x8*>(smem + slot_x * kTileBytes + x_frag + (((4u * kk + frag_kg) ^ sw) << 4) + j * 2048);
+    const uint32_t w_frag = kWRing + (wave_f + frag_row) * 128u;
+    // X fragment j / W fragment i of half kk of the step that sits in slot xs of the X ring / ws of the W ring
+    auto read_x = [&](uint32_t xs, uint32_t kk, int j) {
+        return *reinterpret_cast<const bf16x8*>(smem + xs * kXBytes + x_frag + (((4u * kk + frag_kg) ^ sw) << 4) + j * 2048);
     };
-    auto read_w = [&](uint32_t slot_x, uint32_t kk, int i) {
-        return *reinterpret_cast<const bf16x8*>(smem + ring_add(slot_x, 1) * kTileBytes + w_frag + (((4u * kk + frag_kg) ^ sw) << 4) + i * 2048);
+    auto read_w = [&](uint32_t ws, uint32_t kk, int i) {
+        return *reinterpret_cast<const bf16x8*>(smem + ws * kWBytes + w_frag + (((4u * kk + frag_kg) ^ sw) << 4) + i * 2048);
     };
 
     f32x4 acc[NI][NJ];   // [feature tile][token tile]
@@ -283,11 +292,17 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
             for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
     const uint32_t n_k = K / BK;   // >= 3 (the host sends shorter K to the fallback kernel)
-    issue_tile(xbase, xoff, 0, 0);
-    issue_tile(wbase, woff, 0, 1);
-    issue_tile(xbase, xoff, 1, 2);
-    issue_tile(wbase, woff, 1, 3);
-    wait_loads<2 * LOADS>();       // step 0 has landed; X1, W1 may still be in flight
+#pragma unroll
+    for (int i = 0; i < XLOADS; ++i) issue_x(0, 0, i);
+#pragma unroll
+    for (int i = 0; i < WLOADS; ++i) issue_w(0, 0, i);
+#pragma unroll
+    for (int i = 0; i < XLOADS; ++i) issue_x(1, 1, i);
+#pragma unroll
+    for (int i = 0; i < WLOADS; ++i) issue_w(1, 1, i);
+    // step 0 has landed; X1, W1 may still be in flight (counted with the loads every wavefront issues: a wavefront
+    // that issues one more waits for a little more than it has to)
+    wait_loads<XLOADS_ALL + WLOADS>();
     __syncthreads();
 
     bf16x8 wf0[NI], wf1[NI], xf[NJ];
@@ -296,13 +311,15 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j) xf[j] = read_x(0, 0, j);
 
-    // One half: MFMA m multiplies W fragment i = m % NI with X fragment j = m / NI.  After the first MFMA of token
-    // tile j < NI, W fragment j of the next half is read into wf_n; after the last MFMA of token tile j its X
-    // fragment is read again for the next half; after the second (then the third) MFMA of token tile j load
-    // number j (NJ + j) of the N_LOADS loads of `base` is issued.  sched_barrier(0) after every group keeps the order.
-    auto half = [&](const bf16x8 (&wf)[NI], bf16x8 (&wf_n)[NI], bool read_next, uint32_t slot_n, uint32_t kk_n, auto n_loads_c,
-                    const unsigned char* base, const uint32_t (&off)[LOADS], uint32_t kt_l, uint32_t slot_l) {
+    // One half: MFMA m multiplies W fragment i with X fragment j = m / NI.  After the first MFMA of token tile j < NI,
+    // W fragment j of the next half is read into wf_n; after the last MFMA of token tile j its X fragment is read
+    // again for the next half; after the second (and, where NI > 3, the third) MFMA of token tile j one load is
+    // issued: X loads of step kt_l into X slot slot_l (LOAD_X) or W loads into W slot slot_l.
+    // sched_barrier(0) after every group keeps the order.
+    auto half = [&](const bf16x8 (&wf)[NI], bf16x8 (&wf_n)[NI], bool read_next, uint32_t xs_n, uint32_t ws_n, uint32_t kk_n,
+                    auto load_x_c, auto n_loads_c, uint32_t kt_l, uint32_t slot_l) {
         constexpr int N_LOADS = decltype(n_loads_c)::value;
+        constexpr bool LOAD_X = decltype(load_x_c)::value;
 #pragma unroll
         for (int m = 0; m < NMFMA; ++m) {
             const int q = m % NI, j = m / NI;                 // q-th MFMA of token tile j
@@ -310,53 +327,58 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (q == 0) {
-                if (j < NI && read_next) wf_n[j] = read_w(slot_n, kk_n, j);
+                if (j < NI && read_next) wf_n[j] = read_w(ws_n, kk_n, j);
             } else if (q == NI - 1) {
-                if (read_next) xf[j] = read_x(slot_n, kk_n, j);
+                if (read_next) xf[j] = read_x(xs_n, kk_n, j);
             } else if (q <= 2) {
                 const int l = (q - 1) * NJ + j;
-                if (l < N_LOADS) issue_one(base, off, kt_l, slot_l, l);
+                if (l < N_LOADS) {
+                    if constexpr (LOAD_X) issue_x(kt_l, slot_l, l);
+                    else issue_w(kt_l, slot_l, l);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // `slot` is the ring slot of X of step kt; W of step kt sits in the next slot.
-    // LOAD_X: X of step kt+2 is issued during half 0 (into the slot W of step kt-1 used);
-    // LOAD_W: W of step kt+2 is issued during half 1 (into the slot X of step kt used).
-    auto k_step = [&](uint32_t kt, uint32_t slot, auto load_x, auto load_w, auto wait, auto next) {
+    // xs / ws: the ring slots of X / W of step kt.
+    // LOAD_X: X of step kt+2 is issued during half 0 (into the X slot step kt-1 used);
+    // LOAD_W: W of step kt+2 is issued during half 1 (into the W slot of step kt itself).
+    auto k_step = [&](uint32_t kt, uint32_t xs, uint32_t ws, auto load_x, auto load_w, auto wait, auto next) {
         constexpr bool LOAD_X = decltype(load_x)::value, LOAD_W = decltype(load_w)::value, NEXT = decltype(next)::value;
         constexpr int WAIT = decltype(wait)::value;
-        using xl = std::integral_constant<int, LOAD_X ? LOADS : 0>;
-        using wl = std::integral_constant<int, LOAD_W ? LOADS : 0>;
-        half(wf0, wf1, true, slot, 1, xl{}, xbase, xoff, kt + 2, ring_add(slot, 4));
+        using xl = std::integral_constant<int, LOAD_X ? XLOADS : 0>;
+        using wl = std::integral_constant<int, LOAD_W ? WLOADS : 0>;
+        const uint32_t xs_next = xs == kXSlots - 1 ? 0u : xs + 1u, xs_prev = xs == 0 ? kXSlots - 1u : xs - 1u;
+        half(wf0, wf1, true, xs, ws, 1, std::true_type{}, xl{}, kt + 2, xs_prev);
         if constexpr (NEXT) {
             wait_loads<WAIT>();
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);
-        half(wf1, wf0, NEXT, ring_add(slot, 2), 0, wl{}, wbase, woff, kt + 2, slot);
+        half(wf1, wf0, NEXT, xs_next, ws ^ 1u, 0, std::false_type{}, wl{}, kt + 2, ws);
     };
     using yes = std::true_type;
     using no = std::false_type;
     const std::integral_constant<int, 0> w0;
-    const std::integral_constant<int, LOADS> w1;      // the X tile of the step after next may still be in flight
-    uint32_t kt = 0, slot = 0;
+    const std::integral_constant<int, XLOADS_ALL> w1;      // the X tile of the step after next may still be in flight
+    uint32_t kt = 0, xs = 0, ws = 0;
     auto advance = [&]() {
         ++kt;
-        slot = ring_add(slot, 2);
+        xs = xs == kXSlots - 1 ? 0u : xs + 1u;
+        ws ^= 1u;
     };
     // At the barrier of step kt the loads in flight, oldest first, are X(kt+1), W(kt+1), X(kt+2): the last may stay.
     while (kt + 2 < n_k) {
-        k_step(kt, slot, yes{}, yes{}, w1, yes{});
+        k_step(kt, xs, ws, yes{}, yes{}, w1, yes{});
         advance();
     }
-    k_step(kt, slot, no{}, no{}, w0, yes{});     // step n_k-2: the last step must have landed completely
+    k_step(kt, xs, ws, no{}, no{}, w0, yes{});     // step n_k-2: the last step must have landed completely
     advance();
-    k_step(kt, slot, no{}, no{}, w0, no{});      // step n_k-1
+    k_step(kt, xs, ws, no{}, no{}, w0, no{});      // step n_k-1
     __syncthreads();
     constexpr int kEpilogueBytes = NJ * 16 * EpilogueRows<NI * 2>::ROWB;   // per wavefront, see store_tile16
-    static_assert(WAVES * kEpilogueBytes <= kRingSlots * kTileBytes, "the epilogue reuses the ring's LDS");
+    static_assert(WAVES * kEpilogueBytes <= ring_lds_bytes(TM, TN), "the epilogue reuses the ring's LDS");
     store_tile16<NI, NJ, PACKED>(acc, smem + wave * kEpilogueBytes, lane, a.y[tc.tensor], (size_t)a.row_begin,
                                  tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
@@ -488,13 +510,13 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.row_begin = shape->rank_begin * Ns;
     a.M = shape->rank_count * Ns;
     a.D = shape->D;
-    if ((int64_t)BM * a.D * 2 >= ((int64_t)1 << 32)) return fail(COCODIFF_ERR_SHAPE, "qkv_proj: D (%d) too large", a.D);
+    if ((int64_t)288 * a.D * 2 >= ((int64_t)1 << 32)) return fail(COCODIFF_ERR_SHAPE, "qkv_proj: D (%d) too large", a.D);
     const bool ring_kernel = a.D % BK == 0 && a.D >= 3 * BK;
 
-    // Tile shape: 256 x 256 does the least operand traffic per flop; 192 x 192 is taken when its tile count fills
-    // the compute units so much better that it wins all the same (small token counts).  Cost = rounds x tile area,
-    // x 1.2 for the smaller tile (measured: per flop it is that much slower on this power-limited part, so three
-    // full rounds of it only tie with two ragged rounds of the large one), a round being one tile on every unit.
+    // Tile shape (tokens x features).  256 x 256 does the least operand traffic per flop; the others are taken when
+    // their tile count fills the compute units so much better that they win all the same.  Cost = rounds x tile area
+    // x a measured per-flop penalty, a round being one tile on every unit: 288 x 192 moves 11 % more operand bytes per
+    // flop, 192 x 192 a third more with half as many wavefronts.
     static const int n_cu = [] {     // asked once (thread-safe initialisation); 0 = could not be read
         int dev = 0, val = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&val, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
@@ -502,13 +524,23 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
         return val;
     }();
     if (n_cu <= 0) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
-    auto tiles_of = [&](int t) { return (int64_t)((a.M + t - 1) / t) * ((a.D + t - 1) / t) * a.n_tensors; };
-    auto rounds_of = [&](int t) { return (tiles_of(t) + n_cu - 1) / n_cu; };
-    const double cost256 = (double)rounds_of(256) * 256.0 * 256.0;
-    const double cost192 = (double)rounds_of(192) * 192.0 * 192.0 * 1.2;
-    static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);      // tuning knob: 192 or 256
-    const bool small_tile = ring_kernel && (forced_tile ? forced_tile == 192 : cost192 < cost256);
-    a.bm = a.bn = small_tile ? 192 : 256;
+    struct TileShape { int bm, bn; double penalty; };
+    static const TileShape shapes[3] = {{256, 256, 1.0}, {288, 192, kPenalty288}, {192, 192, 1.2}};
+    static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);      // tuning knob: 256, 288 or 192 (tokens per tile)
+    int pick = 0;
+    double best = 0.0;
+    for (int i = 0; i < 3; ++i) {
+        const TileShape& t = shapes[i];
+        const int64_t tiles = (int64_t)((a.M + t.bm - 1) / t.bm) * ((a.D + t.bn - 1) / t.bn) * a.n_tensors;
+        const double cost = (double)((tiles + n_cu - 1) / n_cu) * t.bm * t.bn * t.penalty;
+        if (forced_tile ? forced_tile == t.bm : (i == 0 || cost < best)) {
+            pick = i;
+            best = cost;
+        }
+    }
+    a.bm = shapes[pick].bm;
+    a.bn = shapes[pick].bn;
+    if (!ring_kernel) a.bm = a.bn = 256;      // the fallback kernel has one tile shape
     a.tiles_m = (a.M + a.bm - 1) / a.bm;
     a.tiles_n_per_tensor = (a.D + a.bn - 1) / a.bn;
     const uint32_t n_tiles = (uint32_t)a.tiles_m * a.tiles_n_per_tensor * a.n_tensors;
@@ -516,30 +548,35 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     // dynamic LDS above 64 KB needs the attribute, once per process (thread-safe initialisation)
     static const hipError_t attr_rc = [] {
         hipError_t e = hipSuccess;
-        const void* big[2] = {(const void*)qkv_gemm_direct_kernel<4, 4, 8, false>, (const void*)qkv_gemm_direct_kernel<4, 4, 8, true>};
-        const void* small[2] = {(const void*)qkv_gemm_direct_kernel<2, 6, 6, false>, (const void*)qkv_gemm_direct_kernel<2, 6, 6, true>};
-        const void* staged[2] = {(const void*)qkv_gemm_staged_kernel<false>, (const void*)qkv_gemm_staged_kernel<true>};
-        for (int i = 0; i < 2 && e == hipSuccess; ++i) {
-            e = hipFuncSetAttribute(big[i], hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes256);
-            if (e == hipSuccess) e = hipFuncSetAttribute(small[i], hipFuncAttributeMaxDynamicSharedMemorySize, kRingLdsBytes192);
-            if (e == hipSuccess) e = hipFuncSetAttribute(staged[i], hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        }
+        const std::pair<const void*, int> kernels[] = {
+            {(const void*)qkv_gemm_direct_kernel<4, 4, 8, false>, ring_lds_bytes(256, 256)},
+            {(const void*)qkv_gemm_direct_kernel<4, 4, 8, true>, ring_lds_bytes(256, 256)},
+            {(const void*)qkv_gemm_direct_kernel<4, 3, 9, false>, ring_lds_bytes(288, 192)},
+            {(const void*)qkv_gemm_direct_kernel<4, 3, 9, true>, ring_lds_bytes(288, 192)},
+            {(const void*)qkv_gemm_direct_kernel<2, 6, 6, false>, ring_lds_bytes(192, 192)},
+            {(const void*)qkv_gemm_direct_kernel<2, 6, 6, true>, ring_lds_bytes(192, 192)},
+            {(const void*)qkv_gemm_staged_kernel<false>, kLdsBytes},
+            {(const void*)qkv_gemm_staged_kernel<true>, kLdsBytes}};
+        for (const auto& k : kernels)
+            if (e == hipSuccess) e = hipFuncSetAttribute(k.first, hipFuncAttributeMaxDynamicSharedMemorySize, k.second);
         return e;
     }();
     if (attr_rc != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(attr_rc));
     hipStream_t st = as_stream(stream);
-    if (ring_kernel && small_tile && packed)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 6, 6, true>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
-    else if (ring_kernel && small_tile)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<2, 6, 6, false>), dim3(n_tiles), dim3(256), kRingLdsBytes192, st, a);
-    else if (ring_kernel && packed)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<4, 4, 8, true>), dim3(n_tiles), dim3(512), kRingLdsBytes256, st, a);
-    else if (ring_kernel)
-        hipLaunchKernelGGL((qkv_gemm_direct_kernel<4, 4, 8, false>), dim3(n_tiles), dim3(512), kRingLdsBytes256, st, a);
-    else if (packed)
-        hipLaunchKernelGGL(qkv_gemm_staged_kernel<true>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, st, a);
-    else
-        hipLaunchKernelGGL(qkv_gemm_staged_kernel<false>, dim3(n_tiles), dim3(kStagedThreads), kLdsBytes, st, a);
+    auto launch = [&](auto kernel, int threads, int lds) { hipLaunchKernelGGL(kernel, dim3(n_tiles), dim3(threads), lds, st, a); };
+    if (!ring_kernel) {
+        if (packed) launch(qkv_gemm_staged_kernel<true>, kStagedThreads, kLdsBytes);
+        else launch(qkv_gemm_staged_kernel<false>, kStagedThreads, kLdsBytes);
+    } else if (a.bm == 256) {
+        if (packed) launch(qkv_gemm_direct_kernel<4, 4, 8, true>, 512, ring_lds_bytes(256, 256));
+        else launch(qkv_gemm_direct_kernel<4, 4, 8, false>, 512, ring_lds_bytes(256, 256));
+    } else if (a.bm == 288) {
+        if (packed) launch(qkv_gemm_direct_kernel<4, 3, 9, true>, 512, ring_lds_bytes(288, 192));
+        else launch(qkv_gemm_direct_kernel<4, 3, 9, false>, 512, ring_lds_bytes(288, 192));
+    } else {
+        if (packed) launch(qkv_gemm_direct_kernel<2, 6, 6, true>, 256, ring_lds_bytes(192, 192));
+        else launch(qkv_gemm_direct_kernel<2, 6, 6, false>, 256, ring_lds_bytes(192, 192));
+    }
     return check_launch("qkv_gemm_kernel");
 }
 
