@@ -409,6 +409,36 @@ def test_proj_sampled_rows_at_full_size(oracle, name):
         say(f"proj {name} {w}: {len(ids)} sampled rows, abs {e[0]:.3g} rel {e[1]:.3g}")
 
 
+def test_proj_ragged_edges_of_the_288_token_tile(oracle):
+    """9200 tokens x 3008 features, one weight: 512 tiles of 288 x 192 are two rounds of the compute units where 432
+    square tiles are 1.69, so the host picks the 288 x 192 tile; its last token tile has 272 of 288 rows and its last
+    feature tile 128 of 192 columns.  Rows around both edges against the oracle, and nothing written past the end."""
+    import torch
+    N, H, d = 9200, 47, 64
+    D = H * d
+    rng = np.random.default_rng(2881)
+    x = f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32))
+    w = f32_to_bf16_bits(rng.standard_normal((D, D), dtype=np.float32) * np.float32(D ** -0.5))
+    out = torch.full((N + 16, D), -1, dtype=torch.int16, device="cuda:0")
+    say("proj 9200 x 3008: launch")
+    cd.qkv_proj(cd.Shape.make(N, D, H, d, 1), to_dev(x), None, None, to_dev(w), None, None, out[:N])
+    _sync()
+    got = to_host_bits(out)
+    assert np.all(got[N:] == 0xFFFF), "rows past the last token were written"
+    ids = np.concatenate([np.arange(0, 8), np.arange(280, 296), np.arange(8920, 8936), np.arange(N - 24, N),
+                          rng.choice(N, size=64, replace=False)])
+    e = assert_float_parity(got[ids], oracle.qkv_proj(x[ids], w), "proj 288-token tile")
+    say(f"proj 9200 x 3008: {len(ids)} rows, abs {e[0]:.3g} rel {e[1]:.3g}")
+    # the same through the exchange-buffer epilogue: identical bits after a pack of the plain result
+    sh = cd.Shape.make(N, D, H, d, 1)
+    buf_direct = torch.full((N * D + 64,), -1, dtype=torch.int16, device="cuda:0")
+    buf_packed = dev_empty((N * D,))
+    cd.qkv_proj_pack(sh, to_dev(x), None, None, to_dev(w), None, None, buf_direct[:N * D], cd.RECV_MAJOR)
+    cd.a2a_pack(sh, out[:N], buf_packed, cd.RECV_MAJOR)
+    _sync()
+    assert torch.equal(buf_direct[:N * D], buf_packed) and bool((buf_direct[N * D:] == -1).all().cpu())
+
+
 # ---------------------------------------------------------------------------
 # the whole path, two streams (V first), against the oracle chain
 # ---------------------------------------------------------------------------
