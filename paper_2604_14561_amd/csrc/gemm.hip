@@ -17,8 +17,8 @@
 // the rows' pieces straight into their chunks of the exchange buffer.
 // Fallback kernel (any K that is a multiple of 8): global -> registers -> LDS, zero-filled K tail.
 // The epilogue rounds to bf16, transposes through the (now idle) LDS and writes whole rows.
+#include <initializer_list>
 #include <type_traits>
-#include <utility>
 
 #include "internal.h"
 
@@ -200,7 +200,9 @@ __device__ __forceinline__ void wait_loads() {
 // instruction group.
 // ---------------------------------------------------------------------------------------------
 constexpr int kXSlots = 3, kWSlots = 2;
-constexpr double kPenalty288 = 1.07;   // measured per-flop cost of the 288 x 192 tile against 256 x 256 (4.5 - 8 %)
+constexpr double kPenalty288 = 1.07;   // measured per-flop cost of the 288 x 192 tile against 256 x 256 (4.5 - 8 %):
+                                       // 11 % more operand bytes into LDS and 18 % more fragment reads per flop
+constexpr double kPenalty192 = 1.2;    // 192 x 192: a third more operand bytes, half as many wavefronts
 constexpr int ring_lds_bytes(int bm, int bn) { return (kXSlots * bm + kWSlots * bn) * BK * 2; }
 
 // One global -> LDS load of 16 bytes per lane: lane l's vector lands at lds_addr + 16*l.  Written as inline
@@ -467,6 +469,19 @@ __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArg
 }
 
 
+// A tile shape of the main kernel with its two epilogues and launch parameters.
+struct TileKernel {
+    int bm, bn, threads, lds;
+    double penalty;               // measured per-flop cost against the 256 x 256 tile
+    const void* plain;
+    const void* packed;
+};
+template <int WN, int NI, int NJ>
+TileKernel tile_kernel(double penalty) {
+    return {2 * NJ * 16, WN * NI * 16, 128 * WN, ring_lds_bytes(2 * NJ * 16, WN * NI * 16), penalty,
+            (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, false>, (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, true>};
+}
+
 }  // namespace cocodiff
 
 using namespace cocodiff;
@@ -515,8 +530,7 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
 
     // Tile shape (tokens x features).  256 x 256 does the least operand traffic per flop; the others are taken when
     // their tile count fills the compute units so much better that they win all the same.  Cost = rounds x tile area
-    // x a measured per-flop penalty, a round being one tile on every unit: 288 x 192 moves 11 % more operand bytes per
-    // flop, 192 x 192 a third more with half as many wavefronts.
+    // x a measured per-flop penalty, a round being one tile on every unit.
     static const int n_cu = [] {     // asked once (thread-safe initialisation); 0 = could not be read
         int dev = 0, val = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&val, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
@@ -524,23 +538,22 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
         return val;
     }();
     if (n_cu <= 0) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
-    struct TileShape { int bm, bn; double penalty; };
-    static const TileShape shapes[3] = {{256, 256, 1.0}, {288, 192, kPenalty288}, {192, 192, 1.2}};
-    static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);      // tuning knob: 256, 288 or 192 (tokens per tile)
-    int pick = 0;
+    // (Measured and left out: 224 x 256 equals 288 x 192 at 9216 tokens and nothing else gains from it; 160 x 192,
+    // 256 x 192 and 192 x 256 win a few percent at 2304 tokens only.)
+    static const TileKernel shapes[] = {tile_kernel<4, 4, 8>(1.0), tile_kernel<4, 3, 9>(kPenalty288), tile_kernel<2, 6, 6>(kPenalty192)};
+    static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);      // tuning knob: tokens * 1000 + features of a tile
+    const TileKernel* pick = &shapes[0];
     double best = 0.0;
-    for (int i = 0; i < 3; ++i) {
-        const TileShape& t = shapes[i];
+    for (const TileKernel& t : shapes) {
         const int64_t tiles = (int64_t)((a.M + t.bm - 1) / t.bm) * ((a.D + t.bn - 1) / t.bn) * a.n_tensors;
         const double cost = (double)((tiles + n_cu - 1) / n_cu) * t.bm * t.bn * t.penalty;
-        if (forced_tile ? forced_tile == t.bm : (i == 0 || cost < best)) {
-            pick = i;
+        if (forced_tile ? forced_tile == t.bm * 1000 + t.bn : (&t == &shapes[0] || cost < best)) {
+            pick = &t;
             best = cost;
         }
     }
-    a.bm = shapes[pick].bm;
-    a.bn = shapes[pick].bn;
-    if (!ring_kernel) a.bm = a.bn = 256;      // the fallback kernel has one tile shape
+    a.bm = ring_kernel ? pick->bm : BM;      // the fallback kernel has one tile shape
+    a.bn = ring_kernel ? pick->bn : BM;
     a.tiles_m = (a.M + a.bm - 1) / a.bm;
     a.tiles_n_per_tensor = (a.D + a.bn - 1) / a.bn;
     const uint32_t n_tiles = (uint32_t)a.tiles_m * a.tiles_n_per_tensor * a.n_tensors;
@@ -548,35 +561,23 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     // dynamic LDS above 64 KB needs the attribute, once per process (thread-safe initialisation)
     static const hipError_t attr_rc = [] {
         hipError_t e = hipSuccess;
-        const std::pair<const void*, int> kernels[] = {
-            {(const void*)qkv_gemm_direct_kernel<4, 4, 8, false>, ring_lds_bytes(256, 256)},
-            {(const void*)qkv_gemm_direct_kernel<4, 4, 8, true>, ring_lds_bytes(256, 256)},
-            {(const void*)qkv_gemm_direct_kernel<4, 3, 9, false>, ring_lds_bytes(288, 192)},
-            {(const void*)qkv_gemm_direct_kernel<4, 3, 9, true>, ring_lds_bytes(288, 192)},
-            {(const void*)qkv_gemm_direct_kernel<2, 6, 6, false>, ring_lds_bytes(192, 192)},
-            {(const void*)qkv_gemm_direct_kernel<2, 6, 6, true>, ring_lds_bytes(192, 192)},
-            {(const void*)qkv_gemm_staged_kernel<false>, kLdsBytes},
-            {(const void*)qkv_gemm_staged_kernel<true>, kLdsBytes}};
-        for (const auto& k : kernels)
-            if (e == hipSuccess) e = hipFuncSetAttribute(k.first, hipFuncAttributeMaxDynamicSharedMemorySize, k.second);
+        for (const TileKernel& t : shapes)
+            for (const void* k : {t.plain, t.packed})
+                if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, t.lds);
+        for (const void* k : {(const void*)qkv_gemm_staged_kernel<false>, (const void*)qkv_gemm_staged_kernel<true>})
+            if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         return e;
     }();
     if (attr_rc != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot reserve LDS: %s", hipGetErrorString(attr_rc));
     hipStream_t st = as_stream(stream);
-    auto launch = [&](auto kernel, int threads, int lds) { hipLaunchKernelGGL(kernel, dim3(n_tiles), dim3(threads), lds, st, a); };
-    if (!ring_kernel) {
-        if (packed) launch(qkv_gemm_staged_kernel<true>, kStagedThreads, kLdsBytes);
-        else launch(qkv_gemm_staged_kernel<false>, kStagedThreads, kLdsBytes);
-    } else if (a.bm == 256) {
-        if (packed) launch(qkv_gemm_direct_kernel<4, 4, 8, true>, 512, ring_lds_bytes(256, 256));
-        else launch(qkv_gemm_direct_kernel<4, 4, 8, false>, 512, ring_lds_bytes(256, 256));
-    } else if (a.bm == 288) {
-        if (packed) launch(qkv_gemm_direct_kernel<4, 3, 9, true>, 512, ring_lds_bytes(288, 192));
-        else launch(qkv_gemm_direct_kernel<4, 3, 9, false>, 512, ring_lds_bytes(288, 192));
-    } else {
-        if (packed) launch(qkv_gemm_direct_kernel<2, 6, 6, true>, 256, ring_lds_bytes(192, 192));
-        else launch(qkv_gemm_direct_kernel<2, 6, 6, false>, 256, ring_lds_bytes(192, 192));
-    }
+    void* kernel_args[] = {&a};
+    hipError_t le;
+    if (ring_kernel)
+        le = hipLaunchKernel(packed ? pick->packed : pick->plain, dim3(n_tiles), dim3(pick->threads), kernel_args, pick->lds, st);
+    else
+        le = hipLaunchKernel(packed ? (const void*)qkv_gemm_staged_kernel<true> : (const void*)qkv_gemm_staged_kernel<false>, dim3(n_tiles),
+                             dim3(kStagedThreads), kernel_args, kLdsBytes, st);
+    if (le != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: launch failed: %s", hipGetErrorString(le));
     return check_launch("qkv_gemm_kernel");
 }
 
