@@ -295,7 +295,9 @@ def main() -> int:
             step_fn()
         torch.cuda.synchronize()
         assert int(n_act.cpu()[0]) == cfg.n_changed, "selection did not find the perturbed tiles"
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        # HIP events around the projection launches, in every fourth step of the timed region: with events in every
+        # step the step itself is 2 % slower (six extra marker packets between its five kernels)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] if i % 4 == 0 else None for i in range(args.steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
@@ -304,7 +306,7 @@ def main() -> int:
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         log(f"  host enqueue time per step {(t_enq - t0) * 1e3 / args.steps:.3f} ms of {(t1 - t0) * 1e3 / args.steps:.3f} ms")
-        return (t1 - t0) * 1e3 / args.steps, evs
+        return (t1 - t0) * 1e3 / args.steps, [e for e in evs if e is not None]
 
     ms_per_step, events = time_schedule(step)
     tokens_per_s = N / (ms_per_step * 1e-3)
