@@ -5,10 +5,10 @@ A step is one pass of the whole hot path over one synthetic layer input, all P l
 order of the paper's Section III-C (V is projected first and its layout change and selection run under the
 Q and K work).  Default schedule "fused2", two HIP streams, every result of the path produced (exchange buffers,
 head-parallel Q, K, V, the selection's list and compact V):
-  stream V : qkv_proj_pack(V -> exchange buffer) -> a2a_unpack_select(V, V_prev)
-  stream QK: [after V's projection] qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K)
+  main stream: qkv_proj_pack(V -> exchange buffer) -> qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K)
+  side stream: [after V's projection] a2a_unpack_select(V, V_prev); joined at the end of the step
 (norm + RoPE on the receiving side of the exchange).  "fused3" projects Q and K by two launches and uses a third
-stream; "fused3s" keeps norm + RoPE on the sending side: qkv_proj -> qk_norm_rope_pack -> a2a_unpack.
+stream; "fused2x" swaps the roles of the two streams; "fused3s" keeps norm + RoPE on the sending side: qkv_proj -> qk_norm_rope_pack -> a2a_unpack.
 "vfirst" / "vfirst3" are the same orders through the stand-alone calls only (projection, norm+RoPE in place, pack,
 unpack, select as separate launches); the default run times "vfirst" too and reports it as `standalone_calls_path`.
 "serial" runs the stand-alone calls on one stream.
@@ -54,7 +54,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--schedule", default="fused2", choices=["vfirst", "vfirst3", "serial", "fused2", "fused3", "fused3s"])
+    ap.add_argument("--schedule", default="fused2", choices=["vfirst", "vfirst3", "serial", "fused2", "fused2x", "fused3", "fused3s"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     args = ap.parse_args()
@@ -120,7 +120,9 @@ def main() -> int:
     del v_prev_host
 
     def step_vfirst(ev=None):
-        """ev: optional (v0, v1, qk0, qk1) timing events bracketing the two projection launches."""
+        """The stand-alone calls in the default schedule's shape: both projections on the main stream, V's pack,
+        unpack and selection on the side stream under the Q and K work.
+        ev: optional (v0, v1, qk0, qk1) timing events bracketing the two projection launches."""
         if ev:
             ev[0].record(s_v)
         cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=s_v)
@@ -128,23 +130,23 @@ def main() -> int:
             ev[1].record(s_v)
         v_ready = torch.cuda.Event()
         v_ready.record(s_v)
-        cd.a2a_pack(sh, v, bv, ORDER, stream=s_v)
-        cd.a2a_unpack(sh, bv, hv, ORDER, stream=s_v)
-        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
-        s_qk.wait_event(v_ready)            # V's projection goes first; its layout change overlaps what follows
         if ev:
-            ev[2].record(s_qk)
-        cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=s_qk)
+            ev[2].record(s_v)
+        cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=s_v)
         if ev:
-            ev[3].record(s_qk)
-        cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=s_qk)
-        cd.a2a_pack(sh, q, bq, ORDER, stream=s_qk)
-        cd.a2a_pack(sh, k, bk, ORDER, stream=s_qk)
-        cd.a2a_unpack(sh, bq, hq, ORDER, stream=s_qk)
-        cd.a2a_unpack(sh, bk, hk, ORDER, stream=s_qk)
+            ev[3].record(s_v)
+        s_qk.wait_event(v_ready)            # V's layout change and selection overlap what follows its projection
+        cd.a2a_pack(sh, v, bv, ORDER, stream=s_qk)
+        cd.a2a_unpack(sh, bv, hv, ORDER, stream=s_qk)
+        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_qk)
+        cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=s_v)
+        cd.a2a_pack(sh, q, bq, ORDER, stream=s_v)
+        cd.a2a_pack(sh, k, bk, ORDER, stream=s_v)
+        cd.a2a_unpack(sh, bq, hq, ORDER, stream=s_v)
+        cd.a2a_unpack(sh, bk, hk, ORDER, stream=s_v)
         done = torch.cuda.Event()
         done.record(s_qk)
-        s_v.wait_event(done)                # join: the next layer cannot start before Q and K are laid out
+        s_v.wait_event(done)                # join: the next layer cannot start before everything is laid out
 
     s_q = torch.cuda.Stream()
 
@@ -200,11 +202,10 @@ def main() -> int:
             cd.a2a_unpack(sh, buf, dst, ORDER, stream=st)
         cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=st)
 
-    def step_fused2(ev=None):
-        """V-First on two streams with the fused calls: V's projection writes its exchange buffer, its unpack carries
-        the selection's flag pass; behind V's projection Q and K are projected by one launch straight into their
-        exchange buffers and normalised and rotated inside one unpack pass (receiving side).  4 launches and 7.2
-        tensor passes over HBM beside the projections, against 13 and 14.2 with the stand-alone calls."""
+    def step_fused2x(ev=None):
+        """fused2 with the streams the other way round (V's projection and its unpack + selection on one stream, the Q
+        and K projection and their unpack on the other, behind an event): the Q and K projection then starts a
+        cross-stream wait later, 2 % more step time at C3."""
         if ev:
             ev[0].record(s_v)
         cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
@@ -223,6 +224,32 @@ def main() -> int:
         done = torch.cuda.Event()
         done.record(s_qk)
         s_v.wait_event(done)                # join: the next layer cannot start before Q and K are laid out
+
+    def step_fused2(ev=None):
+        """V-First with the fused calls on two streams: V's projection writes its exchange buffer; the projection of Q
+        and K (one launch, straight into their exchange buffers) follows it on the same stream, so no cross-stream wait
+        sits between the two projections; V's unpack, which carries the selection's flag pass, waits for V's projection
+        on the side stream and runs under the Q and K projection; Q and K are normalised and rotated inside one unpack
+        pass (receiving side).  4 launches and 7.2 tensor passes over HBM beside the projections, against 13 and 14.2
+        with the stand-alone calls."""
+        if ev:
+            ev[0].record(s_v)
+        cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
+        if ev:
+            ev[1].record(s_v)
+        v_ready = torch.cuda.Event()
+        v_ready.record(s_v)
+        if ev:
+            ev[2].record(s_v)
+        cd.qkv_proj_pack(sh, X, Wq, Wk, None, bq, bk, None, ORDER, stream=s_v)
+        if ev:
+            ev[3].record(s_v)
+        s_qk.wait_event(v_ready)
+        cd.a2a_unpack_select(sh, bv, ORDER, hv, hv_prev, T, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_qk)
+        cd.a2a_unpack_norm_rope(sh, bq, bk, hq, hk, gq, gk, cfg.eps, rope, ORDER, stream=s_v)
+        done = torch.cuda.Event()
+        done.record(s_qk)
+        s_v.wait_event(done)                # join
 
     def step_fused3(ev=None):
         """V-First order with the fused calls: every projection writes its exchange buffer itself (no [N][D] tensor
@@ -286,7 +313,7 @@ def main() -> int:
         s_v.wait_event(done_q)
         s_v.wait_event(done_k)
 
-    schedules = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial, "fused2": step_fused2, "fused3": step_fused3,
+    schedules = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial, "fused2": step_fused2, "fused2x": step_fused2x, "fused3": step_fused3,
                  "fused3s": step_fused3s}
     step = schedules[args.schedule]
 
