@@ -202,7 +202,7 @@ __device__ __forceinline__ void wait_loads() {
 constexpr int kXSlots = 3, kWSlots = 2;
 constexpr double kPenalty288 = 1.07;   // measured per-flop cost of the 288 x 192 tile against 256 x 256 (4.5 - 8 %):
                                        // 11 % more operand bytes into LDS and 18 % more fragment reads per flop
-constexpr double kPenalty192 = 1.2;    // 192 x 192: a third more operand bytes, half as many wavefronts
+constexpr double kPenalty192 = 1.2;    // 192 x 192: a third more operand bytes and twice the fragment reads per flop
 constexpr int ring_lds_bytes(int bm, int bn) { return (kXSlots * bm + kWSlots * bn) * BK * 2; }
 
 // One global -> LDS load of 16 bytes per lane: lane l's vector lands at lds_addr + 16*l.  Written as inline
@@ -216,7 +216,7 @@ __device__ __forceinline__ void load_to_lds(const void* g, uint32_t lds_addr) {
 //   256 x 256: WN = 4, NI = 4, NJ = 8 (8 wavefronts of 64 features x 128 tokens);
 //   288 x 192: WN = 4, NI = 3, NJ = 9 (8 wavefronts of 48 x 144) -- 9216 tokens x 3072 features are exactly 512 such
 //              tiles, two rounds of 256 compute units, where 432 square tiles are 1.69;
-//   192 x 192: WN = 2, NI = 6, NJ = 6 (4 wavefronts of 96 x 96).
+//   192 x 192: WN = 4, NI = 3, NJ = 6 (8 wavefronts of 48 x 96; 2 - 5 % faster than 4 wavefronts of 96 x 96).
 template <int WN, int NI, int NJ, bool PACKED>
 __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     constexpr int WAVES = 2 * WN;
@@ -540,7 +540,7 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     if (n_cu <= 0) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
     // (Measured and left out: 224 x 256 equals 288 x 192 at 9216 tokens and nothing else gains from it; 160 x 192,
     // 256 x 192 and 192 x 256 win a few percent at 2304 tokens only.)
-    static const TileKernel shapes[] = {tile_kernel<4, 4, 8>(1.0), tile_kernel<4, 3, 9>(kPenalty288), tile_kernel<2, 6, 6>(kPenalty192)};
+    static const TileKernel shapes[] = {tile_kernel<4, 4, 8>(1.0), tile_kernel<4, 3, 9>(kPenalty288), tile_kernel<4, 3, 6>(kPenalty192)};
     static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);      // tuning knob: tokens * 1000 + features of a tile
     const TileKernel* pick = &shapes[0];
     double best = 0.0;
