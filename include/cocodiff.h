@@ -187,8 +187,10 @@ COCODIFF_API int cocodiff_a2a_unpack(const cocodiff_shape* shape, const cocodiff
  * Step 4 -- V-Major active-tile selection (Section III-D, threshold-per-tile form).
  * v_cur, v_prev: [S][N][W] bf16 (head-parallel: S = H, W = d; sequence layout: S = 1, W = D).
  * Tile t = tokens [t*tile_tokens, (t+1)*tile_tokens) of every slab s; NT = N / tile_tokens.
- *   flags[t]      = 1 if some element of the tile has NOT(|v_cur - v_prev| <= tau) in fp32, else 0
- *                   (NaN counts as changed; |diff| == tau does not).  [NT] int32, may be NULL.
+ *   flags[t]      = 1 if some element of the tile has NOT(|v_cur - v_prev| <= tau), else 0, decided on the
+ *                   difference of the widened values in double precision, tau widened too (NaN counts as
+ *                   changed; |diff| == tau does not; a difference that an fp32 subtraction would round
+ *                   onto tau still counts as what it is).  [NT] int32, may be NULL.
  *   active_idx[j] = id of the j-th active tile, ascending, j < n_active.  [NT] int32.
  *   *n_active     = number of active tiles (device int32), also when it exceeds cap_tiles.
  *   compact[s][j*tile_tokens + m][w] = v_cur[s][active_idx[j]*tile_tokens + m][w] for

@@ -15,8 +15,9 @@
  *     ascending order and their current values are gathered densely.
  *
  * All data are 16-bit patterns (bf16) copied without interpretation, except
- * the selection's comparison, which widens bf16 to fp32 exactly and takes the
- * decision in fp32 (the precision the GPU kernel decides in).
+ * the selection's comparison, which widens both bf16 values and the fp32
+ * threshold to double exactly and takes the decision on the double difference
+ * (exact whenever the two exponents are less than 45 binary orders apart).
  *
  * Outer loops carry an OpenMP pragma; nothing is blocked, fused or reordered.
  */
@@ -76,16 +77,16 @@ void oracle_a2a_unpack(const uint16_t* xbuf, uint16_t* y, int N, int H, int d, i
         }
 }
 
-static inline float bf16_to_f32(uint16_t b) {
+static inline double bf16_to_f64(uint16_t b) {
     uint32_t u = (uint32_t)b << 16;
     float f;
     memcpy(&f, &u, sizeof f);
-    return f;
+    return (double)f;
 }
 
 /*
  * cur, prev: [S][N][W].  Tile t = tokens [t*T, (t+1)*T) of every slab s.
- * flag[t] = 1 iff some element has NOT(|cur - prev| <= tau)   (so NaN counts as changed).
+ * flag[t] = 1 iff some element has NOT(|double(cur) - double(prev)| <= double(tau))   (so NaN counts as changed).
  * idx: ascending active tile ids; compact[s][j*T + (n - t*T)][w] = cur[s][n][w] for the j-th
  * active tile t, for j < cap_tiles; the compact buffer is [S][cap_tiles*T][W].
  * Returns the number of active tiles (also beyond cap_tiles).
@@ -100,8 +101,8 @@ int oracle_vmajor_select(int S, int N, int W, int T, const uint16_t* cur, const 
             for (int n = t * T; n < (t + 1) * T; ++n)
                 for (int w = 0; w < W; ++w) {
                     const int64_t e = ((int64_t)s * N + n) * W + w;
-                    const float diff = fabsf(bf16_to_f32(cur[e]) - bf16_to_f32(prev[e]));
-                    if (!(diff <= tau)) active = 1;
+                    const double diff = fabs(bf16_to_f64(cur[e]) - bf16_to_f64(prev[e]));
+                    if (!(diff <= (double)tau)) active = 1;
                 }
         flags[t] = active;
     }

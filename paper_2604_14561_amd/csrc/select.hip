@@ -1,5 +1,5 @@
 // V-Major active-tile selection (paper Section III-D), threshold-per-tile form:
-//   flag[t] = any element of tile t with NOT(|v_cur - v_prev| <= tau)   (fp32 decision)
+//   flag[t] = any element of tile t with NOT(|v_cur - v_prev| <= tau)   (decided on the difference in double)
 //   idx     = ascending list of flagged tiles, n_active = its length
 //   compact = v_cur of the flagged tiles gathered densely in list order.
 //
@@ -28,16 +28,30 @@ struct SelectShape {
     uint64_t slab8;         // vectors per slab = N*W/8
 };
 
+// The decision is NOT(|double(c) - double(p)| <= double(tau)).  The fp32 difference d = fl(c - p) decides it whenever
+// |d| != tau (rounding is monotonic and tau is an fp32 value: |x| <= tau gives |d| <= tau, |d| > tau gives |x| > tau);
+// only |d| == tau can hide a difference that exceeds tau by less than half an fp32 ulp, and those vectors are
+// compared again in double.
 __device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, float tau) {
     const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
     const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
-    bool changed = false;
+    bool changed = false, tie = false;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const float dl = fabsf(bf16_lo(cw[i]) - bf16_lo(pw[i]));
         const float dh = fabsf(bf16_hi(cw[i]) - bf16_hi(pw[i]));
         changed |= !(dl <= tau);
         changed |= !(dh <= tau);
+        tie |= dl == tau;
+        tie |= dh == tau;
+    }
+    if (tie && !changed) {
+        const double tau_d = (double)tau;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            changed |= !(fabs((double)bf16_lo(cw[i]) - (double)bf16_lo(pw[i])) <= tau_d);
+            changed |= !(fabs((double)bf16_hi(cw[i]) - (double)bf16_hi(pw[i])) <= tau_d);
+        }
     }
     return changed;
 }

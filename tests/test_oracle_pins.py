@@ -447,6 +447,38 @@ def test_select_edge_cases(oracle):
     assert n == NT and compact.shape == (S, 2 * T, W) and np.array_equal(compact, cur[:, :2 * T, :])
 
 
+def test_select_decides_on_the_exact_difference_not_on_its_fp32_rounding(oracle):
+    """|cur - prev| can exceed tau by less than half an fp32 ulp (exponents more than 16 binary orders apart): an fp32
+    subtraction rounds such a difference onto tau and would call the tile unchanged.  The definition compares the
+    difference itself; exact rational arithmetic on the bit patterns is the judge here."""
+    from fractions import Fraction
+    S, N, W, T = 1, 64, 8, 16
+    NT = N // T
+
+    def frac(bits16):
+        return Fraction(float(bf16_bits_to_f32(np.array([bits16], dtype=np.uint16))[0]))
+
+    cases = [  # (cur, prev, tau, active?)
+        (2.0 ** -9, -(2.0 ** -40), 2.0 ** -9, True),      # fp32: 2^-9 + 2^-40 rounds to 2^-9 = tau
+        (2.0 ** -9, 2.0 ** -40, 2.0 ** -9, False),        # just below tau on the other side
+        (-(2.0 ** -9), 2.0 ** -40, 2.0 ** -9, True),      # mirrored signs
+        (1.0, -(2.0 ** -30), 1.0, True),
+        (1.0, 2.0 ** -30, 1.0, False),
+        (1.5, 0.5 - 2.0 ** -8, 1.0, True),                # ordinary: 1 + 2^-8 > 1
+        (1.5, 0.5, 1.0, False),                           # exactly tau
+    ]
+    for t_case, (c, p, tau, want) in enumerate(cases):
+        cur = np.zeros((S, N, W), dtype=np.uint16)
+        prev = np.zeros((S, N, W), dtype=np.uint16)
+        t = t_case % NT
+        cur[0, t * T + 5, 3], prev[0, t * T + 5, 3] = _bits([c])[0], _bits([p])[0]
+        assert bf16_bits_to_f32(cur[0, t * T + 5, 3:4])[0] == np.float32(c) and bf16_bits_to_f32(prev[0, t * T + 5, 3:4])[0] == np.float32(p)
+        exact_active = abs(frac(cur[0, t * T + 5, 3]) - frac(prev[0, t * T + 5, 3])) > Fraction(float(np.float32(tau)))
+        assert exact_active == want
+        flags, idx, n, _ = oracle.vmajor_select(cur, prev, tau, T)
+        assert (n == 1 and idx.tolist() == [t] and flags[t] == 1) if want else (n == 0 and not flags.any()), (c, p, tau)
+
+
 def test_select_scatter_back_leaves_nothing_active(oracle):
     cfg = CONFIGS["C1"]
     cur, prev, changed = make_v_pair(cfg)
