@@ -31,7 +31,10 @@
  *     kernel attribute (LDS above 64 KB) and must happen outside a capture;
  *   - inputs are not modified; outputs must not alias inputs unless "in place" is stated;
  *   - bf16 values are raw 16-bit patterns (cocodiff_bf16); float arithmetic is fp32
- *     inside the kernels with one round-to-nearest-even to bf16 at each kernel's output.
+ *     inside the kernels with one round-to-nearest-even to bf16 at each kernel's output;
+ *   - the library reads no environment variable: which kernel runs depends on the arguments and the
+ *     device only (measurement builds compiled with -DCOCODIFF_TUNING read a few COCODIFF_* tuning
+ *     variables; the shipped build does not).
  */
 #ifndef COCODIFF_H
 #define COCODIFF_H
@@ -283,6 +286,13 @@ COCODIFF_API int cocodiff_a2a_unpack_seq(const cocodiff_shape* shape, const coco
                                          int slot_order, void* stream);
 
 /* Host helpers (not on the hot path). */
+
+/* Which tile the projection takes for this shape's rank range and n_tensors (1..3) weights in one launch, on the
+ * current device: tile extent in tokens and features, number of workgroups (= tiles), compute units of the device.
+ * Any out pointer may be NULL.  Host arithmetic only; it needs a current HIP device for the unit count
+ * (COCODIFF_ERR_HIP without one).  For reports and for tests that must land on a given tile shape. */
+COCODIFF_API int cocodiff_qkv_proj_plan(const cocodiff_shape* shape, int32_t n_tensors, int32_t* tile_tokens,
+                                        int32_t* tile_features, int32_t* n_tiles, int32_t* n_compute_units);
 
 /* Bytes of the cos/sin table described at cocodiff_rope (0 on a bad description; `cs` is ignored). */
 COCODIFF_API size_t cocodiff_rope_table_bytes(const cocodiff_rope* rope);

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     qk_norm_rope_pack,
     qkv_proj,
     qkv_proj_pack,
+    qkv_proj_plan,
     rope_table,
     util_copy,
     util_mfma_rate,

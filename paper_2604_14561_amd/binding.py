@@ -25,7 +25,7 @@ EXPORTS = (
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
     "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
-    "cocodiff_rope_table_fill", "cocodiff_util_copy", "cocodiff_util_mfma_rate", "cocodiff_version", "cocodiff_last_error",
+    "cocodiff_rope_table_fill", "cocodiff_qkv_proj_plan", "cocodiff_util_copy", "cocodiff_util_mfma_rate", "cocodiff_version", "cocodiff_last_error",
 )
 
 
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_rope_table_bytes.restype = sz
         L.cocodiff_rope_table_fill.argtypes = [rp, vp]
         L.cocodiff_util_copy.argtypes = [vp, vp, sz, vp]
+        L.cocodiff_qkv_proj_plan.argtypes = [sp, i32, vp, vp, vp, vp]
+        L.cocodiff_qkv_proj_plan.restype = ci
         L.cocodiff_version.restype = ctypes.c_char_p
         L.cocodiff_last_error.restype = ctypes.c_char_p
         L.cocodiff_util_mfma_rate.argtypes = [i32, i32, vp, vp]
@@ -238,6 +240,13 @@ def rope_table(grid: Sequence[int], pairs: Sequence[int], theta: float) -> np.nd
     out = np.empty(nbytes // 4, dtype=np.float32)
     _check(lib().cocodiff_rope_table_fill(ctypes.byref(r), out.ctypes.data_as(ctypes.c_void_p)))
     return out
+
+
+def qkv_proj_plan(shape: Shape, n_tensors: int) -> dict:
+    """Tile shape and workgroup count the projection takes for this shape and number of weights per launch."""
+    out = [ctypes.c_int32(0) for _ in range(4)]
+    _check(lib().cocodiff_qkv_proj_plan(ctypes.byref(shape), int(n_tensors), *(ctypes.byref(o) for o in out)))
+    return {"tile_tokens": out[0].value, "tile_features": out[1].value, "n_tiles": out[2].value, "compute_units": out[3].value}
 
 
 def util_copy(src, dst, nbytes: int, stream=None) -> None:

@@ -482,6 +482,55 @@ TileKernel tile_kernel(double penalty) {
             (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, false>, (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, true>};
 }
 
+// The tile shapes of the main kernel, and which one a launch of M tokens x D features x n_tensors weights takes.
+// 256 x 256 does the least operand traffic per flop; the others are taken when their tile count fills the compute
+// units so much better that they win all the same.  Cost = rounds x tile area x a measured per-flop penalty, a round
+// being one tile on every unit.  (Measured and left out: 224 x 256 equals 288 x 192 at 9216 tokens and nothing else
+// gains from it; 160 x 192, 256 x 192 and 192 x 256 win a few percent at 2304 tokens only.)
+static const TileKernel* tile_shapes(int* count) {
+    static const TileKernel shapes[] = {tile_kernel<4, 4, 8>(1.0), tile_kernel<4, 3, 9>(kPenalty288), tile_kernel<4, 3, 6>(kPenalty192)};
+    *count = (int)(sizeof(shapes) / sizeof(shapes[0]));
+    return shapes;
+}
+
+struct LaunchPlan {
+    const TileKernel* pick;    // nullptr: the compute-unit count could not be read
+    bool ring_kernel;          // false: the general kernel (K not a multiple of 64, or shorter than three steps)
+    int32_t bm, bn, tiles_m, tiles_n_per_tensor, n_cu;
+};
+
+static LaunchPlan plan_launch(int32_t M, int32_t D, int32_t n_tensors) {
+    static const int n_cu = [] {     // asked once (thread-safe initialisation); 0 = could not be read
+        int dev = 0, val = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&val, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        return val;
+    }();
+    LaunchPlan p{};
+    p.n_cu = n_cu;
+    if (n_cu <= 0) return p;
+    int n_shapes = 0;
+    const TileKernel* shapes = tile_shapes(&n_shapes);
+    p.pick = &shapes[0];
+    static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);     // tuning builds only
+    double best = 0.0;
+    for (int i = 0; i < n_shapes; ++i) {
+        const TileKernel& t = shapes[i];
+        const int64_t tiles = (int64_t)((M + t.bm - 1) / t.bm) * ((D + t.bn - 1) / t.bn) * n_tensors;
+        const double cost = (double)((tiles + n_cu - 1) / n_cu) * t.bm * t.bn * t.penalty;
+        if (forced_tile ? forced_tile == t.bm * 1000 + t.bn : (i == 0 || cost < best)) {
+            p.pick = &t;
+            best = cost;
+        }
+    }
+    p.ring_kernel = D % BK == 0 && D >= 3 * BK;
+    p.bm = p.ring_kernel ? p.pick->bm : BM;      // the general kernel has one tile shape
+    p.bn = p.ring_kernel ? p.pick->bn : BM;
+    p.tiles_m = (M + p.bm - 1) / p.bm;
+    p.tiles_n_per_tensor = (D + p.bn - 1) / p.bn;
+    return p;
+}
+
 }  // namespace cocodiff
 
 using namespace cocodiff;
@@ -526,44 +575,24 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.M = shape->rank_count * Ns;
     a.D = shape->D;
     if ((int64_t)288 * a.D * 2 >= ((int64_t)1 << 32)) return fail(COCODIFF_ERR_SHAPE, "qkv_proj: D (%d) too large", a.D);
-    const bool ring_kernel = a.D % BK == 0 && a.D >= 3 * BK;
-
-    // Tile shape (tokens x features).  256 x 256 does the least operand traffic per flop; the others are taken when
-    // their tile count fills the compute units so much better that they win all the same.  Cost = rounds x tile area
-    // x a measured per-flop penalty, a round being one tile on every unit.
-    static const int n_cu = [] {     // asked once (thread-safe initialisation); 0 = could not be read
-        int dev = 0, val = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&val, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-            return 0;
-        return val;
-    }();
-    if (n_cu <= 0) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
-    // (Measured and left out: 224 x 256 equals 288 x 192 at 9216 tokens and nothing else gains from it; 160 x 192,
-    // 256 x 192 and 192 x 256 win a few percent at 2304 tokens only.)
-    static const TileKernel shapes[] = {tile_kernel<4, 4, 8>(1.0), tile_kernel<4, 3, 9>(kPenalty288), tile_kernel<4, 3, 6>(kPenalty192)};
-    static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);      // tuning knob: tokens * 1000 + features of a tile
-    const TileKernel* pick = &shapes[0];
-    double best = 0.0;
-    for (const TileKernel& t : shapes) {
-        const int64_t tiles = (int64_t)((a.M + t.bm - 1) / t.bm) * ((a.D + t.bn - 1) / t.bn) * a.n_tensors;
-        const double cost = (double)((tiles + n_cu - 1) / n_cu) * t.bm * t.bn * t.penalty;
-        if (forced_tile ? forced_tile == t.bm * 1000 + t.bn : (&t == &shapes[0] || cost < best)) {
-            pick = &t;
-            best = cost;
-        }
-    }
-    a.bm = ring_kernel ? pick->bm : BM;      // the fallback kernel has one tile shape
-    a.bn = ring_kernel ? pick->bn : BM;
-    a.tiles_m = (a.M + a.bm - 1) / a.bm;
-    a.tiles_n_per_tensor = (a.D + a.bn - 1) / a.bn;
+    const LaunchPlan plan = plan_launch(a.M, a.D, a.n_tensors);
+    if (!plan.pick) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
+    const TileKernel* pick = plan.pick;
+    const bool ring_kernel = plan.ring_kernel;
+    a.bm = plan.bm;
+    a.bn = plan.bn;
+    a.tiles_m = plan.tiles_m;
+    a.tiles_n_per_tensor = plan.tiles_n_per_tensor;
     const uint32_t n_tiles = (uint32_t)a.tiles_m * a.tiles_n_per_tensor * a.n_tensors;
 
     // dynamic LDS above 64 KB needs the attribute, once per process (thread-safe initialisation)
     static const hipError_t attr_rc = [] {
         hipError_t e = hipSuccess;
-        for (const TileKernel& t : shapes)
-            for (const void* k : {t.plain, t.packed})
-                if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, t.lds);
+        int n_shapes = 0;
+        const TileKernel* shapes = tile_shapes(&n_shapes);
+        for (int i = 0; i < n_shapes; ++i)
+            for (const void* k : {shapes[i].plain, shapes[i].packed})
+                if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, shapes[i].lds);
         for (const void* k : {(const void*)qkv_gemm_staged_kernel<false>, (const void*)qkv_gemm_staged_kernel<true>})
             if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         return e;
@@ -591,4 +620,18 @@ extern "C" int cocodiff_qkv_proj_pack(const cocodiff_shape* shape, const cocodif
                                       const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
                                       cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, cocodiff_bf16* vbuf, int slot_order, void* stream) {
     return proj_launch(shape, x, wq, wk, wv, qbuf, kbuf, vbuf, true, slot_order, stream);
+}
+
+extern "C" int cocodiff_qkv_proj_plan(const cocodiff_shape* shape, int32_t n_tensors, int32_t* tile_tokens, int32_t* tile_features,
+                                      int32_t* n_tiles, int32_t* n_compute_units) {
+    int rc = check_shape(shape);
+    if (rc != COCODIFF_OK) return rc;
+    if (n_tensors < 1 || n_tensors > 3) return fail(COCODIFF_ERR_SHAPE, "qkv_proj_plan: n_tensors (%d) must be 1, 2 or 3", n_tensors);
+    const LaunchPlan p = plan_launch(shape->rank_count * (shape->N / shape->P), shape->D, n_tensors);
+    if (!p.pick) return fail(COCODIFF_ERR_HIP, "qkv_proj_plan: cannot read the compute-unit count");
+    if (tile_tokens) *tile_tokens = p.bm;
+    if (tile_features) *tile_features = p.bn;
+    if (n_tiles) *n_tiles = p.tiles_m * p.tiles_n_per_tensor * n_tensors;
+    if (n_compute_units) *n_compute_units = p.n_cu;
+    return COCODIFF_OK;
 }

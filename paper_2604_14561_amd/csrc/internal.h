@@ -31,11 +31,18 @@ inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s);
 //     place) are non-temporal;
 //   * other loads are cached while the launch touches less than ~192 MB (a consumer may find its producer's
 //     output on chip) and non-temporal above.
-// COCODIFF_STREAM_LD_MB / _ST_MB / _ONCE_MB in the environment (read once) move the three thresholds: tuning
-// knobs, not part of the interface.
+// The library as shipped reads no environment variable.  A build with -DCOCODIFF_TUNING (measurement sweeps only)
+// reads, once: COCODIFF_STREAM_LD_MB / _ST_MB / _ONCE_MB (the three thresholds below), COCODIFF_GEMM_TILE
+// (tokens * 1000 + features: forces a projection tile shape) and COCODIFF_UNPACK_HPZ (heads per lane batch of the
+// normalising unpack).
 inline size_t tune_value(const char* name, size_t dflt) {
+#ifdef COCODIFF_TUNING
     const char* e = getenv(name);
     return e ? (size_t)strtoull(e, nullptr, 10) : dflt;
+#else
+    (void)name;
+    return dflt;
+#endif
 }
 inline bool stream_loads(size_t bytes_touched) {
     static const size_t threshold = tune_value("COCODIFF_STREAM_LD_MB", 192) << 20;

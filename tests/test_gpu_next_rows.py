@@ -72,7 +72,7 @@ def test_second_all_to_all_rank_ranges(oracle):
 
 
 @gpu
-@pytest.mark.parametrize("name", ["C1", "C3", "C5"])
+@pytest.mark.parametrize("name", ["C1", "C3", "C4", "C5"])
 def test_gather_and_scatter_close_the_selection_loop(oracle, name):
     import torch
     cfg = CONFIGS[name]
@@ -150,7 +150,7 @@ def test_gather_scatter_edge_cases(oracle):
 
 
 @gpu
-@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C5"])
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
 def test_token_metric_and_topk(oracle, name):
     import torch
     cfg = CONFIGS[name]
@@ -176,7 +176,18 @@ def test_token_metric_and_topk(oracle, name):
         cd.vmajor_topk(1, N, metric, k, idx, n_act)
         _sync()
         assert int(n_act.cpu()[0]) == k
-        assert np.array_equal(idx.cpu().numpy()[:k], oracle.topk_active(got, k))
+        got_list = idx.cpu().numpy()[:k]
+        assert np.array_equal(got_list, oracle.topk_active(got, k))
+        # ... and against the oracle's own set from the same INPUTS (fp64 metric): the two sets may differ only in
+        # tokens whose fp64 metric lies within the fp32 accumulation error of the cut (the smallest active metric)
+        want_list = oracle.topk_active(want, k)
+        if 0 < k < N:
+            cut = np.sort(want)[N - k]
+            differ = np.setxor1d(got_list, want_list)
+            assert np.all(np.abs(want[differ] - cut) <= 2e-4 * max(cut, 1e-3)), (step, len(differ))
+            assert len(differ) <= 0.01 * N, (step, len(differ))
+        else:
+            assert np.array_equal(got_list, want_list)
     # one segment per logical rank: each rank ranks its own N/P tokens, ids local to the rank
     P, Ns = cfg.P, cfg.N // cfg.P
     n_act = dev_empty((P,), "i32")
@@ -233,7 +244,7 @@ def test_topk_ties_nan_and_extremes(oracle):
 # ---------------------------------------------------------------------------
 
 @gpu
-@pytest.mark.parametrize("name,order", [("C1", 0), ("C1", 1), ("C2", 1), ("C3", 1), ("C5", 0)])
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C1", 1), ("C2", 1), ("C3", 1), ("C4", 0), ("C5", 0)])
 def test_proj_pack_equals_proj_then_pack(oracle, name, order):
     cfg = CONFIGS[name]
     print(f"proj_pack {name} order {order}", flush=True)
@@ -273,7 +284,7 @@ def test_proj_pack_equals_proj_then_pack(oracle, name, order):
 
 
 @gpu
-@pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C5", 1)])
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C4", 0), ("C5", 1)])
 def test_norm_rope_pack_equals_norm_rope_then_pack(oracle, name, order):
     import torch
     cfg = CONFIGS[name]
@@ -321,7 +332,7 @@ def test_norm_rope_pack_equals_norm_rope_then_pack(oracle, name, order):
 
 
 @gpu
-@pytest.mark.parametrize("name,order", [("C1", 0), ("C1", 1), ("C2", 1), ("C3", 1), ("C5", 0)])
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C1", 1), ("C2", 1), ("C3", 1), ("C4", 1), ("C5", 0)])
 def test_unpack_norm_rope_equals_norm_rope_pack_unpack(oracle, name, order):
     """Normalising on the receiver: raw rows in the exchange buffer, norm + RoPE inside the unpack pass."""
     import torch
@@ -368,7 +379,7 @@ def test_unpack_norm_rope_equals_norm_rope_pack_unpack(oracle, name, order):
 
 
 @gpu
-@pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C5", 0)])
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C4", 0), ("C5", 0)])
 def test_unpack_select_equals_unpack_then_select(oracle, name, order):
     import torch
     cfg = CONFIGS[name]
@@ -447,13 +458,13 @@ def test_next_rows_argument_errors():
 
 
 # ---------------------------------------------------------------------------
-# the benchmark's default schedule: fused entry points on three streams
+# the benchmark's schedules: fused entry points on three and on two streams
 # ---------------------------------------------------------------------------
 
 @gpu
 @pytest.mark.parametrize("name", ["C2", "C3"])
-def test_fused_three_stream_step_equals_standalone_calls_and_oracle(oracle, name):
-    """The step bench.py times by default (V-First order, three streams, fused entry points) against the same step
+def test_fused_steps_equal_standalone_calls_and_oracle(oracle, name):
+    """The fused V-First steps (three streams; then the two-stream form bench.py times by default) against the same step
     through the five stand-alone calls on one stream (bit-identical: every buffer and the selection), and
     sampled rows of its head-parallel Q against the oracle chain."""
     import torch
