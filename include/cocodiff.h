@@ -210,6 +210,22 @@ COCODIFF_API int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t
                            cocodiff_bf16* compact, int32_t cap_tiles,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * cocodiff_vmajor_select for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, results and rules, but no workspace -- the
+ * flag words live in an array the library owns on each GPU (256 KiB per GPU, held until the process ends), so
+ * nothing is allocated or freed by the call, here or by the caller.  Limit: N / tile_tokens <= 65536 tiles
+ * (COCODIFF_ERR_CAPACITY beyond, nothing enqueued).  The device of `stream` must be the current device.  All
+ * calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams without
+ * an ordering between them) race and must use cocodiff_vmajor_select with separate workspaces instead; calls on
+ * one stream, or otherwise ordered, are safe (nothing needs clearing between them).  The first call on a device
+ * resolves the array's address (no allocation; do it outside a graph capture).
+ */
+COCODIFF_API int cocodiff_vmajor_select_static(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
+                                  const cocodiff_bf16* v_cur, const cocodiff_bf16* v_prev, float tau,
+                                  int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                                  cocodiff_bf16* compact, int32_t cap_tiles, void* stream);
+
 /* Bytes of device scratch cocodiff_vmajor_select needs for this shape (0 on a bad shape). */
 COCODIFF_API size_t cocodiff_vmajor_select_workspace_bytes(int32_t S, int32_t N, int32_t W, int32_t tile_tokens);
 

@@ -29,6 +29,7 @@ from .binding import (  # noqa: F401
     vmajor_gather,
     vmajor_scatter,
     vmajor_select,
+    vmajor_select_static,
     vmajor_token_metric,
     vmajor_topk,
     vmajor_select_workspace_bytes,

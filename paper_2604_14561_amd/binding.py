@@ -22,7 +22,7 @@ SEND_MAJOR, RECV_MAJOR = 0, 1
 EXPORTS = (
     "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack",
     "cocodiff_a2a_unpack_select", "cocodiff_a2a_unpack_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
-    "cocodiff_vmajor_select", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
+    "cocodiff_vmajor_select", "cocodiff_vmajor_select_static", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
     "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_bytes",
     "cocodiff_rope_table_fill", "cocodiff_qkv_proj_plan", "cocodiff_util_copy", "cocodiff_util_mfma_rate", "cocodiff_version", "cocodiff_last_error",
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_a2a_pack.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_a2a_unpack.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_vmajor_select.argtypes = [i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.cocodiff_vmajor_select_static.argtypes = [i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, i32, vp]
+        L.cocodiff_vmajor_select_static.restype = ci
         L.cocodiff_vmajor_gather.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
         L.cocodiff_vmajor_scatter.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
         L.cocodiff_vmajor_token_metric.argtypes = [i32, i32, i32, vp, vp, vp, vp]
@@ -198,6 +200,14 @@ def vmajor_select(S: int, N: int, W: int, tile_tokens: int, v_cur, v_prev, tau: 
     _check(lib().cocodiff_vmajor_select(S, N, W, tile_tokens, _ptr(v_cur), _ptr(v_prev), float(tau), _ptr(flags),
                                         _ptr(active_idx), _ptr(n_active), _ptr(compact), int(cap_tiles),
                                         _ptr(workspace), int(workspace_bytes), _stream(stream)))
+
+
+def vmajor_select_static(S: int, N: int, W: int, tile_tokens: int, v_cur, v_prev, tau: float, flags, active_idx,
+                         n_active, compact, cap_tiles: int, stream=None) -> None:
+    """vmajor_select without a workspace: the flag words live in an array the library owns on the GPU."""
+    _check(lib().cocodiff_vmajor_select_static(S, N, W, tile_tokens, _ptr(v_cur), _ptr(v_prev), float(tau), _ptr(flags),
+                                               _ptr(active_idx), _ptr(n_active), _ptr(compact), int(cap_tiles),
+                                               _stream(stream)))
 
 
 def vmajor_gather(S: int, N: int, W: int, tile_tokens: int, x, active_idx, n_active, compact, cap_tiles: int, stream=None) -> None:

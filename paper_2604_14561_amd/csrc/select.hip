@@ -16,9 +16,17 @@
 // The flag pass can take the current values from the exchange buffer of the first all-to-all instead and write
 // the head-parallel tensor on the way (the receiver's unpack and the selection in one pass).
 // The same file holds the gather / scatter of listed tiles (sender-side extraction, receiver-side overwrite).
+#include <mutex>
+
 #include "internal.h"
 
 namespace cocodiff {
+
+// Library-owned flag words for cocodiff_vmajor_select_static: one word per tile, up to kStaticMaxTiles tiles
+// (256 KiB per GPU, held until the process ends).  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and host calls use the per-device address static_scratch() returns.
+constexpr uint32_t kStaticMaxTiles = 1u << 16;
+static __device__ __align__(256) uint32_t scratch[kStaticMaxTiles];
 
 constexpr int kSelThreads = 256;
 constexpr int kSelUnroll = 6;     // 16-byte vectors per tensor a lane keeps in flight
@@ -283,6 +291,45 @@ extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t t
                                       void* workspace, size_t workspace_bytes, void* stream) {
     return select_launch(S, N, W, tile_tokens, v_cur, v_prev, tau, flags, active_idx, n_active, compact, cap_tiles, workspace,
                          workspace_bytes, nullptr, stream);
+}
+
+// Address of `scratch` on the current device; asked once per device (every GPU holds its own copy of the array).
+static int static_scratch(uint32_t** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static uint32_t* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(COCODIFF_ERR_HIP, "select_static: no current device: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(COCODIFF_ERR_HIP, "select_static: device %d is outside the %d supported", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(COCODIFF_ERR_HIP, "select_static: cannot resolve the scratch array on device %d: %s", dev, hipGetErrorString(e));
+        ptrs[dev] = static_cast<uint32_t*>(p);
+    }
+    *out = ptrs[dev];
+    return COCODIFF_OK;
+}
+
+extern "C" int cocodiff_vmajor_select_static(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
+                                             const cocodiff_bf16* v_cur, const cocodiff_bf16* v_prev, float tau,
+                                             int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                                             cocodiff_bf16* compact, int32_t cap_tiles, void* stream) {
+    SelectShape sh;
+    int rc = select_shape(S, N, W, tile_tokens, &sh);
+    if (rc != COCODIFF_OK) return rc;
+    if (sh.NT > kStaticMaxTiles)
+        return fail(COCODIFF_ERR_CAPACITY, "select_static: %u tiles exceed the %u the library-owned scratch holds; "
+                    "use cocodiff_vmajor_select with a caller workspace", sh.NT, kStaticMaxTiles);
+    uint32_t* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != COCODIFF_OK) return rc;
+    // the flag pass overwrites every byte of the flag words the gather pass reads: nothing of an earlier call survives
+    return select_launch(S, N, W, tile_tokens, v_cur, v_prev, tau, flags, active_idx, n_active, compact, cap_tiles, ws,
+                         (size_t)kStaticMaxTiles * sizeof(uint32_t), nullptr, stream);
 }
 
 extern "C" int cocodiff_a2a_unpack_select(const cocodiff_shape* shape, const cocodiff_bf16* vbuf, int slot_order,
