@@ -29,7 +29,16 @@ constexpr uint32_t kStaticMaxTiles = 1u << 16;
 static __device__ __align__(256) uint32_t scratch[kStaticMaxTiles];
 
 constexpr int kSelThreads = 256;
-constexpr int kSelUnroll = 6;     // 16-byte vectors per tensor a lane keeps in flight
+constexpr int kSelUnroll = 6;     // 16-byte vectors a lane of the gather / move kernels keeps in flight; a flag-pass share is up to 6 x 256
+// vectors per tensor and lane in one round of the flag pass: plain, and with the unpack inside (measured on tensors of
+// 57, 127 and 613 MB against rounds of 1, 2 and 6)
+#ifndef COCODIFF_FLAG_UNROLL
+#define COCODIFF_FLAG_UNROLL 3
+#endif
+#ifndef COCODIFF_FLAG_UNROLL_PLAIN
+#define COCODIFF_FLAG_UNROLL_PLAIN 3
+#endif
+constexpr int kFlagUnroll = COCODIFF_FLAG_UNROLL, kFlagUnrollPlain = COCODIFF_FLAG_UNROLL_PLAIN;
 
 struct SelectShape {
     uint32_t S, NT, seg8;   // seg8: 16-byte vectors per (tile, slab) segment
@@ -38,31 +47,56 @@ struct SelectShape {
 
 // The decision is NOT(|double(c) - double(p)| <= double(tau)).  The fp32 difference d = fl(c - p) decides it whenever
 // |d| != tau (rounding is monotonic and tau is an fp32 value: |x| <= tau gives |d| <= tau, |d| > tau gives |x| > tau);
-// only |d| == tau can hide a difference that exceeds tau by less than half an fp32 ulp, and those vectors are
-// compared again in double.
-__device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, float tau) {
+// only |d| == tau can hide a difference that exceeds tau by less than half an fp32 ulp, and only vectors with such a
+// tie and no change are compared again in double.
+//   vec_suspect: one compare per element for the streaming loop, NOT(|d| < tau_s): true for every change and every tie
+//                (tau_s = tau, or the smallest positive fp32 when tau is 0, so that equal values are no suspects);
+//   vec_changed: the fp32 decision plus a note of ties (tau_tie = tau, or NaN when tau is 0: a zero fp32 difference of
+//                two bf16 values is exactly zero).
+__device__ __forceinline__ bool vec_suspect(const vec16& c, const vec16& p, float tau_s) {
     const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
     const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
-    bool changed = false, tie = false;
+    bool suspect = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        suspect |= !(fabsf(bf16_lo(cw[i]) - bf16_lo(pw[i])) < tau_s);
+        suspect |= !(fabsf(bf16_hi(cw[i]) - bf16_hi(pw[i])) < tau_s);
+    }
+    return suspect;
+}
+
+__device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, float tau, float tau_tie, bool& tie) {
+    const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+    const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
+    bool changed = false;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const float dl = fabsf(bf16_lo(cw[i]) - bf16_lo(pw[i]));
         const float dh = fabsf(bf16_hi(cw[i]) - bf16_hi(pw[i]));
         changed |= !(dl <= tau);
         changed |= !(dh <= tau);
-        tie |= dl == tau;
-        tie |= dh == tau;
-    }
-    if (tie && !changed) {
-        const double tau_d = (double)tau;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            changed |= !(fabs((double)bf16_lo(cw[i]) - (double)bf16_lo(pw[i])) <= tau_d);
-            changed |= !(fabs((double)bf16_hi(cw[i]) - (double)bf16_hi(pw[i])) <= tau_d);
-        }
+        tie |= dl == tau_tie;
+        tie |= dh == tau_tie;
     }
     return changed;
 }
+
+__device__ __forceinline__ bool vec_changed_double(const vec16& c, const vec16& p, float tau) {
+    const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+    const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
+    const double tau_d = (double)tau;
+    bool changed = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        changed |= !(fabs((double)bf16_lo(cw[i]) - (double)bf16_lo(pw[i])) <= tau_d);
+        changed |= !(fabs((double)bf16_hi(cw[i]) - (double)bf16_hi(pw[i])) <= tau_d);
+    }
+    return changed;
+}
+
+struct Thresholds {
+    float tau, tau_s, tau_tie;   // see vec_suspect / vec_changed
+};
 
 // Where the current tensor comes from when the flag pass also does the receiver-side unpack of the first
 // all-to-all: the exchange buffer, chunk (sender r -> receiver p) = [Ns tokens][Hp heads][d].
@@ -74,51 +108,114 @@ struct UnpackSource {
     int recv_major;
 };
 
+// Division of an index by a launch constant: multiply-high by ceil(2^32 / d), exact while n * d < 2^32 (the host
+// checks the largest n of every use and falls back to the hardware-free plain division otherwise); d = 1 has no magic.
+struct Divisor {
+    uint32_t d, magic;
+};
+template <bool MAGIC>
+__device__ __forceinline__ uint32_t div_by(uint32_t n, const Divisor& f) {
+    if (!MAGIC) return n / f.d;
+    return f.d == 1u ? n : __umulhi(n, f.magic);
+}
+
 // Workgroup (t, part): verdict over vectors [part * share, (part + 1) * share) of tile t's index space
 // g = s * seg8 + v (S segments of seg8 vectors), written to byte `part` of the tile's flag word.
 // FROM_BUF: the current values are read from the exchange buffer (and written to their place in the
 // head-parallel tensor on the way) instead of from `cur`.
-template <bool NT_CUR, bool NT_PREV, bool FROM_BUF>
-__global__ void __launch_bounds__(kSelThreads) select_flag_kernel(const vec16* __restrict__ cur, const vec16* __restrict__ prev,
-                                                                  float tau, uint8_t* __restrict__ flag_bytes, SelectShape sh,
-                                                                  uint32_t share, UnpackSource u) {
+struct FlagPass {
+    const vec16* cur;
+    const vec16* prev;
+    uint8_t* flag_bytes;
+    SelectShape sh;
+    uint32_t share;
+    Thresholds th;
+    UnpackSource u;
+    Divisor seg8, d8, Ns, Hp;
+};
+
+// The share goes in rounds of U vectors per lane.  In a round the streaming part does one compare per element; the
+// workgroup then agrees (one barrier) whether the round holds a suspect.  Without one -- the common case -- its part
+// of the head-parallel tensor is streamed out non-temporally (nobody reads it again soon, nothing stays dirty in L2);
+// with one (a changed tile, as a rule) it is stored cached -- the gather pass reads those vectors again -- and the
+// lanes settle their verdict from the registers.
+// FAST: multiply-high divisions and 32-bit byte offsets from the tensors' base addresses (one address register per
+// vector instead of three 64-bit pointers); the host takes it when every tensor is below 4 GiB and the divisions are
+// exact, else the plain form.
+template <bool FAST> struct OffsetType { typedef uint64_t type; };
+template <> struct OffsetType<true> { typedef uint32_t type; };
+
+template <bool NT_PREV, bool FROM_BUF, int U, bool FAST>
+__global__ void __launch_bounds__(kSelThreads) select_flag_kernel(FlagPass a) {
+    typedef typename OffsetType<FAST>::type off_t;     // byte offsets
     const uint32_t t = blockIdx.x, part = blockIdx.y;
-    const uint32_t total = sh.S * sh.seg8;
-    const uint32_t begin = part * share, end = min(total, begin + share);
-    bool changed = false;
-    // a lane keeps kSelUnroll vectors of each tensor in flight
-    for (uint32_t g0 = begin + threadIdx.x; g0 < end; g0 += kSelUnroll * kSelThreads) {
-        vec16 c[kSelUnroll], p[kSelUnroll];
-        uint64_t hs_at[kSelUnroll];
+    const uint32_t total = a.sh.S * a.sh.seg8;
+    const uint32_t begin = part * a.share, end = min(total, begin + a.share);
+    const char* cur_b = reinterpret_cast<const char*>(a.cur);
+    const char* prev_b = reinterpret_cast<const char*>(a.prev);
+    const char* buf_b = reinterpret_cast<const char*>(a.u.buf);
+    char* hs_b = reinterpret_cast<char*>(a.u.hs_out);
+    const off_t tile_at = (off_t)t * a.sh.seg8;
+    bool changed = false, ever_suspect = false;
+    // the round count is the same for every lane (the barrier inside a round needs the whole workgroup)
+    for (uint32_t base = begin; base < end; base += U * kSelThreads) {
+        vec16 c[U], p[U];
+        off_t at[U];
+        // a vector beyond the share's end reads the share's last vector again (same verdict) and is not stored
 #pragma unroll
-        for (int k = 0; k < kSelUnroll; ++k) {
-            const uint32_t g = g0 + k * kSelThreads;
-            if (g < end) {
-                const uint32_t s = g / sh.seg8, v = g - s * sh.seg8;
-                const uint64_t at = (uint64_t)s * sh.slab8 + (uint64_t)t * sh.seg8 + v;
-                if (FROM_BUF) {
-                    // s is the head, v = (token in tile) * d8 + i8
-                    const uint32_t tl = v / u.d8, i8 = v - tl * u.d8;
-                    const uint32_t n = t * u.T + tl, r = n / u.Ns, m = n - r * u.Ns;
-                    const uint32_t pr = s / u.Hp, hl = s - pr * u.Hp;
-                    const size_t slot = u.recv_major ? (size_t)pr * u.P + r : (size_t)r * u.P + pr;
-                    c[k] = ld_nt(u.buf + slot * u.chunk8 + (size_t)m * u.row8 + hl * u.d8 + i8);
-                    hs_at[k] = at;
-                } else {
-                    c[k] = ld_vec<NT_CUR>(cur + at);
-                }
-                p[k] = ld_vec<NT_PREV>(prev + at);
+        for (int k = 0; k < U; ++k) {
+            const uint32_t g = min(base + threadIdx.x + k * kSelThreads, end - 1u);
+            const uint32_t s = div_by<FAST>(g, a.seg8), v = g - s * a.sh.seg8;
+            at[k] = ((off_t)s * (off_t)a.sh.slab8 + tile_at + v) * 16u;
+            if (FROM_BUF) {
+                // s is the head, v = (token in tile) * d8 + i8
+                const uint32_t tl = div_by<FAST>(v, a.d8), i8 = v - tl * a.u.d8;
+                const uint32_t n = t * a.u.T + tl, r = div_by<FAST>(n, a.Ns), m = n - r * a.u.Ns;
+                const uint32_t pr = div_by<FAST>(s, a.Hp), hl = s - pr * a.u.Hp;
+                const uint32_t slot = a.u.recv_major ? pr * a.u.P + r : r * a.u.P + pr;
+                const off_t from = ((off_t)slot * a.u.chunk8 + (off_t)m * a.u.row8 + hl * a.u.d8 + i8) * 16u;
+                c[k] = ld_nt(reinterpret_cast<const vec16*>(buf_b + from));
+            } else {
+                c[k] = *reinterpret_cast<const vec16*>(cur_b + at[k]);
+            }
+            p[k] = ld_vec<NT_PREV>(reinterpret_cast<const vec16*>(prev_b + at[k]));
+        }
+        bool suspect = false;
+#pragma unroll
+        for (int k = 0; k < U; ++k) suspect |= vec_suspect(c[k], p[k], a.th.tau_s);
+        // the store policy needs the workgroup's verdict; without stores every lane settles its own suspects
+        const bool any_suspect = FROM_BUF ? __syncthreads_or(suspect ? 1 : 0) != 0 : suspect;
+        if (FROM_BUF) {
+            if (any_suspect) {
+#pragma unroll
+                for (int k = 0; k < U; ++k)
+                    if (base + threadIdx.x + k * kSelThreads < end) *reinterpret_cast<vec16*>(hs_b + at[k]) = c[k];
+            } else {
+#pragma unroll
+                for (int k = 0; k < U; ++k)
+                    if (base + threadIdx.x + k * kSelThreads < end) st_nt(reinterpret_cast<vec16*>(hs_b + at[k]), c[k]);
             }
         }
+        if (any_suspect) {
+            ever_suspect = true;
+            bool tie = false, ch = false;
+            // (the empty asm hides the values' origin, or the compiler keeps all 8 * U differences of the streaming
+            // part alive across the barrier to reuse them here: three times the registers)
 #pragma unroll
-        for (int k = 0; k < kSelUnroll; ++k)
-            if (g0 + k * kSelThreads < end) {
-                changed |= vec_changed(c[k], p[k], tau);
-                if (FROM_BUF) u.hs_out[hs_at[k]] = c[k];      // cached store: the gather pass reads the active tiles again
+            for (int k = 0; k < U; ++k) {
+                asm volatile("" : "+v"(c[k]), "+v"(p[k]));
+                ch |= vec_changed(c[k], p[k], a.th.tau, a.th.tau_tie, tie);
             }
+            if (tie && !ch) {
+#pragma unroll
+                for (int k = 0; k < U; ++k) ch |= vec_changed_double(c[k], p[k], a.th.tau);
+            }
+            changed |= ch;
+        }
     }
-    const int any = __syncthreads_or(changed ? 1 : 0) ? 1 : 0;
-    if (threadIdx.x == 0) flag_bytes[4u * t + part] = (uint8_t)any;
+    // with FROM_BUF ever_suspect is the same in every lane: the workgroup takes the barrier together, or not at all
+    const int any = (!FROM_BUF || ever_suspect) ? (__syncthreads_or(changed ? 1 : 0) ? 1 : 0) : 0;
+    if (threadIdx.x == 0) a.flag_bytes[4u * t + part] = (uint8_t)any;
 }
 
 // Sum over the workgroup of one count per lane; every lane gets the total.
@@ -260,12 +357,38 @@ static int select_launch(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
     const uint32_t share = ((per_tile + parts_max - 1) / parts_max + kSelThreads - 1) / kSelThreads * kSelThreads;
     const uint32_t parts = (per_tile + share - 1) / share;                  // every share non-empty
     const uint32_t mask = parts >= 4 ? 0xffffffffu : (1u << (8 * parts)) - 1u;
-    // v_cur stays cached: the second launch reads the active tiles again
-    const UnpackSource src = from_buf ? *from_buf : UnpackSource{};
+    // v_cur stays cached: the second launch reads the active tiles again (streaming loads of v_cur were measured on
+    // tensors of 127 and 613 MB too: 5 % slower and equal)
+    FlagPass fp;
+    fp.cur = (const vec16*)v_cur;
+    fp.prev = (const vec16*)v_prev;
+    fp.flag_bytes = (uint8_t*)tile_flag;
+    fp.sh = sh;
+    fp.share = share;
+    fp.th.tau = tau;
+    fp.th.tau_s = tau > 0.f ? tau : (tau == 0.f ? __builtin_bit_cast(float, 1u) : tau);
+    fp.th.tau_tie = tau > 0.f ? tau : __builtin_nanf("");
+    fp.u = from_buf ? *from_buf : UnpackSource{};
+    // the fast form: multiply-high division is exact while (largest dividend) * divisor < 2^32; 32-bit byte offsets
+    // need every tensor below 4 GiB
+    bool magic = (uint64_t)S * sh.slab8 * 16u < ((uint64_t)1 << 32);
+    auto divisor = [&](uint32_t d, uint64_t max_n) {
+        Divisor f{d ? d : 1u, 0u};
+        if (f.d > 1u) f.magic = (uint32_t)((((uint64_t)1 << 32) + f.d - 1) / f.d);
+        if (max_n * f.d >= ((uint64_t)1 << 32)) magic = false;
+        return f;
+    };
+    fp.seg8 = divisor(sh.seg8, per_tile);
+    fp.d8 = divisor(from_buf ? fp.u.d8 : 1u, sh.seg8);
+    fp.Ns = divisor(from_buf ? fp.u.Ns : 1u, (uint64_t)N);
+    fp.Hp = divisor(from_buf ? fp.u.Hp : 1u, sh.S);
     with_policy(from_buf != nullptr, stream_loads_once(touched), [&](auto F, auto Pv) {
         constexpr bool fb = decltype(F)::value, pv = decltype(Pv)::value;
-        hipLaunchKernelGGL((select_flag_kernel<false, pv, fb>), dim3(sh.NT, parts), dim3(kSelThreads), 0, st, (const vec16*)v_cur,
-                           (const vec16*)v_prev, tau, (uint8_t*)tile_flag, sh, share, src);
+        constexpr int unroll = fb ? kFlagUnroll : kFlagUnrollPlain;
+        if (magic)
+            hipLaunchKernelGGL((select_flag_kernel<pv, fb, unroll, true>), dim3(sh.NT, parts), dim3(kSelThreads), 0, st, fp);
+        else
+            hipLaunchKernelGGL((select_flag_kernel<pv, fb, unroll, false>), dim3(sh.NT, parts), dim3(kSelThreads), 0, st, fp);
     });
     rc = check_launch("select_flag_kernel");
     if (rc != COCODIFF_OK) return rc;
