@@ -2,22 +2,28 @@
 """Benchmark of the Ulysses attention-input path on one MI355X.
 
 A step is one pass of the whole hot path over one synthetic layer input, all P logical ranks, in the V-First
-order of the paper's Section III-C (V is projected first and its layout change and selection run under the
-Q and K work).  Default schedule "fused2", two HIP streams, every result of the path produced (exchange buffers,
-head-parallel Q, K, V, the selection's list and compact V):
-  main stream: qkv_proj_pack(V -> exchange buffer) -> qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K)
-  side stream: [after V's projection] a2a_unpack_select(V, V_prev); joined at the end of the step
-(norm + RoPE on the receiving side of the exchange).  "fused3" projects Q and K by two launches and uses a third
-stream; "fused2x" swaps the roles of the two streams; "fused3s" keeps norm + RoPE on the sending side: qkv_proj -> qk_norm_rope_pack -> a2a_unpack.
-"vfirst" / "vfirst3" are the same orders through the stand-alone calls only (projection, norm+RoPE in place, pack,
-unpack, select as separate launches); the default run times "vfirst" too and reports it as `standalone_calls_path`.
-"serial" runs the stand-alone calls on one stream.
-Inputs are resident in HBM before the timed region.  Prints ONE JSON line on stdout.
+order of the paper's Section III-C (V is projected first; its layout change and selection come before Q's and K's).
+Every headline schedule produces every result of the path: the three exchange buffers of the first all-to-all,
+head-parallel Q (normalised, rotated), K (same) and V, and the selection's flags, list, count and compact V.
+
+  fused1     one stream:  qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_select(V) -> a2a_unpack_norm_rope(Q, K)
+  fused1qkv  one stream:  qkv_proj_pack(V, Q, K in one launch, V's tiles first) -> a2a_unpack_select -> a2a_unpack_norm_rope
+  fused2     two streams: main qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K);
+                          side [after V's projection] a2a_unpack_select(V); joined at the end of the step
+The default run times all three with the same --warmup / --steps and reports each; `value` is the fastest one
+measured in this run (named in config.schedule).  Also timed and reported beside it: the same step through the five
+stand-alone calls only ("vfirst", two streams; "serial", one), the single-GPU direct form that writes V straight
+into the head-parallel layout ("fused1_vdirect": no exchange buffer for V), a HIP-graph replay of the headline
+schedule, the sender's share alone, every kernel alone (HBM-bound ones on cold data), the per-rank back-to-back
+form of the rank-range calls, and the two largest workloads (`other_workloads`).
+Inputs are resident in HBM before any timed region.  Prints ONE JSON line on stdout.
 """
 import argparse
+import glob
 import json
 import os
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -28,16 +34,18 @@ METRIC = "tokens/s per layer (QKV+norm+RoPE+pack); pack/select GB/s vs HBM peak"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "qkv_gemm_hbm_traffic.txt")
+HEADLINE_CANDIDATES = ("fused1", "fused1qkv", "fused2")
 
 
-def measured_traffic(workload: str, schedule: str):
+def measured_traffic(workload: str, kernel_tile: str):
     """Bytes per launch that crossed the L2 <-> memory-fabric boundary for the projection kernel, from the
-    committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs of this script); None if not recorded."""
+    committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs of this script); None if the summary has no
+    line for this workload AND this tile shape (a summary of another kernel form does not count)."""
     try:
         with open(TRAFFIC_FILE) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) >= 4 and parts[0] == "traffic_bytes_per_launch" and parts[1] == workload and parts[2] == schedule:
+                if len(parts) >= 4 and parts[0] == "traffic_bytes_per_launch" and parts[1] == workload and parts[2] == kernel_tile:
                     return int(parts[3])
     except OSError:
         pass
@@ -48,15 +56,355 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+class ChipSampler:
+    """Shader clock (MHz) and socket power (W) read from the amdgpu hwmon files about every 2 ms by a background
+    thread, so that a timed region of a few milliseconds still gets samples; a value that cannot be read is None."""
+
+    def __init__(self):
+        hw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*"))
+        self.power_file = next((p for d in hw for p in (os.path.join(d, "power1_input"), os.path.join(d, "power1_average")) if os.path.exists(p)), None)
+        self.clock_file = next((os.path.join(d, "freq1_input") for d in hw if os.path.exists(os.path.join(d, "freq1_input"))), None)
+        self.samples = []      # (time, MHz or None, W or None)
+        self._stop = threading.Event()
+        self._thread = None
+
+    @staticmethod
+    def _read(path, scale):
+        if not path:
+            return None
+        try:
+            with open(path) as f:
+                return int(f.read()) / scale
+        except (OSError, ValueError):
+            return None
+
+    def _run(self):
+        while not self._stop.is_set():
+            self.samples.append((time.perf_counter(), self._read(self.clock_file, 1e6), self._read(self.power_file, 1e6)))
+            time.sleep(0.002)
+
+    def start(self):
+        self._thread = threading.Thread(target=self._run, daemon=True)
+        self._thread.start()
+
+    def stop(self):
+        self._stop.set()
+        if self._thread:
+            self._thread.join(timeout=5)
+
+    def window(self, t0, t1):
+        """Medians over the samples taken in [t0, t1] (perf_counter times), with the sample count."""
+        import numpy as np
+        rows = [s for s in self.samples if t0 <= s[0] <= t1]
+        mhz = [s[1] for s in rows if s[1] is not None]
+        w = [s[2] for s in rows if s[2] is not None]
+        return {"sclk_MHz": int(np.median(mhz)) if mhz else None, "power_W": int(np.median(w)) if w else None, "samples": len(rows)}
+
+
+class Workload:
+    """Device buffers of one workload and the step functions over them."""
+
+    def __init__(self, cfg, cd, torch, np, dev):
+        from synth import make_layer_inputs, perturb_tiles
+        self.cfg, self.cd, self.torch, self.np = cfg, cd, torch, np
+        N, D, H, d, P, T = cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, cfg.tile_tokens
+        log(f"bench: {cfg.name} N={N} D={D} H={H}x{d} P={P}; generating inputs")
+
+        def up(a):
+            a = np.ascontiguousarray(a)
+            return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+
+        def bf(shape):
+            return torch.empty(shape, dtype=torch.int16, device=dev)
+
+        self.up, self.bf = up, bf
+        self.inp = inp = make_layer_inputs(cfg)
+        self.X, self.Wq, self.Wk, self.Wv = up(inp["X"]), up(inp["Wq"]), up(inp["Wk"]), up(inp["Wv"])
+        self.gq, self.gk = up(inp["gamma_q"]), up(inp["gamma_k"])
+        self.table = up(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta))
+        self.rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, self.table.data_ptr())
+        self.sh = cd.Shape.make(N, D, H, d, P)
+        self.q, self.k, self.v = bf((N, D)), bf((N, D)), bf((N, D))
+        self.bq, self.bk, self.bv = bf((N * D,)), bf((N * D,)), bf((N * D,))
+        self.hq, self.hk, self.hv = bf((H, N, d)), bf((H, N, d)), bf((H, N, d))
+        self.NT = cfg.NT
+        self.cap = self.NT
+        self.ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device=dev)
+        self.flags = torch.empty(self.NT, dtype=torch.int32, device=dev)
+        self.idx = torch.empty(self.NT, dtype=torch.int32, device=dev)
+        self.n_act = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.compact = bf((H, self.cap * T, d))
+        self.s_main, self.s_side, self.s_third = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        self.ORDER = cd.RECV_MAJOR
+        # previous-step V: this layer's own head-parallel V with a seeded fraction of 16-token tiles perturbed
+        cd.qkv_proj(self.sh, self.X, None, None, self.Wv, None, None, self.v)
+        cd.a2a_pack(self.sh, self.v, self.bv, self.ORDER)
+        cd.a2a_unpack(self.sh, self.bv, self.hv, self.ORDER)
+        torch.cuda.synchronize()
+        v_prev_host, _ = perturb_tiles(self.bits(self.hv), 1, T, cfg.n_changed, np.random.default_rng(cfg.index), cfg.noise_sigma)
+        self.hv_prev = up(v_prev_host)
+        del v_prev_host
+        self.schedules = {"fused1": self.step_fused1, "fused1qkv": self.step_fused1qkv, "fused2": self.step_fused2,
+                          "fused2x": self.step_fused2x, "fused3": self.step_fused3, "fused3s": self.step_fused3s,
+                          "fused1_vdirect": self.step_fused1_vdirect,
+                          "vfirst": self.step_vfirst, "vfirst3": self.step_vfirst3, "serial": self.step_serial}
+
+    def bits(self, t):
+        return t.cpu().numpy().view(self.np.uint16)
+
+    # -- helpers ---------------------------------------------------------------------------------------------
+    def proj(self, rec, stream, call):
+        """One projection launch; with a recorder, bracketed by HIP events on the launch stream."""
+        if rec is None:
+            call(stream)
+            return
+        e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        call(stream)
+        e1.record(stream)
+        rec.append((e0, e1))
+
+    def fork(self, src, dst):
+        ev = self.torch.cuda.Event()
+        ev.record(src)
+        dst.wait_event(ev)
+
+    def unpack_select(self, stream):
+        c = self.cfg
+        self.cd.a2a_unpack_select(self.sh, self.bv, self.ORDER, self.hv, self.hv_prev, c.tile_tokens, c.tau, self.flags, self.idx,
+                                  self.n_act, self.compact, self.cap, self.ws, stream=stream)
+
+    def select(self, stream):
+        c = self.cfg
+        self.cd.vmajor_select(c.H, c.N, c.d, c.tile_tokens, self.hv, self.hv_prev, c.tau, self.flags, self.idx, self.n_act,
+                              self.compact, self.cap, self.ws, stream=stream)
+
+    def unpack_norm_rope(self, stream, which="qk"):
+        bq, hq, gq = (self.bq, self.hq, self.gq) if "q" in which else (None, None, None)
+        bk, hk, gk = (self.bk, self.hk, self.gk) if "k" in which else (None, None, None)
+        self.cd.a2a_unpack_norm_rope(self.sh, bq, bk, hq, hk, gq, gk, self.cfg.eps, self.rope, self.ORDER, stream=stream)
+
+    # -- headline schedules (every result of the path) -------------------------------------------------------
+    def step_fused1(self, rec=None):
+        cd, sh, st = self.cd, self.sh, self.s_main
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, None, None, self.Wv, None, None, self.bv, self.ORDER, stream=s))
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, self.Wq, self.Wk, None, self.bq, self.bk, None, self.ORDER, stream=s))
+        self.unpack_select(st)
+        self.unpack_norm_rope(st)
+
+    def step_fused1qkv(self, rec=None):
+        cd, sh, st = self.cd, self.sh, self.s_main
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, self.Wq, self.Wk, self.Wv, self.bq, self.bk, self.bv, self.ORDER, stream=s))
+        self.unpack_select(st)
+        self.unpack_norm_rope(st)
+
+    def step_fused2(self, rec=None):
+        """Both projections on the main stream (no cross-stream wait between them); V's unpack, which carries the
+        selection's flag pass, waits for V's projection on the side stream and runs under the Q and K projection."""
+        cd, sh, st, side = self.cd, self.sh, self.s_main, self.s_side
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, None, None, self.Wv, None, None, self.bv, self.ORDER, stream=s))
+        self.fork(st, side)
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, self.Wq, self.Wk, None, self.bq, self.bk, None, self.ORDER, stream=s))
+        self.unpack_select(side)
+        self.unpack_norm_rope(st)
+        self.fork(side, st)                 # join: the next layer cannot start before everything is laid out
+
+    # -- other forms of the step ----------------------------------------------------------------------------
+    def step_fused2x(self, rec=None):
+        """fused2 with the roles of the streams swapped: the Q and K projection waits behind a cross-stream event."""
+        cd, sh, st, side = self.cd, self.sh, self.s_main, self.s_side
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, None, None, self.Wv, None, None, self.bv, self.ORDER, stream=s))
+        self.fork(st, side)
+        self.unpack_select(st)
+        self.proj(rec, side, lambda s: cd.qkv_proj_pack(sh, self.X, self.Wq, self.Wk, None, self.bq, self.bk, None, self.ORDER, stream=s))
+        self.unpack_norm_rope(side)
+        self.fork(side, st)
+
+    def step_fused3(self, rec=None):
+        """Q and K projected by separate launches, each tensor's unpack under the next projection (three streams)."""
+        cd, sh, st, side, third = self.cd, self.sh, self.s_main, self.s_side, self.s_third
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, None, None, self.Wv, None, None, self.bv, self.ORDER, stream=s))
+        self.fork(st, side)
+        self.unpack_select(st)
+        self.proj(rec, side, lambda s: cd.qkv_proj_pack(sh, self.X, self.Wq, None, None, self.bq, None, None, self.ORDER, stream=s))
+        self.fork(side, third)
+        self.proj(rec, side, lambda s: cd.qkv_proj_pack(sh, self.X, None, self.Wk, None, None, self.bk, None, self.ORDER, stream=s))
+        self.unpack_norm_rope(third, "q")
+        self.unpack_norm_rope(side, "k")
+        self.fork(third, st)
+        self.fork(side, st)
+
+    def step_fused3s(self, rec=None):
+        """Norm + RoPE on the sending side, the order the paper describes: qkv_proj -> qk_norm_rope_pack -> a2a_unpack."""
+        cd, sh, st, side, third, c = self.cd, self.sh, self.s_main, self.s_side, self.s_third, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, None, None, self.Wv, None, None, self.bv, self.ORDER, stream=s))
+        self.fork(st, side)
+        self.unpack_select(st)
+        self.proj(rec, side, lambda s: cd.qkv_proj(sh, self.X, self.Wq, None, None, self.q, None, None, stream=s))
+        self.fork(side, third)
+        self.proj(rec, side, lambda s: cd.qkv_proj(sh, self.X, None, self.Wk, None, None, self.k, None, stream=s))
+        cd.qk_norm_rope_pack(sh, self.q, None, self.gq, None, c.eps, self.rope, self.bq, None, self.ORDER, stream=third)
+        cd.a2a_unpack(sh, self.bq, self.hq, self.ORDER, stream=third)
+        cd.qk_norm_rope_pack(sh, None, self.k, None, self.gk, c.eps, self.rope, None, self.bk, self.ORDER, stream=side)
+        cd.a2a_unpack(sh, self.bk, self.hk, self.ORDER, stream=side)
+        self.fork(third, st)
+        self.fork(side, st)
+
+    def step_fused1_vdirect(self, rec=None):
+        """Single-GPU direct form for V: its projection writes the head-parallel tensor itself (pack, exchange and
+        unpack are the store address), the selection reads it there; no exchange buffer of V exists.  Q and K as in
+        fused1."""
+        cd, sh, st = self.cd, self.sh, self.s_main
+        self.proj(rec, st, lambda s: cd.qkv_proj_hs(sh, self.X, None, None, self.Wv, None, None, self.hv, stream=s))
+        self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, self.Wq, self.Wk, None, self.bq, self.bk, None, self.ORDER, stream=s))
+        self.select(st)
+        self.unpack_norm_rope(st)
+
+    def step_vfirst(self, rec=None):
+        """The stand-alone calls in fused2's shape: both projections on the main stream, V's pack, unpack and selection
+        on the side stream under the Q and K work."""
+        cd, sh, st, side, c = self.cd, self.sh, self.s_main, self.s_side, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj(sh, self.X, None, None, self.Wv, None, None, self.v, stream=s))
+        self.fork(st, side)
+        self.proj(rec, st, lambda s: cd.qkv_proj(sh, self.X, self.Wq, self.Wk, None, self.q, self.k, None, stream=s))
+        cd.a2a_pack(sh, self.v, self.bv, self.ORDER, stream=side)
+        cd.a2a_unpack(sh, self.bv, self.hv, self.ORDER, stream=side)
+        self.select(side)
+        cd.qk_norm_rope(sh, self.q, self.k, self.gq, self.gk, c.eps, self.rope, stream=st)
+        for src, buf, dst in ((self.q, self.bq, self.hq), (self.k, self.bk, self.hk)):
+            cd.a2a_pack(sh, src, buf, self.ORDER, stream=st)
+            cd.a2a_unpack(sh, buf, dst, self.ORDER, stream=st)
+        self.fork(side, st)
+
+    def step_vfirst3(self, rec=None):
+        """V, then Q, then K projected one after the other (the order of the paper's Section III-C); each tensor's
+        norm/RoPE and layout change on a side stream under the next tensor's projection."""
+        cd, sh, st, side, third, c = self.cd, self.sh, self.s_main, self.s_side, self.s_third, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj(sh, self.X, None, None, self.Wv, None, None, self.v, stream=s))
+        self.fork(st, side)
+        cd.a2a_pack(sh, self.v, self.bv, self.ORDER, stream=st)
+        cd.a2a_unpack(sh, self.bv, self.hv, self.ORDER, stream=st)
+        self.select(st)
+        self.proj(rec, side, lambda s: cd.qkv_proj(sh, self.X, self.Wq, None, None, self.q, None, None, stream=s))
+        self.fork(side, third)
+        self.proj(rec, side, lambda s: cd.qkv_proj(sh, self.X, None, self.Wk, None, None, self.k, None, stream=s))
+        cd.qk_norm_rope(sh, self.q, None, self.gq, None, c.eps, self.rope, stream=third)
+        cd.a2a_pack(sh, self.q, self.bq, self.ORDER, stream=third)
+        cd.a2a_unpack(sh, self.bq, self.hq, self.ORDER, stream=third)
+        cd.qk_norm_rope(sh, None, self.k, None, self.gk, c.eps, self.rope, stream=side)
+        cd.a2a_pack(sh, self.k, self.bk, self.ORDER, stream=side)
+        cd.a2a_unpack(sh, self.bk, self.hk, self.ORDER, stream=side)
+        self.fork(third, st)
+        self.fork(side, st)
+
+    def step_serial(self, rec=None):
+        cd, sh, st, c = self.cd, self.sh, self.s_main, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj(sh, self.X, None, None, self.Wv, None, None, self.v, stream=s))
+        self.proj(rec, st, lambda s: cd.qkv_proj(sh, self.X, self.Wq, self.Wk, None, self.q, self.k, None, stream=s))
+        cd.qk_norm_rope(sh, self.q, self.k, self.gq, self.gk, c.eps, self.rope, stream=st)
+        for src, buf, dst in ((self.v, self.bv, self.hv), (self.q, self.bq, self.hq), (self.k, self.bk, self.hk)):
+            cd.a2a_pack(sh, src, buf, self.ORDER, stream=st)
+            cd.a2a_unpack(sh, buf, dst, self.ORDER, stream=st)
+        self.select(st)
+
+    # -- timing ----------------------------------------------------------------------------------------------
+    def check_selection(self):
+        assert int(self.n_act.cpu()[0]) == self.cfg.n_changed, "selection did not find the perturbed tiles"
+
+    def time_steps(self, step_fn, warmup, steps):
+        """`warmup` untimed steps, then exactly `steps` steps between two synchronisations.  Returns
+        (ms per step, (t0, t1) of the timed region on the perf_counter clock)."""
+        torch = self.torch
+        for _ in range(warmup):
+            step_fn()
+        torch.cuda.synchronize()
+        self.check_selection()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step_fn()
+        t_enq = time.perf_counter()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        log(f"    host enqueue {(t_enq - t0) * 1e3 / steps:.3f} ms of {(t1 - t0) * 1e3 / steps:.3f} ms per step")
+        return (t1 - t0) * 1e3 / steps, (t0, t1)
+
+    def projection_in_step(self, step_fn, steps):
+        """A pass of its own (outside every headline timing): `steps` steps with every projection launch bracketed by
+        HIP events on its launch stream.  Returns (average launch duration in us, launches per step, ms per step of
+        this instrumented pass)."""
+        torch = self.torch
+        for _ in range(3):
+            step_fn()
+        torch.cuda.synchronize()
+        rec = []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step_fn(rec)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        total_us = sum(e0.elapsed_time(e1) for e0, e1 in rec) * 1e3
+        return total_us / len(rec), len(rec) / steps, ms
+
+    def tile_name(self, n_tensors):
+        p = self.cd.qkv_proj_plan(self.sh, n_tensors)
+        return f"{p['tile_tokens']}x{p['tile_features']}"
+
+
+def timed_blocks(torch, fns, blocks=7):
+    """us per call: median and minimum over `blocks` blocks of one pass over `fns` (at least 8 calls) between two HIP
+    events on torch's current stream."""
+    st = torch.cuda.current_stream()
+    per_block = len(fns) * max(1, -(-8 // len(fns)))
+    for i in range(min(per_block, 2 * len(fns))):
+        fns[i % len(fns)]()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(blocks + 1)]
+    torch.cuda.synchronize()
+    evs[0].record(st)
+    for blk in range(blocks):
+        for i in range(per_block):
+            fns[i % len(fns)]()
+        evs[blk + 1].record(st)
+    torch.cuda.synchronize()
+    t = sorted(evs[i].elapsed_time(evs[i + 1]) / per_block * 1e3 for i in range(blocks))
+    return t[len(t) // 2], t[0]
+
+
+def time_headline(w, names, warmup, steps, sampler):
+    """Every schedule in `names` with the same warm-up and step count; returns ({name: entry}, fastest name)."""
+    out = {}
+    for name in names:
+        log(f"  schedule {name}")
+        ms, (t0, t1) = w.time_steps(w.schedules[name], warmup, steps)
+        out[name] = {"ms_per_step": round(ms, 4), "value": round(w.cfg.N / (ms * 1e-3), 1)}
+        if sampler:
+            out[name]["chip"] = sampler.window(t0, t1)
+    best = min(out, key=lambda n: out[n]["ms_per_step"])
+    return out, best
+
+
+def roofline_of(w, schedule, steps):
+    """The projection inside the step: an instrumented pass of the schedule."""
+    cfg = w.cfg
+    us, per_step, ms_instr = w.projection_in_step(w.schedules[schedule], steps)
+    flops_per_launch = 2.0 * cfg.N * (3 * cfg.D) * cfg.D / per_step
+    achieved = flops_per_launch / us / 1e6
+    tile = w.tile_name(3 if per_step == 1 else 2)
+    return {"kernel": "qkv_gemm_direct_kernel", "tile": tile, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(cfg.name, tile),
+            "avg_launch_us": round(us, 2), "launches_per_step": round(per_step, 2), "event_steps": steps,
+            "ms_per_step_instrumented": round(ms_instr, 4)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--schedule", default="fused2", choices=["vfirst", "vfirst3", "serial", "fused2", "fused2x", "fused3", "fused3s"])
+    ap.add_argument("--schedule", default="auto", help="auto = time fused1, fused1qkv and fused2, report the fastest; or one schedule's name")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs all P logical ranks of the path on ONE GPU; "
@@ -67,285 +415,49 @@ def main() -> int:
     import torch
 
     import paper_2604_14561_amd as cd
-    from synth import CONFIGS, make_layer_inputs, perturb_tiles
+    from synth import CONFIGS
 
     if not os.path.exists(cd.binding.LIB_PATH):
         from paper_2604_14561_amd import build as _build
         _build.build()
 
-    cfg = CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    sampler = ChipSampler()
+    sampler.start()
+
+    cfg = CONFIGS[args.config]
     N, D, H, d, P, T = cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, cfg.tile_tokens
-    log(f"bench: {cfg.name} N={N} D={D} H={H}x{d} P={P}; generating inputs")
+    w = Workload(cfg, cd, torch, np, dev)
+    if args.schedule != "auto" and args.schedule not in w.schedules:
+        log(f"bench.py: unknown schedule {args.schedule}; one of {sorted(w.schedules)}")
+        return 2
+    names = HEADLINE_CANDIDATES if args.schedule == "auto" else (args.schedule,)
+    per_schedule, best = time_headline(w, names, args.warmup, args.steps, sampler)
+    ms_per_step = per_schedule[best]["ms_per_step"]
+    tokens_per_s = per_schedule[best]["value"]
+    log(f"  headline: {best} {ms_per_step} ms per step; all: { {k_: v_['ms_per_step'] for k_, v_ in per_schedule.items()} }")
+    roofline = roofline_of(w, best, max(args.steps, 50))
+    roofline["chip_during_headline"] = per_schedule[best].get("chip")
 
-    def up(a):
-        a = np.ascontiguousarray(a)
-        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
-
-    def bits(t):
-        return t.cpu().numpy().view(np.uint16)
-
-    inp = make_layer_inputs(cfg)
-    X, Wq, Wk, Wv = up(inp["X"]), up(inp["Wq"]), up(inp["Wk"]), up(inp["Wv"])
-    gq, gk = up(inp["gamma_q"]), up(inp["gamma_k"])
-    table = up(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta))
-    rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, table.data_ptr())
-    sh = cd.Shape.make(N, D, H, d, P)
-
-    def bf(shape):
-        return torch.empty(shape, dtype=torch.int16, device=dev)
-
-    q, k, v = bf((N, D)), bf((N, D)), bf((N, D))
-    bq, bk, bv = bf((N * D,)), bf((N * D,)), bf((N * D,))
-    hq, hk, hv = bf((H, N, d)), bf((H, N, d)), bf((H, N, d))
-    NT = cfg.NT
-    cap = NT
-    ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device=dev)
-    flags = torch.empty(NT, dtype=torch.int32, device=dev)
-    idx = torch.empty(NT, dtype=torch.int32, device=dev)
-    n_act = torch.zeros(1, dtype=torch.int32, device=dev)
-    compact = bf((H, cap * T, d))
-
-    s_v, s_qk = torch.cuda.Stream(), torch.cuda.Stream()
-    ORDER = cd.RECV_MAJOR
-
-    # previous-step V: this layer's own head-parallel V with a seeded fraction of 16-token tiles perturbed
-    cd.qkv_proj(sh, X, None, None, Wv, None, None, v)
-    cd.a2a_pack(sh, v, bv, ORDER)
-    cd.a2a_unpack(sh, bv, hv, ORDER)
-    torch.cuda.synchronize()
-    v_prev_host, changed = perturb_tiles(bits(hv), 1, T, cfg.n_changed, np.random.default_rng(cfg.index), cfg.noise_sigma)
-    hv_prev = up(v_prev_host)
-    del v_prev_host
-
-    def step_vfirst(ev=None):
-        """The stand-alone calls in the default schedule's shape: both projections on the main stream, V's pack,
-        unpack and selection on the side stream under the Q and K work.
-        ev: optional (v0, v1, qk0, qk1) timing events bracketing the two projection launches."""
-        if ev:
-            ev[0].record(s_v)
-        cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=s_v)
-        if ev:
-            ev[1].record(s_v)
-        v_ready = torch.cuda.Event()
-        v_ready.record(s_v)
-        if ev:
-            ev[2].record(s_v)
-        cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=s_v)
-        if ev:
-            ev[3].record(s_v)
-        s_qk.wait_event(v_ready)            # V's layout change and selection overlap what follows its projection
-        cd.a2a_pack(sh, v, bv, ORDER, stream=s_qk)
-        cd.a2a_unpack(sh, bv, hv, ORDER, stream=s_qk)
-        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_qk)
-        cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=s_v)
-        cd.a2a_pack(sh, q, bq, ORDER, stream=s_v)
-        cd.a2a_pack(sh, k, bk, ORDER, stream=s_v)
-        cd.a2a_unpack(sh, bq, hq, ORDER, stream=s_v)
-        cd.a2a_unpack(sh, bk, hk, ORDER, stream=s_v)
-        done = torch.cuda.Event()
-        done.record(s_qk)
-        s_v.wait_event(done)                # join: the next layer cannot start before everything is laid out
-
-    s_q = torch.cuda.Stream()
-
-    def step_vfirst3(ev=None):
-        """V, then Q, then K projected one after the other (the order of the paper's Section III-C); each tensor's
-        norm/RoPE and layout change run on a side stream under the next tensor's projection."""
-        if ev:
-            ev[0].record(s_v)
-        cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=s_v)
-        if ev:
-            ev[1].record(s_v)
-        v_ready = torch.cuda.Event()
-        v_ready.record(s_v)
-        cd.a2a_pack(sh, v, bv, ORDER, stream=s_v)
-        cd.a2a_unpack(sh, bv, hv, ORDER, stream=s_v)
-        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
-        s_qk.wait_event(v_ready)
-        if ev:
-            ev[2].record(s_qk)
-        cd.qkv_proj(sh, X, Wq, None, None, q, None, None, stream=s_qk)
-        q_ready = torch.cuda.Event()
-        q_ready.record(s_qk)
-        cd.qkv_proj(sh, X, None, Wk, None, None, k, None, stream=s_qk)
-        if ev:
-            ev[3].record(s_qk)
-        s_q.wait_event(q_ready)
-        cd.qk_norm_rope(sh, q, None, gq, None, cfg.eps, rope, stream=s_q)
-        cd.a2a_pack(sh, q, bq, ORDER, stream=s_q)
-        cd.a2a_unpack(sh, bq, hq, ORDER, stream=s_q)
-        cd.qk_norm_rope(sh, None, k, None, gk, cfg.eps, rope, stream=s_qk)
-        cd.a2a_pack(sh, k, bk, ORDER, stream=s_qk)
-        cd.a2a_unpack(sh, bk, hk, ORDER, stream=s_qk)
-        done_q, done_k = torch.cuda.Event(), torch.cuda.Event()
-        done_q.record(s_q)
-        done_k.record(s_qk)
-        s_v.wait_event(done_q)
-        s_v.wait_event(done_k)
-
-    def step_serial(ev=None):
-        st = s_v
-        if ev:
-            ev[0].record(st)
-        cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=st)
-        if ev:
-            ev[1].record(st)
-            ev[2].record(st)
-        cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=st)
-        if ev:
-            ev[3].record(st)
-        cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=st)
-        for src, buf, dst in ((v, bv, hv), (q, bq, hq), (k, bk, hk)):
-            cd.a2a_pack(sh, src, buf, ORDER, stream=st)
-            cd.a2a_unpack(sh, buf, dst, ORDER, stream=st)
-        cd.vmajor_select(H, N, d, T, hv, hv_prev, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=st)
-
-    def step_fused2x(ev=None):
-        """fused2 with the streams the other way round (V's projection and its unpack + selection on one stream, the Q
-        and K projection and their unpack on the other, behind an event): the Q and K projection then starts a
-        cross-stream wait later, 2 % more step time at C3."""
-        if ev:
-            ev[0].record(s_v)
-        cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
-        if ev:
-            ev[1].record(s_v)
-        v_ready = torch.cuda.Event()
-        v_ready.record(s_v)
-        cd.a2a_unpack_select(sh, bv, ORDER, hv, hv_prev, T, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
-        s_qk.wait_event(v_ready)            # V's projection goes first; its layout change overlaps what follows
-        if ev:
-            ev[2].record(s_qk)
-        cd.qkv_proj_pack(sh, X, Wq, Wk, None, bq, bk, None, ORDER, stream=s_qk)
-        if ev:
-            ev[3].record(s_qk)
-        cd.a2a_unpack_norm_rope(sh, bq, bk, hq, hk, gq, gk, cfg.eps, rope, ORDER, stream=s_qk)
-        done = torch.cuda.Event()
-        done.record(s_qk)
-        s_v.wait_event(done)                # join: the next layer cannot start before Q and K are laid out
-
-    def step_fused2(ev=None):
-        """V-First with the fused calls on two streams: V's projection writes its exchange buffer; the projection of Q
-        and K (one launch, straight into their exchange buffers) follows it on the same stream, so no cross-stream wait
-        sits between the two projections; V's unpack, which carries the selection's flag pass, waits for V's projection
-        on the side stream and runs under the Q and K projection; Q and K are normalised and rotated inside one unpack
-        pass (receiving side).  4 launches and 7.2 tensor passes over HBM beside the projections, against 13 and 14.2
-        with the stand-alone calls."""
-        if ev:
-            ev[0].record(s_v)
-        cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
-        if ev:
-            ev[1].record(s_v)
-        v_ready = torch.cuda.Event()
-        v_ready.record(s_v)
-        if ev:
-            ev[2].record(s_v)
-        cd.qkv_proj_pack(sh, X, Wq, Wk, None, bq, bk, None, ORDER, stream=s_v)
-        if ev:
-            ev[3].record(s_v)
-        s_qk.wait_event(v_ready)
-        cd.a2a_unpack_select(sh, bv, ORDER, hv, hv_prev, T, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_qk)
-        cd.a2a_unpack_norm_rope(sh, bq, bk, hq, hk, gq, gk, cfg.eps, rope, ORDER, stream=s_v)
-        done = torch.cuda.Event()
-        done.record(s_qk)
-        s_v.wait_event(done)                # join
-
-    def step_fused3(ev=None):
-        """V-First order with the fused calls: every projection writes its exchange buffer itself (no [N][D] tensor
-        exists), V's unpack carries the selection's flag pass, Q's and K's unpack carries norm + RoPE (done on the
-        receiving side).  6 launches and 7.2 tensor passes over HBM beside the projections, against 13 and 14.2."""
-        if ev:
-            ev[0].record(s_v)
-        cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
-        if ev:
-            ev[1].record(s_v)
-        v_ready = torch.cuda.Event()
-        v_ready.record(s_v)
-        cd.a2a_unpack_select(sh, bv, ORDER, hv, hv_prev, T, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
-        s_qk.wait_event(v_ready)
-        if ev:
-            ev[2].record(s_qk)
-        cd.qkv_proj_pack(sh, X, Wq, None, None, bq, None, None, ORDER, stream=s_qk)
-        q_ready = torch.cuda.Event()
-        q_ready.record(s_qk)
-        cd.qkv_proj_pack(sh, X, None, Wk, None, None, bk, None, ORDER, stream=s_qk)
-        if ev:
-            ev[3].record(s_qk)
-        s_q.wait_event(q_ready)
-        cd.a2a_unpack_norm_rope(sh, bq, None, hq, None, gq, None, cfg.eps, rope, ORDER, stream=s_q)
-        cd.a2a_unpack_norm_rope(sh, None, bk, None, hk, None, gk, cfg.eps, rope, ORDER, stream=s_qk)
-        done_q, done_k = torch.cuda.Event(), torch.cuda.Event()
-        done_q.record(s_q)
-        done_k.record(s_qk)
-        s_v.wait_event(done_q)
-        s_v.wait_event(done_k)
-
-    def step_fused3s(ev=None):
-        """Sender-side variant of fused3: V's projection writes the exchange buffer itself, Q and K are
-        normalised and rotated on their way into theirs, V's unpack computes the selection's flags (5 fewer launches
-        and 4 fewer passes over HBM per step)."""
-        if ev:
-            ev[0].record(s_v)
-        cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
-        if ev:
-            ev[1].record(s_v)
-        v_ready = torch.cuda.Event()
-        v_ready.record(s_v)
-        cd.a2a_unpack_select(sh, bv, ORDER, hv, hv_prev, T, cfg.tau, flags, idx, n_act, compact, cap, ws, stream=s_v)
-        s_qk.wait_event(v_ready)
-        if ev:
-            ev[2].record(s_qk)
-        cd.qkv_proj(sh, X, Wq, None, None, q, None, None, stream=s_qk)
-        q_ready = torch.cuda.Event()
-        q_ready.record(s_qk)
-        cd.qkv_proj(sh, X, None, Wk, None, None, k, None, stream=s_qk)
-        if ev:
-            ev[3].record(s_qk)
-        s_q.wait_event(q_ready)
-        cd.qk_norm_rope_pack(sh, q, None, gq, None, cfg.eps, rope, bq, None, ORDER, stream=s_q)
-        cd.a2a_unpack(sh, bq, hq, ORDER, stream=s_q)
-        cd.qk_norm_rope_pack(sh, None, k, None, gk, cfg.eps, rope, None, bk, ORDER, stream=s_qk)
-        cd.a2a_unpack(sh, bk, hk, ORDER, stream=s_qk)
-        done_q, done_k = torch.cuda.Event(), torch.cuda.Event()
-        done_q.record(s_q)
-        done_k.record(s_qk)
-        s_v.wait_event(done_q)
-        s_v.wait_event(done_k)
-
-    schedules = {"vfirst": step_vfirst, "vfirst3": step_vfirst3, "serial": step_serial, "fused2": step_fused2, "fused2x": step_fused2x, "fused3": step_fused3,
-                 "fused3s": step_fused3s}
-    step = schedules[args.schedule]
-
-    def time_schedule(step_fn):
-        for _ in range(args.warmup):
-            step_fn()
-        torch.cuda.synchronize()
-        assert int(n_act.cpu()[0]) == cfg.n_changed, "selection did not find the perturbed tiles"
-        # HIP events around the projection launches, in every fourth step of the timed region: with events in every
-        # step the step itself is 2 % slower (six extra marker packets between its five kernels)
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] if i % 4 == 0 else None for i in range(args.steps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            step_fn(evs[i])
-        t_enq = time.perf_counter()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        log(f"  host enqueue time per step {(t_enq - t0) * 1e3 / args.steps:.3f} ms of {(t1 - t0) * 1e3 / args.steps:.3f} ms")
-        return (t1 - t0) * 1e3 / args.steps, [e for e in evs if e is not None]
-
-    ms_per_step, events = time_schedule(step)
-    tokens_per_s = N / (ms_per_step * 1e-3)
-    # the same step replayed from a HIP graph (capture of the three streams): what is left when the host's launch
-    # work is taken out -- a check that the step is GPU-bound, and what a launch-bound small workload gains
-    graph_replay = None
-    if args.schedule in ("fused2", "fused3") and not args.no_breakdown:
+    # ---- the same step in other forms, reported beside the headline ----
+    other_forms, graph_replay, layer_only = {}, None, None
+    if not args.no_breakdown:
+        for name in ("vfirst", "serial", "fused1_vdirect"):
+            if name not in per_schedule:
+                log(f"  schedule {name}")
+                ms, _ = w.time_steps(w.schedules[name], args.warmup, args.steps)
+                other_forms[name] = {"ms_per_step": round(ms, 4), "value": round(N / (ms * 1e-3), 1)}
+        other_forms["vfirst"]["note"] = "the five stand-alone calls only, two streams"
+        other_forms["serial"]["note"] = "the five stand-alone calls only, one stream"
+        other_forms["fused1_vdirect"]["note"] = ("V's projection writes the head-parallel tensor itself (no exchange buffer for V); "
+                                                 "every other result as in the headline schedules")
+        # the headline step replayed from a HIP graph: what is left when the host's launch work is taken out
         try:
             graph = torch.cuda.CUDAGraph()
             torch.cuda.synchronize()
-            with torch.cuda.graph(graph, stream=s_v):
-                step()
+            with torch.cuda.graph(graph, stream=w.s_main):
+                w.schedules[best]()
             for _ in range(args.warmup):
                 graph.replay()
             torch.cuda.synchronize()
@@ -354,59 +466,42 @@ def main() -> int:
                 graph.replay()
             torch.cuda.synchronize()
             ms_g = (time.perf_counter() - t0) * 1e3 / args.steps
-            assert int(n_act.cpu()[0]) == cfg.n_changed
-            graph_replay = {"schedule": args.schedule, "ms_per_step": round(ms_g, 4), "value": round(N / (ms_g * 1e-3), 1), "unit": "tokens/s"}
+            w.check_selection()
+            graph_replay = {"schedule": best, "ms_per_step": round(ms_g, 4), "value": round(N / (ms_g * 1e-3), 1), "unit": "tokens/s"}
             log(f"  HIP graph replay of the step: {graph_replay}")
             del graph
         except Exception as e:      # reported, never fatal: the headline is the eager step
             log(f"  HIP graph replay not measured: {e}")
-    # the same step through the stand-alone calls only (no fused entry point), reported beside the headline
-    standalone = None
-    if args.schedule in ("fused2", "fused3") and not args.no_breakdown:
-        sa_name = "vfirst" if args.schedule == "fused2" else "vfirst3"
-        ms_sa, _ = time_schedule(schedules[sa_name])
-        standalone = {"schedule": sa_name, "ms_per_step": round(ms_sa, 4), "value": round(N / (ms_sa * 1e-3), 1), "unit": "tokens/s"}
-        log(f"  stand-alone calls ({sa_name} schedule): {standalone}")
 
-    # The sender's share alone -- projection of Q, K, V + norm and RoPE of Q and K + the three packs, up to the
-    # filled exchange buffers (the layer's work before the all-to-all) -- in three forms; `value` above is the longer
-    # path that also holds the receiver's unpack and the selection.
-    layer_only = None
-    if not args.no_breakdown:
+        # The sender's share alone -- projection of Q, K, V + norm and RoPE of Q and K + the three packs, up to the
+        # filled exchange buffers (the layer's work before the all-to-all); `value` above is the longer path that
+        # also holds the receiver's unpack and the selection.
+        sh, st, side, O = w.sh, w.s_main, w.s_side, w.ORDER
+
         def sender_serial():
-            cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v, stream=s_v)
-            cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=s_v)
-            for src, buf in ((v, bv), (q, bq), (k, bk)):
-                cd.a2a_pack(sh, src, buf, ORDER, stream=s_v)
+            cd.qkv_proj(sh, w.X, w.Wq, w.Wk, w.Wv, w.q, w.k, w.v, stream=st)
+            cd.qk_norm_rope(sh, w.q, w.k, w.gq, w.gk, cfg.eps, w.rope, stream=st)
+            for src, buf in ((w.v, w.bv), (w.q, w.bq), (w.k, w.bk)):
+                cd.a2a_pack(sh, src, buf, O, stream=st)
 
         def sender_vfirst():
-            cd.qkv_proj(sh, X, None, None, Wv, None, None, v, stream=s_v)
-            v_ready = torch.cuda.Event()
-            v_ready.record(s_v)
-            cd.a2a_pack(sh, v, bv, ORDER, stream=s_v)
-            s_qk.wait_event(v_ready)
-            cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=s_qk)
-            cd.qk_norm_rope(sh, q, k, gq, gk, cfg.eps, rope, stream=s_qk)
-            cd.a2a_pack(sh, q, bq, ORDER, stream=s_qk)
-            cd.a2a_pack(sh, k, bk, ORDER, stream=s_qk)
-            done = torch.cuda.Event()
-            done.record(s_qk)
-            s_v.wait_event(done)
+            cd.qkv_proj(sh, w.X, None, None, w.Wv, None, None, w.v, stream=st)
+            w.fork(st, side)
+            cd.a2a_pack(sh, w.v, w.bv, O, stream=st)
+            cd.qkv_proj(sh, w.X, w.Wq, w.Wk, None, w.q, w.k, None, stream=side)
+            cd.qk_norm_rope(sh, w.q, w.k, w.gq, w.gk, cfg.eps, w.rope, stream=side)
+            cd.a2a_pack(sh, w.q, w.bq, O, stream=side)
+            cd.a2a_pack(sh, w.k, w.bk, O, stream=side)
+            w.fork(side, st)
 
         def sender_fused():
-            cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER, stream=s_v)
-            v_ready = torch.cuda.Event()
-            v_ready.record(s_v)
-            s_qk.wait_event(v_ready)
-            cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None, stream=s_qk)
-            cd.qk_norm_rope_pack(sh, q, k, gq, gk, cfg.eps, rope, bq, bk, ORDER, stream=s_qk)
-            done = torch.cuda.Event()
-            done.record(s_qk)
-            s_v.wait_event(done)
+            cd.qkv_proj_pack(sh, w.X, None, None, w.Wv, None, None, w.bv, O, stream=st)
+            cd.qkv_proj(sh, w.X, w.Wq, w.Wk, None, w.q, w.k, None, stream=st)
+            cd.qk_norm_rope_pack(sh, w.q, w.k, w.gq, w.gk, cfg.eps, w.rope, w.bq, w.bk, O, stream=st)
 
         layer_only = {}
         for label, fn in (("serial_one_stream", sender_serial), ("vfirst_two_streams", sender_vfirst),
-                          ("vfirst_fused_calls", sender_fused)):
+                          ("fused_calls_one_stream", sender_fused)):
             for _ in range(args.warmup):
                 fn()
             torch.cuda.synchronize()
@@ -418,46 +513,21 @@ def main() -> int:
             layer_only[label] = {"ms": round(ms_l, 4), "tokens/s": round(N / (ms_l * 1e-3), 1)}
         log(f"  sender's share alone (projection + norm + RoPE + pack): {layer_only}")
 
-    # dominant kernel: the projection GEMM (launched per step as V, then Q+K -- or V, Q, K in the vfirst3 order)
-    n_launch = 3 if args.schedule in ("vfirst3", "fused3", "fused3s") else 2
-    gemm_ms = [(e[0].elapsed_time(e[1]), e[2].elapsed_time(e[3])) for e in events]
-    gemm_ms_per_launch = float(np.mean([a + b for a, b in gemm_ms])) / n_launch
-    flops_per_launch = 2.0 * N * (3 * D) * D / n_launch
-    achieved_tflops = flops_per_launch / (gemm_ms_per_launch * 1e-3) / 1e12
-    roofline = {"kernel": "qkv_gemm_direct_kernel", "bound": "mfma", "achieved": round(achieved_tflops, 2),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
-                "traffic": measured_traffic(cfg.name, args.schedule), "avg_launch_us": round(gemm_ms_per_launch * 1e3, 2), "launches_per_step": n_launch}
-
     # ---- per-kernel times, each launched alone on one stream (not part of `value`) ----
     # HBM-bound kernels are timed "cold": successive launches rotate over buffer sets whose footprint is more than
-    # twice the 256 MB last-level cache, so no launch finds its input there; "warm" repeats one set.  A block is one
-    # pass over the rotation (at least 8 launches) between two HIP events; median and minimum over 7 blocks.
-    kernels = {}
-    attainable = None
+    # twice the 256 MB last-level cache, so no launch finds its input there; "warm" repeats one set.
+    kernels, attainable = {}, None
     if not args.no_breakdown:
-        st = torch.cuda.current_stream()
         tensor_bytes = N * D * 2
+        sh, O = w.sh, w.ORDER
+        X, Wq, Wk, Wv, q, k, v, bv = w.X, w.Wq, w.Wk, w.Wv, w.q, w.k, w.v, w.bv
+        flags, idx, n_act, compact, cap, ws = w.flags, w.idx, w.n_act, w.compact, w.cap, w.ws
 
-        def timed(fns, blocks=7):
-            per_block = len(fns) * max(1, -(-8 // len(fns)))
-            for i in range(min(per_block, 2 * len(fns))):
-                fns[i % len(fns)]()
-            evs = [torch.cuda.Event(enable_timing=True) for _ in range(blocks + 1)]
-            torch.cuda.synchronize()
-            evs[0].record(st)
-            for blk in range(blocks):
-                for i in range(per_block):
-                    fns[i % len(fns)]()
-                evs[blk + 1].record(st)
-            torch.cuda.synchronize()
-            t = sorted(evs[i].elapsed_time(evs[i + 1]) / per_block * 1e3 for i in range(blocks))
-            return t[len(t) // 2], t[0]                       # us per launch: median, min
-
-        def add(name, fns, flops=None, nbytes=None):
-            med, mn = timed(fns)
+        def add(name, fns, flops=None, nbytes=None, extra=None):
+            med, mn = timed_blocks(torch, fns)
             ent = {"us": round(med, 2), "us_min": round(mn, 2)}
             if len(fns) > 1:
-                ent["us_warm"] = round(timed(fns[:1])[0], 2)
+                ent["us_warm"] = round(timed_blocks(torch, fns[:1])[0], 2)
             if flops:
                 ent["TFLOP/s"] = round(flops / med / 1e6, 1)
                 ent["frac_mfma_peak"] = round(flops / med / 1e6 / PEAK_BF16_TFLOPS, 4)
@@ -468,103 +538,103 @@ def main() -> int:
                 ent["frac_hbm_peak"] = round(nbytes / med / 1e3 / PEAK_HBM_GBS, 4)
                 if attainable:
                     ent["frac_copy_rate"] = round(nbytes / med / 1e3 / attainable["hbm_copy_GB/s"], 4)
+            if extra:
+                ent.update(extra)
             kernels[name] = ent
+            return med
 
-        def chip_state_during(fn, secs=1.2):
-            """Median shader clock (MHz, rocm-smi) and socket power (W, hwmon) while `fn` keeps the GPU busy; a value
-            that cannot be read is None."""
-            import glob
-            import re
-            import subprocess
-            import threading
-            clocks, watts, stop = [], [], threading.Event()
-            hw = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")
-
-            def sample():
-                while not stop.is_set():
-                    try:
-                        if hw:
-                            with open(hw[0]) as f_:
-                                watts.append((time.time(), int(f_.read()) / 1e6))
-                        out = subprocess.run(["rocm-smi", "--showclocks", "--csv"], capture_output=True, text=True, timeout=10).stdout
-                        row = [l for l in out.strip().splitlines() if l.startswith("card0")]
-                        m = re.findall(r"\((\d+)Mhz\)", row[0]) if row else []
-                        if len(m) >= 2:
-                            clocks.append((time.time(), int(m[1])))     # columns: mclk, sclk
-                    except Exception:
-                        return
-            th = threading.Thread(target=sample, daemon=True)
-            t_begin = time.time()
-            th.start()
-            while time.time() < t_begin + secs:
+        def chip_state_during(fn, secs=1.0):
+            t_begin = time.perf_counter()
+            while time.perf_counter() < t_begin + secs:
                 for _ in range(20):
                     fn()
                 torch.cuda.synchronize()
-            stop.set()
-            th.join(timeout=15)
-            late = lambda xs: [v for (ts, v) in xs if ts > t_begin + 0.3]    # the first samples still see the ramp
-            return {"sclk_MHz": int(np.median(late(clocks))) if late(clocks) else None,
-                    "power_W": int(np.median(late(watts))) if late(watts) else None}
+            return sampler.window(t_begin + 0.3, time.perf_counter())      # the first samples still see the ramp
 
         # what the chip attains on the two calibration kernels: a 1000 MiB copy and a register-only MFMA loop
         big = 1000 << 20   # not a power of two: source and destination must not alias onto the same HBM banks
         src_big = torch.empty(big + (3 << 20), dtype=torch.uint8, device=dev)
         dst_big = torch.empty(big, dtype=torch.uint8, device=dev)
-        copy_us = timed([lambda: cd.util_copy(src_big, dst_big, big)])[0]
-        memcpy_us = timed([lambda: dst_big.copy_(src_big[:big])])[0]      # the runtime's own device-to-device copy
+        copy_us = timed_blocks(torch, [lambda: cd.util_copy(src_big, dst_big, big)])[0]
+        memcpy_us = timed_blocks(torch, [lambda: dst_big.copy_(src_big[:big])])[0]      # the runtime's own device-to-device copy
         del src_big, dst_big
-        src_big2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
-        dst_big2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         sink = torch.zeros(1, dtype=torch.float32, device=dev)
         mfma_flops = cd.util_mfma_rate(1024, 2048, sink)
-        mfma_us = timed([lambda: cd.util_mfma_rate(1024, 2048, sink)])[0]
+        mfma_us = timed_blocks(torch, [lambda: cd.util_mfma_rate(1024, 2048, sink)])[0]
         attainable = {"hbm_copy_GB/s": round(2 * big / copy_us / 1e3, 1), "runtime_memcpy_GB/s": round(2 * big / memcpy_us / 1e3, 1),
                       "mfma_loop_TFLOP/s": round(mfma_flops / mfma_us / 1e6, 1)}
         log(f"  attainable on this GPU: {attainable}")
 
         g1 = 2.0 * N * D * D
-        add("qkv_proj_v", [lambda: cd.qkv_proj(sh, X, None, None, Wv, None, None, v)], flops=g1)
-        add("qkv_proj_qk", [lambda: cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None)], flops=2 * g1)
-        add("qkv_proj_qkv", [lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v)], flops=3 * g1)
-        add("qkv_proj_pack_v", [lambda: cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, ORDER)], flops=g1)
+        add("qkv_proj_v", [lambda: cd.qkv_proj(sh, X, None, None, Wv, None, None, v)], flops=g1, extra={"tile": w.tile_name(1)})
+        add("qkv_proj_qk", [lambda: cd.qkv_proj(sh, X, Wq, Wk, None, q, k, None)], flops=2 * g1, extra={"tile": w.tile_name(2)})
+        add("qkv_proj_qkv", [lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v)], flops=3 * g1, extra={"tile": w.tile_name(3)})
+        add("qkv_proj_pack_v", [lambda: cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, O)], flops=g1)
+        add("qkv_proj_hs_v", [lambda: cd.qkv_proj_hs(sh, X, None, None, Wv, None, None, w.hv)], flops=g1)
+        add("qkv_proj_pack_qkv", [lambda: cd.qkv_proj_pack(sh, X, Wq, Wk, Wv, w.bq, w.bk, bv, O)], flops=3 * g1)
+        roofline["alone"] = {"frac": kernels["qkv_proj_pack_qkv"]["frac_mfma_peak"], "TFLOP/s": kernels["qkv_proj_pack_qkv"]["TFLOP/s"],
+                             "launch": "qkv_proj_pack, three weights, nothing beside it"}
 
         # rotation sets: a (token-major), b (exchange buffer), h and p (head-parallel current / previous V; never written)
         R = int(min(64, max(1, -(-(640 << 20) // (2 * tensor_bytes)))))
         sets = []
         for i in range(R):
-            sets.append({"a": v.clone(), "b": bv.clone(), "h": hv if i == 0 else hv.clone(),
-                         "p": hv_prev if i == 0 else hv_prev.clone()})
+            sets.append({"a": v.clone(), "b": bv.clone(), "h": w.hv if i == 0 else w.hv.clone(),
+                         "p": w.hv_prev if i == 0 else w.hv_prev.clone()})
         log(f"  cold timings rotate over {R} buffer sets of 4 x {tensor_bytes / 1e6:.1f} MB")
-        f_act = cfg.n_changed / NT
-        act = bf((H, cap * T, d))
+        f_act = cfg.n_changed / w.NT
+        act = w.bf((H, cap * T, d))
         metric = torch.empty(N, dtype=torch.float32, device=dev)
         tok_idx = torch.empty(N, dtype=torch.int32, device=dev)
         tok_n = torch.zeros(P, dtype=torch.int32, device=dev)
         k_act = cd.cache_active_count(27, 50, 5, 10, N // P)  # mid-schedule step of the paper's 50-step setup
+        gq, gk, rope = w.gq, w.gk, w.rope
 
         def each(fn):
             return [(lambda s_=s_: fn(s_)) for s_ in sets]
 
         add("vmajor_select", each(lambda s_: cd.vmajor_select(H, N, d, T, s_["h"], s_["p"], cfg.tau, flags, idx, n_act, compact, cap, ws)),
             nbytes=(2 + f_act) * tensor_bytes)
-        add("a2a_unpack_select", each(lambda s_: cd.a2a_unpack_select(sh, s_["b"], ORDER, s_["a"], s_["p"], T, cfg.tau, flags, idx, n_act, compact, cap, ws)),
+        add("a2a_unpack_select", each(lambda s_: cd.a2a_unpack_select(sh, s_["b"], O, s_["a"], s_["p"], T, cfg.tau, flags, idx, n_act, compact, cap, ws)),
             nbytes=(3 + f_act) * tensor_bytes)
         assert int(n_act.cpu()[0]) == cfg.n_changed, "the breakdown's selection inputs were disturbed"
         add("vmajor_token_metric", each(lambda s_: cd.vmajor_token_metric(H, N, d, s_["h"], s_["p"], metric)), nbytes=2 * tensor_bytes)
         add("vmajor_topk", [lambda: cd.vmajor_topk(P, N // P, metric, k_act, tok_idx, tok_n)])   # every rank ranks its own tokens
-        # rows after the hot path: sender-side gather / receiver-side scatter of the active tiles, second all-to-all
         add("vmajor_gather", each(lambda s_: cd.vmajor_gather(H, N, d, T, s_["h"], idx, n_act, act, cap)), nbytes=2 * f_act * tensor_bytes)
         add("vmajor_scatter", each(lambda s_: cd.vmajor_scatter(H, N, d, T, act, idx, n_act, s_["a"], cap)), nbytes=2 * f_act * tensor_bytes)
-        add("a2a_pack_hs", each(lambda s_: cd.a2a_pack_hs(sh, s_["h"], s_["b"], ORDER)), nbytes=2 * tensor_bytes)
-        add("a2a_unpack_seq", each(lambda s_: cd.a2a_unpack_seq(sh, s_["b"], s_["a"], ORDER)), nbytes=2 * tensor_bytes)
-        add("a2a_pack", each(lambda s_: cd.a2a_pack(sh, s_["a"], s_["b"], ORDER)), nbytes=2 * tensor_bytes)
-        add("a2a_unpack", each(lambda s_: cd.a2a_unpack(sh, s_["b"], s_["a"], ORDER)), nbytes=2 * tensor_bytes)
-        add("qk_norm_rope", each(lambda s_: cd.qk_norm_rope(sh, s_["a"], s_["b"], gq, gk, cfg.eps, rope)), nbytes=4 * tensor_bytes)
-        add("a2a_unpack_norm_rope", each(lambda s_: cd.a2a_unpack_norm_rope(sh, s_["h"], s_["p"], s_["a"], s_["b"], gq, gk, cfg.eps, rope, ORDER)),
+        add("a2a_pack_hs", each(lambda s_: cd.a2a_pack_hs(sh, s_["h"], s_["b"], O)), nbytes=2 * tensor_bytes)
+        add("a2a_unpack_seq", each(lambda s_: cd.a2a_unpack_seq(sh, s_["b"], s_["a"], O)), nbytes=2 * tensor_bytes)
+        us_pack = add("a2a_pack", each(lambda s_: cd.a2a_pack(sh, s_["a"], s_["b"], O)), nbytes=2 * tensor_bytes)
+        us_unpack = add("a2a_unpack", each(lambda s_: cd.a2a_unpack(sh, s_["b"], s_["a"], O)), nbytes=2 * tensor_bytes)
+        us_nr = add("qk_norm_rope", each(lambda s_: cd.qk_norm_rope(sh, s_["a"], s_["b"], gq, gk, cfg.eps, rope)), nbytes=4 * tensor_bytes)
+        add("a2a_unpack_norm_rope", each(lambda s_: cd.a2a_unpack_norm_rope(sh, s_["h"], s_["p"], s_["a"], s_["b"], gq, gk, cfg.eps, rope, O)),
             nbytes=4 * tensor_bytes)
-        add("qk_norm_rope_pack", each(lambda s_: cd.qk_norm_rope_pack(sh, s_["h"], s_["p"], gq, gk, cfg.eps, rope, s_["a"], s_["b"], ORDER)),
+        add("qk_norm_rope_pack", each(lambda s_: cd.qk_norm_rope_pack(sh, s_["h"], s_["p"], gq, gk, cfg.eps, rope, s_["a"], s_["b"], O)),
             nbytes=4 * tensor_bytes)
         add("copy_same_bytes", each(lambda s_: cd.util_copy(s_["a"], s_["b"], tensor_bytes)), nbytes=2 * tensor_bytes)
+
+        # The per-rank back-to-back form: P launches, each covering one logical rank's share (rank_count = 1), for the
+        # calls that take a rank range; "us" is the whole group of P launches, to compare with the one launch above.
+        ranks = [cd.Shape.make(N, D, H, d, P, r, 1) for r in range(P)]
+
+        def group(fn):
+            def run(s_):
+                for shr in ranks:
+                    fn(shr, s_)
+            return run
+
+        us_proj_all = kernels["qkv_proj_qkv"]["us"]
+        for name, fn, batched_us, kw in (
+                ("qkv_proj_qkv_per_rank", lambda shr, s_: cd.qkv_proj(shr, X, Wq, Wk, Wv, q, k, v), us_proj_all, {"flops": 3 * g1}),
+                ("qk_norm_rope_per_rank", lambda shr, s_: cd.qk_norm_rope(shr, s_["a"], s_["b"], gq, gk, cfg.eps, rope), us_nr, {"nbytes": 4 * tensor_bytes}),
+                ("a2a_pack_per_rank", lambda shr, s_: cd.a2a_pack(shr, s_["a"], s_["b"], O), us_pack, {"nbytes": 2 * tensor_bytes}),
+                ("a2a_unpack_per_rank", lambda shr, s_: cd.a2a_unpack(shr, s_["b"], s_["a"], O), us_unpack, {"nbytes": 2 * tensor_bytes})):
+            fns = [lambda: group(fn)(sets[0])] if "flops" in kw else each(group(fn))
+            med = add(name, fns, extra={"launches": P}, **kw)
+            kernels[name]["vs_one_launch"] = round(med / batched_us, 3)
+            kernels[name].pop("us_warm", None)
+        kernels["qkv_proj_qkv_per_rank"]["tile"] = "{tile_tokens}x{tile_features}".format(**cd.qkv_proj_plan(ranks[0], 3))
+
         kernels["copy_1000MiB"] = {"us": round(copy_us, 2), "GB/s": attainable["hbm_copy_GB/s"],
                                    "frac_hbm_peak": round(attainable["hbm_copy_GB/s"] / PEAK_HBM_GBS, 4)}
         kernels["mfma_register_loop"] = {"us": round(mfma_us, 2), "TFLOP/s": attainable["mfma_loop_TFLOP/s"],
@@ -572,37 +642,40 @@ def main() -> int:
         del sets, act
         # the chip does not hold its top clock under matrix-core load: record what it runs at (last: the throttled
         # state lingers and would colour the timings above)
-        state = {"copy": chip_state_during(lambda: cd.util_copy(src_big2, dst_big2, 256 << 20)),
+        src2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst2 = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        state = {"copy": chip_state_during(lambda: cd.util_copy(src2, dst2, 256 << 20)),
                  "mfma_loop": chip_state_during(lambda: cd.util_mfma_rate(1024, 512, sink)),
                  "projection": chip_state_during(lambda: cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v))}
+        del src2, dst2
         attainable["sclk_MHz"] = {k_: v_["sclk_MHz"] for k_, v_ in state.items()}
         attainable["power_W"] = {k_: v_["power_W"] for k_, v_ in state.items()}
-        del src_big2, dst_big2
         log(f"  chip state under load: clocks {attainable['sclk_MHz']} MHz, socket power {attainable['power_W']} W")
-        roofline["frac_of_mfma_loop"] = round(achieved_tflops / attainable["mfma_loop_TFLOP/s"], 4)
+        roofline["frac_of_mfma_loop"] = round(roofline["achieved"] / attainable["mfma_loop_TFLOP/s"], 4)
         if attainable["sclk_MHz"]["projection"]:
             # the published peak is 2.4 GHz x 256 units x 4 SIMDs x 1024 flop/clk; the same at the clock the chip holds
-            roofline["sclk_MHz"] = attainable["sclk_MHz"]["projection"]
-            roofline["frac_at_sclk"] = round(achieved_tflops / (PEAK_BF16_TFLOPS * attainable["sclk_MHz"]["projection"] / 2400.0), 4)
+            roofline["sclk_MHz_projection_alone"] = attainable["sclk_MHz"]["projection"]
+            roofline["frac_at_sclk"] = round(roofline["achieved"] / (PEAK_BF16_TFLOPS * attainable["sclk_MHz"]["projection"] / 2400.0), 4)
         for name, ent in kernels.items():
-            log(f"  {name:20s} {ent}")
+            log(f"  {name:24s} {ent}")
 
     # ---- the CPU oracle on the host cores, on a bounded sample of the same workload ----
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         oracle.build_c()
+        inp = w.inp
         S_tok = min(N, 24576)                                # float stages: the first S_tok tokens per pass
         ids = np.arange(S_tok)
-        host_seq = bits(v).reshape(N, H, d)
-        host_prev = bits(hv_prev)
+        host_seq = w.bits(w.v).reshape(N, H, d)
+        host_prev = w.bits(w.hv_prev)
         t_float = t_perm = t_pack = t_unpack = t_sel = 0.0
         passes = 0
         while t_float + t_perm < 12.0 and passes < 200:      # about 10-30 s of CPU work in whole passes
             t_a = time.perf_counter()
             o = {}
-            for name, w in (("q", "Wq"), ("k", "Wk"), ("v", "Wv")):
-                o[name] = oracle.qkv_proj(inp["X"][:S_tok], inp[w])
+            for name, wn in (("q", "Wq"), ("k", "Wk"), ("v", "Wv")):
+                o[name] = oracle.qkv_proj(inp["X"][:S_tok], inp[wn])
             for name, g in (("q", "gamma_q"), ("k", "gamma_k")):
                 o[name] = oracle.rope_rotate(oracle.rms_norm(o[name].reshape(S_tok, H, d), oracle.widen(inp[g]), cfg.eps),
                                              ids, cfg.grid, cfg.pairs, cfg.theta)
@@ -626,31 +699,71 @@ def main() -> int:
         per_token = t_float / (passes * S_tok) + t_perm / (passes * N)
         try:
             from threadpoolctl import threadpool_info
-            blas_threads = max([p_.get("num_threads", 1) for p_ in threadpool_info()] or [1])
+            blas_threads = max([p_.get("num_threads", 1) for p_ in threadpool_info() if p_.get("user_api") == "blas"] or [1])
         except Exception:
             blas_threads = os.cpu_count() or 1
-        cpu = {"value": round(1.0 / per_token, 1), "unit": "tokens/s", "cores": int(blas_threads), "kind": "oracle",
+        omp_threads = oracle.omp_max_threads()
+        nproc = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+        cpu = {"value": round(1.0 / per_token, 1), "unit": "tokens/s", "cores": int(max(blas_threads, omp_threads)), "kind": "oracle",
+               "threads": {"blas_fp64_matmul": int(blas_threads), "openmp_index_loops": int(omp_threads), "nproc": int(nproc),
+                           "cpu_count": int(os.cpu_count() or 0)},
                "sample": f"{passes} passes of the oracle over the workload (fp64 projection + norm + RoPE on "
                          f"{S_tok} of {N} tokens per pass; pack/unpack x3 and select on the full tensors): "
                          f"{t_float + t_perm:.1f} s of CPU work",
                "stages": {"proj_norm_rope_tokens/s": round(passes * S_tok / t_float, 1),
                           "a2a_pack_GB/s": round(3 * passes * 2 * N * D * 2 / t_pack / 1e9, 2),
                           "a2a_unpack_GB/s": round(3 * passes * 2 * N * D * 2 / t_unpack / 1e9, 2),
-                          "vmajor_select_GB/s": round(passes * (2 + cfg.n_changed / NT) * N * D * 2 / t_sel / 1e9, 2)}}
+                          "vmajor_select_GB/s": round(passes * (2 + cfg.n_changed / w.NT) * N * D * 2 / t_sel / 1e9, 2)}}
         log(f"  cpu oracle: {cpu}")
 
+    # ---- the two largest workloads, same schedules, same warm-up and step count ----
+    others = None
+    if not args.no_other_workloads and args.schedule == "auto" and cfg.name == "C3":
+        del w
+        torch.cuda.empty_cache()
+        others = {}
+        for name in ("C4", "C5"):
+            ow = Workload(CONFIGS[name], cd, torch, np, dev)
+            oc = ow.cfg
+            sched, obest = time_headline(ow, HEADLINE_CANDIDATES, args.warmup, args.steps, sampler)
+            ent = {"workload": f"N={oc.N} tokens, P={oc.P}", "schedule": obest, "ms_per_step": sched[obest]["ms_per_step"],
+                   "value": sched[obest]["value"], "unit": "tokens/s", "schedules": sched,
+                   "roofline": roofline_of(ow, obest, max(args.steps, 50))}
+            tb = oc.N * oc.D * 2
+            g3 = 6.0 * oc.N * oc.D * oc.D
+            us_alone = timed_blocks(torch, [lambda: cd.qkv_proj_pack(ow.sh, ow.X, ow.Wq, ow.Wk, ow.Wv, ow.bq, ow.bk, ow.bv, ow.ORDER)], blocks=3)[0]
+            ent["roofline"]["alone"] = {"frac": round(g3 / us_alone / 1e6 / PEAK_BF16_TFLOPS, 4), "TFLOP/s": round(g3 / us_alone / 1e6, 1),
+                                        "launch": "qkv_proj_pack, three weights, nothing beside it"}
+            f_o = oc.n_changed / ow.NT
+            hbm = {}
+            for kname, fn, nb in (("a2a_unpack_select", lambda: ow.unpack_select(None), (3 + f_o) * tb),
+                                  ("vmajor_select", lambda: ow.select(None), (2 + f_o) * tb),
+                                  ("a2a_unpack_norm_rope", lambda: ow.unpack_norm_rope(None), 4 * tb),
+                                  ("a2a_pack", lambda: cd.a2a_pack(ow.sh, ow.v, ow.bv, ow.ORDER), 2 * tb),
+                                  ("a2a_unpack", lambda: cd.a2a_unpack(ow.sh, ow.bv, ow.hv, ow.ORDER), 2 * tb)):
+                us = timed_blocks(torch, [fn], blocks=3)[0]     # tensors of 127 MB and 613 MB: beyond the last-level cache as they are
+                hbm[kname] = {"us": round(us, 2), "GB/s": round(nb / us / 1e3, 1), "frac_hbm_peak": round(nb / us / 1e3 / PEAK_HBM_GBS, 4)}
+            ent["kernels_alone"] = hbm
+            others[name] = ent
+            log(f"  {name}: {ent}")
+            del ow
+            torch.cuda.empty_cache()
+    sampler.stop()
+
     out = {
-        "metric": METRIC, "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "metric": METRIC, "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={N} tokens ({'x'.join(map(str, cfg.grid))} grid), D={D}, {H} heads x {d}, "
-                               f"P={P} logical ranks on one GPU, {cfg.n_changed}/{NT} 16-token V tiles changed",
-                   "schedule": args.schedule, "global_batch": 1, "seq_len": N},
+                               f"P={P} logical ranks on one GPU, {cfg.n_changed}/{cfg.NT} 16-token V tiles changed",
+                   "schedule": best, "global_batch": 1, "seq_len": N},
+        "schedules": per_schedule,
         "roofline": roofline,
         "cpu_baseline": cpu,
-        "standalone_calls_path": standalone,
+        "other_forms_of_the_step": other_forms or None,
         "hip_graph_replay": graph_replay,
         "sender_share_only": layer_only,
+        "other_workloads": others,
         "attainable": attainable,
         "kernels": kernels,
     }

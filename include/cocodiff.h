@@ -141,6 +141,18 @@ COCODIFF_API int cocodiff_qk_norm_rope_pack(const cocodiff_shape* shape, const c
                                             int slot_order, void* stream);
 
 /*
+ * cocodiff_qkv_proj_hs = cocodiff_qkv_proj followed by cocodiff_a2a_pack and cocodiff_a2a_unpack of every given
+ * tensor, for ranks that share one memory (this library's case: all P logical ranks on one GPU): the projection's
+ * epilogue writes each 16-byte row piece to its place in the head-parallel tensor q_hs / k_hs / v_hs [H][N][d]
+ * (Section II-A: the layout the first all-to-all ends in), so pack, exchange and unpack are the store address and no
+ * exchange buffer exists.  Bit-identical to the three calls.  Rows (tokens) of the rank range are computed, every
+ * head of them; other tokens' rows are untouched.  Argument rules as for cocodiff_qkv_proj.
+ */
+COCODIFF_API int cocodiff_qkv_proj_hs(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                      const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                      cocodiff_bf16* q_hs, cocodiff_bf16* k_hs, cocodiff_bf16* v_hs, void* stream);
+
+/*
  * cocodiff_a2a_unpack_select = cocodiff_a2a_unpack of V followed by cocodiff_vmajor_select on the unpacked tensor
  * (head-parallel: S = H, W = d): the selection's first pass reads the current values from the exchange buffer
  * vbuf, writes them to their place in v_hs [H][N][d] and compares them with v_prev on the way, so the unpacked

@@ -21,6 +21,7 @@ from .ref import (  # noqa: F401
     active_count,
     build_c,
     cache_ratio,
+    omp_max_threads,
     qk_norm_rope,
     qkv_proj,
     rms_norm,

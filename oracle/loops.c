@@ -25,6 +25,19 @@
 #include <string.h>
 #include <math.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads the OpenMP loops below run on (for the benchmark's report of the CPU baseline). */
+int oracle_omp_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 #define SLOT_SEND_MAJOR 0
 #define SLOT_RECV_MAJOR 1
 

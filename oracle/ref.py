@@ -57,8 +57,15 @@ def _c():
         lib.oracle_a2a_pack_hs.restype = None
         lib.oracle_a2a_unpack_seq.argtypes = [u16p, u16p, ci, ci, ci, ci, ci, ci, ci]
         lib.oracle_a2a_unpack_seq.restype = None
+        lib.oracle_omp_max_threads.argtypes = []
+        lib.oracle_omp_max_threads.restype = ci
         _lib = lib
     return _lib
+
+
+def omp_max_threads() -> int:
+    """Threads the OpenMP index loops of ``loops.c`` run on."""
+    return int(_c().oracle_omp_max_threads())
 
 
 def _u16(a: np.ndarray):

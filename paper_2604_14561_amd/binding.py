@@ -20,7 +20,7 @@ ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_CAPACITY, ERR_HIP = -1, -2, -3, -4, -5
 SEND_MAJOR, RECV_MAJOR = 0, 1
 
 EXPORTS = (
-    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack",
+    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qkv_proj_hs", "cocodiff_qk_norm_rope_pack",
     "cocodiff_a2a_unpack_select", "cocodiff_a2a_unpack_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_static", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         sp, rp = ctypes.POINTER(Shape), ctypes.POINTER(Rope)
         L.cocodiff_qkv_proj.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.cocodiff_qk_norm_rope.argtypes = [sp, vp, vp, vp, vp, f32, rp, vp]
+        L.cocodiff_qkv_proj_hs.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.cocodiff_qkv_proj_hs.restype = ci
         L.cocodiff_a2a_pack.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_a2a_unpack.argtypes = [sp, vp, vp, ci, vp]
         L.cocodiff_vmajor_select.argtypes = [i32, i32, i32, i32, vp, vp, f32, vp, vp, vp, vp, i32, vp, sz, vp]
@@ -103,7 +105,7 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_a2a_unpack_norm_rope.restype = ci
         L.cocodiff_qkv_proj_pack.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ci, vp]
         L.cocodiff_qk_norm_rope_pack.argtypes = [sp, vp, vp, vp, vp, ctypes.c_float, rp, vp, vp, ci, vp]
-        for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
+        for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qkv_proj_hs", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
                      "cocodiff_vmajor_select", "cocodiff_vmajor_gather", "cocodiff_vmajor_scatter",
                      "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk",
                      "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_fill", "cocodiff_util_copy"):
@@ -157,6 +159,11 @@ def qk_norm_rope(shape: Shape, q, k, gamma_q, gamma_k, eps: float, rope: Rope, s
 def qkv_proj_pack(shape: Shape, x, wq, wk, wv, qbuf, kbuf, vbuf, slot_order: int = SEND_MAJOR, stream=None) -> None:
     _check(lib().cocodiff_qkv_proj_pack(ctypes.byref(shape), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv),
                                         _ptr(qbuf), _ptr(kbuf), _ptr(vbuf), int(slot_order), _stream(stream)))
+
+
+def qkv_proj_hs(shape: Shape, x, wq, wk, wv, q_hs, k_hs, v_hs, stream=None) -> None:
+    _check(lib().cocodiff_qkv_proj_hs(ctypes.byref(shape), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv),
+                                      _ptr(q_hs), _ptr(k_hs), _ptr(v_hs), _stream(stream)))
 
 
 def qk_norm_rope_pack(shape: Shape, q, k, gamma_q, gamma_k, eps: float, rope: Rope, qbuf, kbuf,

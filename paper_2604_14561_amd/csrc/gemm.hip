@@ -3,20 +3,19 @@
 // power-limited part it sustains 1.91 PFLOP/s at 0.70 pJ/flop in a register-only loop against 1.72 PFLOP/s at
 // 0.77 pJ/flop for v_mfma_f32_32x32x16_bf16, for the same LDS traffic per flop (a wavefront's tile decides that).
 //
-// Workgroup tile: 256 tokens x 256 features (192 x 192 when that fills the compute units much better: small
-// token counts), K step 64 (a row segment of either operand is one whole 128-byte line; half lines halve the L1
-// fill rate).  W rides the MFMA "A" side, so an accumulator lane
-// holds four consecutive features of one token.  Both operands are K-contiguous; LDS tiles keep rows
-// contiguous and store 16-byte column c of row r at column c ^ swz(r), which makes the 128-bit fragment
-// reads bank-conflict free.
+// Workgroup tile (tokens x features): 256 x 256, 288 x 192 or 192 x 192 -- the host takes the one with the fewest
+// rounds of tiles over the compute units, weighted by a measured per-flop cost (plan_launch).  K step 64: a row
+// segment of either operand is one whole 128-byte line (half lines halve the L1 fill rate).  W rides the MFMA "A"
+// side, so an accumulator lane holds four consecutive features of one token.  Both operands are K-contiguous; LDS
+// tiles keep rows contiguous and store 16-byte column c of row r at column c ^ swz(r), which makes the 128-bit
+// fragment reads bank-conflict free.
 //
-// Main kernel (K a multiple of 64): global -> LDS directly (no staging registers) through a ring of five
-// slots (X and W tiles of a step travel separately; 32 KB each for the 256 x 256 tile).  WN wavefronts along the
-// features x 2 along the tokens: WN = 4 gives 8 wavefronts of 128 x 64 outputs, two per SIMD, so one can multiply
-// while the other waits for LDS, memory or the barrier.  The epilogue writes [N][D] rows or, for the fused call,
-// the rows' pieces straight into their chunks of the exchange buffer.
-// Fallback kernel (any K that is a multiple of 8): global -> registers -> LDS, zero-filled K tail.
-// The epilogue rounds to bf16, transposes through the (now idle) LDS and writes whole rows.
+// Main kernel (K a multiple of 64, at least three steps): global -> LDS directly (no staging registers) through two
+// rings, three slots for X tiles and two for W tiles (160 KB for the 256 x 256 tile).  Eight wavefronts, four along
+// the features x two along the tokens, two per SIMD, so one can multiply while the other waits for LDS, memory or
+// the barrier.  General kernel (any K that is a multiple of 8): global -> registers -> LDS, zero-filled K tail.
+// The epilogue rounds to bf16, transposes through the (now idle) LDS and writes 16-byte vectors: rows of [N][D],
+// row pieces straight into their chunks of the exchange buffer, or row pieces of the head-parallel tensor.
 #include <initializer_list>
 #include <type_traits>
 
@@ -47,7 +46,13 @@ struct GemmArgs {
     // chunk row and per chunk, slot order
     uint32_t Ns, P, row8, chunk8;
     int32_t recv_major;
+    // outputs in head-parallel order [H][N][d]: all tokens, 16-byte vectors per head row
+    uint32_t N_all, d8;
 };
+
+// Where the epilogue writes: token-major [N][D]; the exchange-buffer chunks of the first all-to-all; or the
+// head-parallel tensor [H][N][d] that all-to-all ends in (pack, exchange and unpack folded into the store address).
+enum OutLayout { OUT_SEQ = 0, OUT_CHUNKS = 1, OUT_HEADS = 2 };
 
 // [rows][64] bf16 tiles (128-byte rows): any 16 consecutive rows of one column land in 16 different
 // 16-byte slots of the 256-byte bank span.
@@ -115,9 +120,10 @@ struct EpilogueRows {
 
 // Second half of the epilogue: the wavefront reads back the rows it staged (a wavefront's LDS accesses complete in
 // order: no workgroup barrier is needed) and writes them out.
-// PACKED: the 8 features a lane writes for token n = r*Ns + m go to chunk (sender r, receiver p = feature / (Hp*d))
+// OUT_CHUNKS: the 8 features a lane writes for token n = r*Ns + m go to chunk (sender r, receiver p = feature / (Hp*d))
 // of the exchange buffer Y, row m (Hp*d is a multiple of 8, so a 16-byte vector never straddles two chunks).
-template <uint32_t COLS, uint32_t ROWS, bool PACKED>
+// OUT_HEADS: they go to row n of head feature / d of Y = [H][N][d] (d is a multiple of 8).
+template <uint32_t COLS, uint32_t ROWS, int LAYOUT>
 __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lane, uint16_t* __restrict__ Y, size_t row0,
                                            uint32_t tok0, uint32_t feat0, uint32_t M, uint32_t D, const GemmArgs& a) {
     constexpr uint32_t CP = EpilogueRows<COLS>::CP, ROWB = EpilogueRows<COLS>::ROWB;
@@ -130,11 +136,15 @@ __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lan
         const uint32_t feat = feat0 + c16 * 8u;
         if (c16 < COLS && tok < M && feat < D) {
             const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & (CP - 1u))) << 4));
-            if (PACKED) {
+            if (LAYOUT == OUT_CHUNKS) {
                 const uint32_t n = (uint32_t)row0 + tok, r = n / a.Ns, m = n - r * a.Ns;
                 const uint32_t v8 = feat >> 3, p = v8 / a.row8, c = v8 - p * a.row8;
                 const size_t slot = a.recv_major ? (size_t)p * a.P + r : (size_t)r * a.P + p;
                 reinterpret_cast<vec16*>(Y)[slot * a.chunk8 + (size_t)m * a.row8 + c] = v;
+            } else if (LAYOUT == OUT_HEADS) {
+                const uint32_t n = (uint32_t)row0 + tok;
+                const uint32_t v8 = feat >> 3, h = v8 / a.d8, c = v8 - h * a.d8;
+                reinterpret_cast<vec16*>(Y)[((size_t)h * a.N_all + n) * a.d8 + c] = v;
             } else {
                 *reinterpret_cast<vec16*>(Y + (row0 + tok) * D + feat) = v;
             }
@@ -144,7 +154,7 @@ __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lan
 
 // 32 x 32 accumulator tiles (v_mfma_f32_32x32x16_bf16): element e of lane l in tile (i, j) is feature
 // 32i + 8*(e/4) + 4*(l/32) + e%4 of token 32j + l%32.
-template <int NI, int NJ, bool PACKED>
+template <int NI, int NJ, int LAYOUT>
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane,
                                            uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
                                            uint32_t M, uint32_t D, const GemmArgs& a) {
@@ -157,12 +167,12 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], unsigned
             for (int g = 0; g < 4; ++g)
                 EpilogueRows<NI * 4>::put4(ep, 32u * j + frag_row, 32u * i + 8u * g + 4u * frag_half, acc[i][j][4 * g + 0],
                                            acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-    store_rows<NI * 4, NJ * 32, PACKED>(ep, lane, Y, row0, tok0, feat0, M, D, a);
+    store_rows<NI * 4, NJ * 32, LAYOUT>(ep, lane, Y, row0, tok0, feat0, M, D, a);
 }
 
 // 16 x 16 accumulator tiles (v_mfma_f32_16x16x32_bf16): element e of lane l in tile (i, j) is feature
 // 16i + 4*(l/16) + e of token 16j + l%16.
-template <int NI, int NJ, bool PACKED>
+template <int NI, int NJ, int LAYOUT>
 __device__ __forceinline__ void store_tile16(const f32x4 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane,
                                              uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
                                              uint32_t M, uint32_t D, const GemmArgs& a) {
@@ -173,7 +183,7 @@ __device__ __forceinline__ void store_tile16(const f32x4 (&acc)[NI][NJ], unsigne
         for (int j = 0; j < NJ; ++j)
             EpilogueRows<NI * 2>::put4(ep, 16u * j + frag_row, 16u * i + 4u * frag_q, acc[i][j][0], acc[i][j][1], acc[i][j][2],
                                        acc[i][j][3]);
-    store_rows<NI * 2, NJ * 16, PACKED>(ep, lane, Y, row0, tok0, feat0, M, D, a);
+    store_rows<NI * 2, NJ * 16, LAYOUT>(ep, lane, Y, row0, tok0, feat0, M, D, a);
 }
 
 // s_waitcnt: at most WAIT global->LDS loads of this wavefront still in flight (LDS-read counter untouched)
@@ -217,7 +227,7 @@ __device__ __forceinline__ void load_to_lds(const void* g, uint32_t lds_addr) {
 //   288 x 192: WN = 4, NI = 3, NJ = 9 (8 wavefronts of 48 x 144) -- 9216 tokens x 3072 features are exactly 512 such
 //              tiles, two rounds of 256 compute units, where 432 square tiles are 1.69;
 //   192 x 192: WN = 4, NI = 3, NJ = 6 (8 wavefronts of 48 x 96; 2 - 5 % faster than 4 wavefronts of 96 x 96).
-template <int WN, int NI, int NJ, bool PACKED>
+template <int WN, int NI, int NJ, int LAYOUT>
 __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     constexpr int WAVES = 2 * WN;
     constexpr int TM = 2 * NJ * 16, TN = WN * NI * 16;      // tokens, features per tile
@@ -381,7 +391,7 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     __syncthreads();
     constexpr int kEpilogueBytes = NJ * 16 * EpilogueRows<NI * 2>::ROWB;   // per wavefront, see store_tile16
     static_assert(WAVES * kEpilogueBytes <= ring_lds_bytes(TM, TN), "the epilogue reuses the ring's LDS");
-    store_tile16<NI, NJ, PACKED>(acc, smem + wave * kEpilogueBytes, lane, a.y[tc.tensor], (size_t)a.row_begin,
+    store_tile16<NI, NJ, LAYOUT>(acc, smem + wave * kEpilogueBytes, lane, a.y[tc.tensor], (size_t)a.row_begin,
                                  tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
@@ -392,7 +402,7 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
 constexpr int kStagedThreads = 256;
 constexpr int kVecPerOperand = BM * (BK / 8) / kStagedThreads;   // 16-byte vectors per lane per operand per stage: 8
 
-template <bool PACKED>
+template <int LAYOUT>
 __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const TileCoord tc = tile_of_block(a);
@@ -464,7 +474,7 @@ __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArg
         if (kt + 1 < n_k) store_stage(cur ^ 1u);
         __syncthreads();
     }
-    store_tile<4, 4, PACKED>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t,
+    store_tile<4, 4, LAYOUT>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t,
                           tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
@@ -473,13 +483,13 @@ __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArg
 struct TileKernel {
     int bm, bn, threads, lds;
     double penalty;               // measured per-flop cost against the 256 x 256 tile
-    const void* plain;
-    const void* packed;
+    const void* entry[3];         // by OutLayout
 };
 template <int WN, int NI, int NJ>
 TileKernel tile_kernel(double penalty) {
     return {2 * NJ * 16, WN * NI * 16, 128 * WN, ring_lds_bytes(2 * NJ * 16, WN * NI * 16), penalty,
-            (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, false>, (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, true>};
+            {(const void*)qkv_gemm_direct_kernel<WN, NI, NJ, OUT_SEQ>, (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, OUT_CHUNKS>,
+             (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, OUT_HEADS>}};
 }
 
 // The tile shapes of the main kernel, and which one a launch of M tokens x D features x n_tensors weights takes.
@@ -535,10 +545,11 @@ static LaunchPlan plan_launch(int32_t M, int32_t D, int32_t n_tensors) {
 
 using namespace cocodiff;
 
-// packed = false: q, k, v are [N][D].  packed = true: they are exchange buffers, written in chunk order.
+// layout OUT_SEQ: q, k, v are [N][D]; OUT_CHUNKS: they are exchange buffers, written in chunk order; OUT_HEADS: [H][N][d].
 static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
                        const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
-                       cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, bool packed, int slot_order, void* stream) {
+                       cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, OutLayout layout, int slot_order, void* stream) {
+    const bool packed = layout == OUT_CHUNKS;
     int rc = check_shape(shape);
     if (rc != COCODIFF_OK) return rc;
     if (packed && slot_order != COCODIFF_SEND_MAJOR && slot_order != COCODIFF_RECV_MAJOR)
@@ -556,6 +567,8 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.row8 = (uint32_t)(shape->H / shape->P) * (uint32_t)(shape->d / 8);
     a.chunk8 = a.Ns * a.row8;
     a.recv_major = slot_order == COCODIFF_RECV_MAJOR;
+    a.N_all = (uint32_t)shape->N;
+    a.d8 = (uint32_t)(shape->d / 8);
     a.x = x;
     a.n_tensors = 0;
     const cocodiff_bf16* ws[3] = {wv, wq, wk};   // V first: its tiles are dealt out before Q's and K's
@@ -591,9 +604,10 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
         int n_shapes = 0;
         const TileKernel* shapes = tile_shapes(&n_shapes);
         for (int i = 0; i < n_shapes; ++i)
-            for (const void* k : {shapes[i].plain, shapes[i].packed})
+            for (const void* k : shapes[i].entry)
                 if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, shapes[i].lds);
-        for (const void* k : {(const void*)qkv_gemm_staged_kernel<false>, (const void*)qkv_gemm_staged_kernel<true>})
+        for (const void* k : {(const void*)qkv_gemm_staged_kernel<OUT_SEQ>, (const void*)qkv_gemm_staged_kernel<OUT_CHUNKS>,
+                              (const void*)qkv_gemm_staged_kernel<OUT_HEADS>})
             if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         return e;
     }();
@@ -601,11 +615,12 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     hipStream_t st = as_stream(stream);
     void* kernel_args[] = {&a};
     hipError_t le;
+    static const void* const staged[3] = {(const void*)qkv_gemm_staged_kernel<OUT_SEQ>, (const void*)qkv_gemm_staged_kernel<OUT_CHUNKS>,
+                                          (const void*)qkv_gemm_staged_kernel<OUT_HEADS>};
     if (ring_kernel)
-        le = hipLaunchKernel(packed ? pick->packed : pick->plain, dim3(n_tiles), dim3(pick->threads), kernel_args, pick->lds, st);
+        le = hipLaunchKernel(pick->entry[layout], dim3(n_tiles), dim3(pick->threads), kernel_args, pick->lds, st);
     else
-        le = hipLaunchKernel(packed ? (const void*)qkv_gemm_staged_kernel<true> : (const void*)qkv_gemm_staged_kernel<false>, dim3(n_tiles),
-                             dim3(kStagedThreads), kernel_args, kLdsBytes, st);
+        le = hipLaunchKernel(staged[layout], dim3(n_tiles), dim3(kStagedThreads), kernel_args, kLdsBytes, st);
     if (le != hipSuccess) return fail(COCODIFF_ERR_HIP, "qkv_proj: launch failed: %s", hipGetErrorString(le));
     return check_launch("qkv_gemm_kernel");
 }
@@ -613,13 +628,19 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
 extern "C" int cocodiff_qkv_proj(const cocodiff_shape* shape, const cocodiff_bf16* x,
                                  const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
                                  cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, void* stream) {
-    return proj_launch(shape, x, wq, wk, wv, q, k, v, false, COCODIFF_SEND_MAJOR, stream);
+    return proj_launch(shape, x, wq, wk, wv, q, k, v, OUT_SEQ, COCODIFF_SEND_MAJOR, stream);
 }
 
 extern "C" int cocodiff_qkv_proj_pack(const cocodiff_shape* shape, const cocodiff_bf16* x,
                                       const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
                                       cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, cocodiff_bf16* vbuf, int slot_order, void* stream) {
-    return proj_launch(shape, x, wq, wk, wv, qbuf, kbuf, vbuf, true, slot_order, stream);
+    return proj_launch(shape, x, wq, wk, wv, qbuf, kbuf, vbuf, OUT_CHUNKS, slot_order, stream);
+}
+
+extern "C" int cocodiff_qkv_proj_hs(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                    const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                    cocodiff_bf16* q_hs, cocodiff_bf16* k_hs, cocodiff_bf16* v_hs, void* stream) {
+    return proj_launch(shape, x, wq, wk, wv, q_hs, k_hs, v_hs, OUT_HEADS, COCODIFF_SEND_MAJOR, stream);
 }
 
 extern "C" int cocodiff_qkv_proj_plan(const cocodiff_shape* shape, int32_t n_tensors, int32_t* tile_tokens, int32_t* tile_features,

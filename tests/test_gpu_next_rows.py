@@ -284,6 +284,72 @@ def test_proj_pack_equals_proj_then_pack(oracle, name, order):
 
 
 @gpu
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_proj_hs_equals_proj_pack_unpack(oracle, name):
+    """The projection with the head-parallel epilogue against projection -> pack -> unpack (bit-identical), against the
+    oracle on sampled tokens, and on a rank range (only that range's token rows of every head are written)."""
+    cfg = CONFIGS[name]
+    print(f"proj_hs {name}", flush=True)
+    from synth import make_layer_inputs, sample_token_ids
+    inp = make_layer_inputs(cfg)
+    N, D, H, d, P = cfg.N, cfg.D, cfg.H, cfg.d, cfg.P
+    sh = cd.Shape.make(N, D, H, d, P)
+    X, Wk, Wv = to_dev(inp["X"]), to_dev(inp["Wk"]), to_dev(inp["Wv"])
+    k, v = dev_empty((N, D)), dev_empty((N, D))
+    buf = dev_empty((N * D,))
+    hk, hv, fk, fv = (dev_empty((H, N, d)) for _ in range(4))
+    cd.qkv_proj(sh, X, None, Wk, Wv, None, k, v)
+    for src, dst in ((k, hk), (v, hv)):
+        cd.a2a_pack(sh, src, buf, cd.RECV_MAJOR)
+        cd.a2a_unpack(sh, buf, dst, cd.RECV_MAJOR)
+    for t in (fk, fv):
+        t.fill_(-1)
+    cd.qkv_proj_hs(sh, X, None, Wk, Wv, None, fk, fv)
+    _sync()
+    assert np.array_equal(to_host_bits(fk), to_host_bits(hk)) and np.array_equal(to_host_bits(fv), to_host_bits(hv))
+    ids = np.arange(N) if name in ("C1", "C2") else sample_token_ids(cfg, random_tiles_per_rank=2)
+    got = to_host_bits(fv).transpose(1, 0, 2).reshape(N, D)[ids]
+    assert_float_parity(got, oracle.qkv_proj(inp["X"][ids], inp["Wv"]), f"proj_hs {name}")
+    # one rank alone: its tokens' rows in every head, nothing else
+    fk.fill_(-1)
+    r0 = P // 2
+    cd.qkv_proj_hs(cd.Shape.make(N, D, H, d, P, r0, 1), X, None, Wk, None, None, fk, None)
+    _sync()
+    part, full = to_host_bits(fk), to_host_bits(hk)
+    rows = slice(r0 * cfg.Ns, (r0 + 1) * cfg.Ns)
+    assert np.array_equal(part[:, rows], full[:, rows])
+    assert np.all(part[:, :r0 * cfg.Ns] == 0xFFFF) and np.all(part[:, (r0 + 1) * cfg.Ns:] == 0xFFFF)
+
+
+@gpu
+def test_proj_hs_off_grid_shapes_and_bounds(oracle):
+    """Shapes off the tile grid (ragged token and feature tiles, K not a multiple of 64 on the general kernel), with
+    guard bands around the head-parallel output."""
+    import torch
+    from synth import f32_to_bf16_bits
+    for N, H, d, P in ((272, 5, 64, 1), (528, 9, 64, 1), (48, 3, 40, 3), (9200, 47, 64, 1)):
+        D = H * d
+        rng = np.random.default_rng(N + d)
+        x = f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32))
+        w = f32_to_bf16_bits(rng.standard_normal((D, D), dtype=np.float32) * np.float32(D ** -0.5))
+        sh = cd.Shape.make(N, D, H, d, P)
+        G = 4096
+        raw = torch.full((N * D + 2 * G,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+        out_hs = raw[G:G + N * D]
+        seq = dev_empty((N, D))
+        xd, wd = to_dev(x), to_dev(w)
+        cd.qkv_proj_hs(sh, xd, wd, None, None, out_hs, None, None)
+        cd.qkv_proj(sh, xd, wd, None, None, seq, None, None)
+        _sync()
+        r = raw.cpu().numpy()
+        assert np.all(r[:G] == 0x5A5A) and np.all(r[-G:] == 0x5A5A), (N, D)
+        want = to_host_bits(seq).reshape(N, H, d).transpose(1, 0, 2)
+        assert np.array_equal(to_host_bits(out_hs).reshape(H, N, d), want), (N, D)
+        ids = np.concatenate([np.arange(0, 8), np.arange(N - 8, N)])
+        assert_float_parity(to_host_bits(seq)[ids], oracle.qkv_proj(x[ids], w), f"proj {N}x{D}")
+
+
+@gpu
 @pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C4", 0), ("C5", 1)])
 def test_norm_rope_pack_equals_norm_rope_then_pack(oracle, name, order):
     import torch
