@@ -67,6 +67,12 @@ def lib() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2604_14561_amd.build` "
                 "(there is no fallback path)")
+        # PyTorch brings its own HIP runtime; the tensors this binding is handed live in that runtime, so it has to be
+        # the one this library binds to as well: load torch first, whatever the caller's import order was
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         vp, ci, i32, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
         sp, rp = ctypes.POINTER(Shape), ctypes.POINTER(Rope)
