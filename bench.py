@@ -10,8 +10,8 @@ head-parallel Q (normalised, rotated), K (same) and V, and the selection's flags
   fused1qkv  one stream:  qkv_proj_pack(V, Q, K in one launch, V's tiles first) -> a2a_unpack_select -> a2a_unpack_norm_rope
   fused2     two streams: main qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K);
                           side [after V's projection] a2a_unpack_select(V); joined at the end of the step
-The default run times all three with the same --warmup / --steps and reports each; `value` is the fastest one
-measured in this run (named in config.schedule).  Also timed and reported beside it: the same step through the five
+The default run times all three with the same --warmup / --steps (three times each, interleaved, after a clock
+ramp: see time_headline) and reports each; `value` is the fastest one measured in this run (named in config.schedule).  Also timed and reported beside it: the same step through the five
 stand-alone calls only ("vfirst", two streams; "serial", one), the single-GPU direct form that writes V straight
 into the head-parallel layout ("fused1_vdirect": no exchange buffer for V), a HIP-graph replay of the headline
 schedule, the sender's share alone, every kernel alone (HBM-bound ones on cold data), the per-rank back-to-back
@@ -37,16 +37,18 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "qkv_gemm_hbm_traffic.txt")
 HEADLINE_CANDIDATES = ("fused1", "fused1qkv", "fused2")
 
 
-def measured_traffic(workload: str, kernel_tile: str):
+def measured_traffic(workload: str, kernel_tile: str, launches_per_step: int):
     """Bytes per launch that crossed the L2 <-> memory-fabric boundary for the projection kernel, from the
-    committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs of this script); None if the summary has no
-    line for this workload AND this tile shape (a summary of another kernel form does not count)."""
+    committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs of this script's --profile-projection mode);
+    None if the summary has no line for this workload, this tile shape and this number of launches per step (a
+    summary of another kernel form does not count)."""
     try:
         with open(TRAFFIC_FILE) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) >= 4 and parts[0] == "traffic_bytes_per_launch" and parts[1] == workload and parts[2] == kernel_tile:
-                    return int(parts[3])
+                if (len(parts) >= 5 and parts[0] == "traffic_bytes_per_launch" and parts[1] == workload and parts[2] == kernel_tile
+                        and parts[3] == str(launches_per_step)):
+                    return int(parts[4])
     except OSError:
         pass
     return None
@@ -66,6 +68,8 @@ class ChipSampler:
         self.clock_file = next((os.path.join(d, "freq1_input") for d in hw if os.path.exists(os.path.join(d, "freq1_input"))), None)
         # without a hwmon clock file: the driver's clock-level table, whose current entry carries a star ("1: 1846Mhz *")
         self.dpm_file = None if self.clock_file else next(iter(sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))), None)
+        cap = next((os.path.join(d, "power1_cap") for d in hw if os.path.exists(os.path.join(d, "power1_cap"))), None)
+        self.power_cap_W = self._read(cap, 1e6)
         self.samples = []      # (time, MHz or None, W or None)
         self._stop = threading.Event()
         self._thread = None
@@ -329,19 +333,20 @@ class Workload:
 
     def time_steps(self, step_fn, warmup, steps):
         """`warmup` untimed steps, then exactly `steps` steps between two synchronisations.  Returns
-        (ms per step, (t0, t1) of the timed region on the perf_counter clock)."""
+        (ms per step, (t0, t1) of the timed region on the perf_counter clock).  The selection's count is checked after
+        the timed region (a device-to-host copy in front of it would leave the GPU idle just before the clock starts)."""
         torch = self.torch
         for _ in range(warmup):
             step_fn()
         torch.cuda.synchronize()
-        self.check_selection()
         t0 = time.perf_counter()
         for _ in range(steps):
             step_fn()
         t_enq = time.perf_counter()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        log(f"    host enqueue {(t_enq - t0) * 1e3 / steps:.3f} ms of {(t1 - t0) * 1e3 / steps:.3f} ms per step")
+        self.check_selection()
+        self.enqueue_ms = (t_enq - t0) * 1e3 / steps
         return (t1 - t0) * 1e3 / steps, (t0, t1)
 
     def projection_in_step(self, step_fn, steps):
@@ -386,27 +391,39 @@ def timed_blocks(torch, fns, blocks=7):
 
 
 RAMP_SECONDS = 0.3
+REPEATS = 3
 
 
 def time_headline(w, names, warmup, steps, sampler):
     """Every schedule in `names` with the same warm-up and step count; returns ({name: entry}, fastest name).
+
     Input generation leaves the GPU idle for seconds and its clocks low, and a few warm-up steps (some milliseconds)
-    do not bring them back: whichever schedule is timed first would be charged for the ramp.  So the first schedule
-    is timed twice: once straight away ("after_idle", reported, not a candidate), then, after RAMP_SECONDS of the
-    schedules run round-robin, every schedule is timed with its own `warmup` steps in front."""
-    out = {}
+    do not bring them back; after that the chip's power management overshoots and settles over tens of milliseconds,
+    so a region of `steps` steps a few milliseconds long is charged for whatever state it starts in.  Therefore:
+    the first schedule is timed once straight away ("after_idle": reported, not used); then the schedules run
+    round-robin for RAMP_SECONDS; then every schedule is timed REPEATS times, interleaved (A B C A B C ...), each time
+    with its own `warmup` steps in front and exactly `steps` steps timed.  A schedule's figure is the median of its
+    REPEATS measurements; all of them are reported."""
     ms_idle, _ = w.time_steps(w.schedules[names[0]], warmup, steps)
     t_ramp = time.perf_counter()
     while time.perf_counter() - t_ramp < RAMP_SECONDS:
         for name in names:
             w.schedules[name]()
         w.torch.cuda.synchronize()
+    runs = {name: [] for name in names}
+    for rep in range(REPEATS):
+        for name in names:
+            ms, win = w.time_steps(w.schedules[name], warmup, steps)
+            runs[name].append((ms, win, w.enqueue_ms))
+    out = {}
     for name in names:
-        log(f"  schedule {name}")
-        ms, (t0, t1) = w.time_steps(w.schedules[name], warmup, steps)
-        out[name] = {"ms_per_step": round(ms, 4), "value": round(w.cfg.N / (ms * 1e-3), 1)}
+        ordered = sorted(runs[name], key=lambda r: r[0])
+        ms, (t0, t1), enq = ordered[len(ordered) // 2]
+        out[name] = {"ms_per_step": round(ms, 4), "value": round(w.cfg.N / (ms * 1e-3), 1),
+                     "all_ms_per_step": [round(r[0], 4) for r in runs[name]], "host_enqueue_ms_per_step": round(enq, 4)}
         if sampler:
             out[name]["chip"] = sampler.window(t0, t1)
+        log(f"  schedule {name}: {out[name]}")
     best = min(out, key=lambda n: out[n]["ms_per_step"])
     out[names[0]]["after_idle"] = {"ms_per_step": round(ms_idle, 4), "note": f"timed first, straight after input generation, before the {RAMP_SECONDS} s ramp"}
     return out, best
@@ -420,7 +437,7 @@ def roofline_of(w, schedule, steps):
     achieved = flops_per_launch / us / 1e6
     tile = w.tile_name(3 if per_step == 1 else 2)
     return {"kernel": "qkv_gemm_direct_kernel", "tile": tile, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(cfg.name, tile),
+            "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(cfg.name, tile, int(round(per_step))),
             "avg_launch_us": round(us, 2), "launches_per_step": round(per_step, 2), "event_steps": steps,
             "ms_per_step_instrumented": round(ms_instr, 4)}
 
@@ -697,6 +714,7 @@ def main() -> int:
         del src2, dst2
         attainable["sclk_MHz"] = {k_: v_["sclk_MHz"] for k_, v_ in state.items()}
         attainable["power_W"] = {k_: v_["power_W"] for k_, v_ in state.items()}
+        attainable["power_cap_W"] = int(sampler.power_cap_W) if sampler.power_cap_W else None
         log(f"  chip state under load: clocks {attainable['sclk_MHz']} MHz, socket power {attainable['power_W']} W")
         roofline["frac_of_mfma_loop"] = round(roofline["achieved"] / attainable["mfma_loop_TFLOP/s"], 4)
         if attainable["sclk_MHz"]["projection"]:
