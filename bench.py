@@ -6,11 +6,16 @@ order of the paper's Section III-C (V is projected first; its layout change and 
 Every headline schedule produces every result of the path: the three exchange buffers of the first all-to-all,
 head-parallel Q (normalised, rotated), K (same) and V, and the selection's flags, list, count and compact V.
 
+  fused0     one stream:  qkv_proj_fused(V, Q, K in one launch, V's tiles first: every tensor to its exchange buffer and to its
+                          head-parallel tensor, norm + RoPE of Q and K in the epilogue) -> vmajor_select(V)
+  fused0v    one stream:  qkv_proj_fused(V) -> qkv_proj_fused(Q, K) -> vmajor_select(V)
   fused1     one stream:  qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_select(V) -> a2a_unpack_norm_rope(Q, K)
   fused1qkv  one stream:  qkv_proj_pack(V, Q, K in one launch, V's tiles first) -> a2a_unpack_select -> a2a_unpack_norm_rope
   fused2     two streams: main qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K);
                           side [after V's projection] a2a_unpack_select(V); joined at the end of the step
-The default run times all three with the same --warmup / --steps (three times each, interleaved, after a clock
+(in fused0 / fused0v the exchange buffers of Q and K carry normalised values -- norm + RoPE on the sending side, the paper's
+order -- in the others the projection itself, normalised by the receiver's unpack).
+The default run times all five with the same --warmup / --steps (three times each, interleaved, after a clock
 ramp: see time_headline) and reports each; `value` is the fastest one measured in this run (named in config.schedule).  Also timed and reported beside it: the same step through the five
 stand-alone calls only ("vfirst", two streams; "serial", one), the single-GPU direct form that writes V straight
 into the head-parallel layout ("fused1_vdirect": no exchange buffer for V), a HIP-graph replay of the headline
@@ -34,7 +39,7 @@ METRIC = "tokens/s per layer (QKV+norm+RoPE+pack); pack/select GB/s vs HBM peak"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "qkv_gemm_hbm_traffic.txt")
-HEADLINE_CANDIDATES = ("fused1", "fused1qkv", "fused2")
+HEADLINE_CANDIDATES = ("fused0", "fused0v", "fused1", "fused1qkv", "fused2")
 
 
 def measured_traffic(workload: str, kernel_tile: str, launches_per_step: int):
@@ -164,7 +169,7 @@ class Workload:
         v_prev_host, _ = perturb_tiles(self.bits(self.hv), 1, T, cfg.n_changed, np.random.default_rng(cfg.index), cfg.noise_sigma)
         self.hv_prev = up(v_prev_host)
         del v_prev_host
-        self.schedules = {"fused1": self.step_fused1, "fused1qkv": self.step_fused1qkv, "fused2": self.step_fused2,
+        self.schedules = {"fused0": self.step_fused0, "fused0v": self.step_fused0v, "fused1": self.step_fused1, "fused1qkv": self.step_fused1qkv, "fused2": self.step_fused2,
                           "fused2x": self.step_fused2x, "fused3": self.step_fused3, "fused3s": self.step_fused3s,
                           "fused1_vdirect": self.step_fused1_vdirect,
                           "vfirst": self.step_vfirst, "vfirst3": self.step_vfirst3, "serial": self.step_serial}
@@ -205,6 +210,20 @@ class Workload:
         self.cd.a2a_unpack_norm_rope(self.sh, bq, bk, hq, hk, gq, gk, self.cfg.eps, self.rope, self.ORDER, stream=stream)
 
     # -- headline schedules (every result of the path) -------------------------------------------------------
+    def step_fused0(self, rec=None):
+        cd, sh, st, c = self.cd, self.sh, self.s_main, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj_fused(sh, self.X, self.Wq, self.Wk, self.Wv, self.gq, self.gk, c.eps, self.rope,
+                                                       self.bq, self.bk, self.bv, self.ORDER, self.hq, self.hk, self.hv, stream=s))
+        self.select(st)
+
+    def step_fused0v(self, rec=None):
+        cd, sh, st, c = self.cd, self.sh, self.s_main, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj_fused(sh, self.X, None, None, self.Wv, None, None, c.eps, None,
+                                                       None, None, self.bv, self.ORDER, None, None, self.hv, stream=s))
+        self.proj(rec, st, lambda s: cd.qkv_proj_fused(sh, self.X, self.Wq, self.Wk, None, self.gq, self.gk, c.eps, self.rope,
+                                                       self.bq, self.bk, None, self.ORDER, self.hq, self.hk, None, stream=s))
+        self.select(st)
+
     def step_fused1(self, rec=None):
         cd, sh, st = self.cd, self.sh, self.s_main
         self.proj(rec, st, lambda s: cd.qkv_proj_pack(sh, self.X, None, None, self.Wv, None, None, self.bv, self.ORDER, stream=s))
@@ -366,8 +385,8 @@ class Workload:
         total_us = sum(e0.elapsed_time(e1) for e0, e1 in rec) * 1e3
         return total_us / len(rec), len(rec) / steps, ms
 
-    def tile_name(self, n_tensors):
-        p = self.cd.qkv_proj_plan(self.sh, n_tensors)
+    def tile_name(self, n_tensors, whole_heads=False):
+        p = self.cd.qkv_proj_plan(self.sh, n_tensors, whole_heads)
         return f"{p['tile_tokens']}x{p['tile_features']}"
 
 
@@ -435,8 +454,9 @@ def roofline_of(w, schedule, steps):
     us, per_step, ms_instr = w.projection_in_step(w.schedules[schedule], steps)
     flops_per_launch = 2.0 * cfg.N * (3 * cfg.D) * cfg.D / per_step
     achieved = flops_per_launch / us / 1e6
-    tile = w.tile_name(3 if per_step == 1 else 2)
-    return {"kernel": "qkv_gemm_direct_kernel", "tile": tile, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+    fused = schedule.startswith("fused0")
+    tile = w.tile_name(3 if per_step == 1 else 2, fused)
+    return {"kernel": "qkv_gemm_direct_kernel" + (" (norm + RoPE epilogue, two destinations)" if fused else ""), "tile": tile, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(cfg.name, tile, int(round(per_step))),
             "avg_launch_us": round(us, 2), "launches_per_step": round(per_step, 2), "event_steps": steps,
             "ms_per_step_instrumented": round(ms_instr, 4)}
@@ -454,7 +474,8 @@ def main() -> int:
     ap.add_argument("--no-other-workloads", action="store_true")
     ap.add_argument("--profile-projection", type=int, default=0, metavar="N",
                     help="profiling aid for rocprofv3 counter runs: N launches each of the projection with one, two and three "
-                         "weights (exchange-buffer epilogue) and of a 1000 MiB calibration copy, and nothing else")
+                         "weights (exchange-buffer epilogue), of the fused form with three weights and of a 1000 MiB calibration "
+                         "copy, and nothing else")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs all P logical ranks of the path on ONE GPU; "
@@ -490,6 +511,7 @@ def main() -> int:
             cd.qkv_proj_pack(w.sh, w.X, None, None, w.Wv, None, None, w.bv, w.ORDER)
             cd.qkv_proj_pack(w.sh, w.X, w.Wq, w.Wk, None, w.bq, w.bk, None, w.ORDER)
             cd.qkv_proj_pack(w.sh, w.X, w.Wq, w.Wk, w.Wv, w.bq, w.bk, w.bv, w.ORDER)
+            cd.qkv_proj_fused(w.sh, w.X, w.Wq, w.Wk, w.Wv, w.gq, w.gk, cfg.eps, w.rope, w.bq, w.bk, w.bv, w.ORDER, w.hq, w.hk, w.hv)
             cd.util_copy(src_big, dst_big, big)
         torch.cuda.synchronize()
         sampler.stop()
@@ -636,8 +658,11 @@ def main() -> int:
         add("qkv_proj_pack_v", [lambda: cd.qkv_proj_pack(sh, X, None, None, Wv, None, None, bv, O)], flops=g1)
         add("qkv_proj_hs_v", [lambda: cd.qkv_proj_hs(sh, X, None, None, Wv, None, None, w.hv)], flops=g1)
         add("qkv_proj_pack_qkv", [lambda: cd.qkv_proj_pack(sh, X, Wq, Wk, Wv, w.bq, w.bk, bv, O)], flops=3 * g1)
-        roofline["alone"] = {"frac": kernels["qkv_proj_pack_qkv"]["frac_mfma_peak"], "TFLOP/s": kernels["qkv_proj_pack_qkv"]["TFLOP/s"],
-                             "launch": "qkv_proj_pack, three weights, nothing beside it"}
+        add("qkv_proj_fused_qkv", [lambda: cd.qkv_proj_fused(sh, X, Wq, Wk, Wv, w.gq, w.gk, cfg.eps, w.rope, w.bq, w.bk, bv, O, w.hq, w.hk, w.hv)],
+            flops=3 * g1, extra={"tile": w.tile_name(3, True)})
+        alone_key = "qkv_proj_fused_qkv" if best.startswith("fused0") else "qkv_proj_pack_qkv"
+        roofline["alone"] = {"frac": kernels[alone_key]["frac_mfma_peak"], "TFLOP/s": kernels[alone_key]["TFLOP/s"],
+                             "launch": alone_key.replace("_qkv", "") + ", three weights, nothing beside it"}
 
         # rotation sets: a (token-major), b (exchange buffer), h and p (head-parallel current / previous V; never written)
         R = int(min(64, max(1, -(-(640 << 20) // (2 * tensor_bytes)))))
@@ -796,9 +821,14 @@ def main() -> int:
                    "roofline": roofline_of(ow, obest, max(args.steps, 50))}
             tb = oc.N * oc.D * 2
             g3 = 6.0 * oc.N * oc.D * oc.D
-            us_alone = timed_blocks(torch, [lambda: cd.qkv_proj_pack(ow.sh, ow.X, ow.Wq, ow.Wk, ow.Wv, ow.bq, ow.bk, ow.bv, ow.ORDER)], blocks=3)[0]
+            if obest.startswith("fused0"):
+                alone_fn = lambda: cd.qkv_proj_fused(ow.sh, ow.X, ow.Wq, ow.Wk, ow.Wv, ow.gq, ow.gk, oc.eps, ow.rope, ow.bq, ow.bk, ow.bv,
+                                                     ow.ORDER, ow.hq, ow.hk, ow.hv)
+            else:
+                alone_fn = lambda: cd.qkv_proj_pack(ow.sh, ow.X, ow.Wq, ow.Wk, ow.Wv, ow.bq, ow.bk, ow.bv, ow.ORDER)
+            us_alone = timed_blocks(torch, [alone_fn], blocks=3)[0]
             ent["roofline"]["alone"] = {"frac": round(g3 / us_alone / 1e6 / PEAK_BF16_TFLOPS, 4), "TFLOP/s": round(g3 / us_alone / 1e6, 1),
-                                        "launch": "qkv_proj_pack, three weights, nothing beside it"}
+                                        "launch": ("qkv_proj_fused" if obest.startswith("fused0") else "qkv_proj_pack") + ", three weights, nothing beside it"}
             f_o = oc.n_changed / ow.NT
             hbm = {}
             for kname, fn, nb in (("a2a_unpack_select", lambda: ow.unpack_select(None), (3 + f_o) * tb),

@@ -153,6 +153,26 @@ COCODIFF_API int cocodiff_qkv_proj_hs(const cocodiff_shape* shape, const cocodif
                                       cocodiff_bf16* q_hs, cocodiff_bf16* k_hs, cocodiff_bf16* v_hs, void* stream);
 
 /*
+ * cocodiff_qkv_proj_fused: the sender's whole share in the projection kernel.  For every given weight the epilogue
+ * writes the result to its exchange buffer (qbuf / kbuf / vbuf, chunk order as cocodiff_a2a_pack writes it) AND to its
+ * head-parallel tensor (q_hs / k_hs / v_hs [H][N][d], what cocodiff_a2a_unpack of that buffer gives); either of the
+ * two destinations of a tensor may be NULL.  Q and K are RMS-normalised per (token, head) and rotated (Section II-B,
+ * the rules of cocodiff_qk_norm_rope) on the fp32 accumulators before the one rounding to bf16, so their exchange
+ * buffers carry normalised values (norm + RoPE on the sending side, the order of Section III-C) and they are rounded
+ * once where the chain cocodiff_qkv_proj -> cocodiff_qk_norm_rope rounds twice: the results agree with that chain
+ * to within the float tolerance, not bit for bit.  V is bit-identical to cocodiff_qkv_proj_pack / cocodiff_qkv_proj_hs.
+ * The two destinations of a tensor hold the same bits.
+ * Rules: as cocodiff_qkv_proj and cocodiff_qk_norm_rope; gamma_q / gamma_k required with wq / wk; rope required when Q
+ * or K is given; d must be 64, 128 or 256; D a multiple of 64, at least 192 (COCODIFF_ERR_SHAPE otherwise).
+ */
+COCODIFF_API int cocodiff_qkv_proj_fused(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                         const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                         const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                         const cocodiff_rope* rope,
+                                         cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, cocodiff_bf16* vbuf, int slot_order,
+                                         cocodiff_bf16* q_hs, cocodiff_bf16* k_hs, cocodiff_bf16* v_hs, void* stream);
+
+/*
  * cocodiff_a2a_unpack_select = cocodiff_a2a_unpack of V followed by cocodiff_vmajor_select on the unpacked tensor
  * (head-parallel: S = H, W = d): the selection's first pass reads the current values from the exchange buffer
  * vbuf, writes them to their place in v_hs [H][N][d] and compares them with v_prev on the way, so the unpacked
@@ -317,10 +337,12 @@ COCODIFF_API int cocodiff_a2a_unpack_seq(const cocodiff_shape* shape, const coco
 
 /* Which tile the projection takes for this shape's rank range and n_tensors (1..3) weights in one launch, on the
  * current device: tile extent in tokens and features, number of workgroups (= tiles), compute units of the device.
- * Any out pointer may be NULL.  Host arithmetic only; it needs a current HIP device for the unit count
- * (COCODIFF_ERR_HIP without one).  For reports and for tests that must land on a given tile shape. */
-COCODIFF_API int cocodiff_qkv_proj_plan(const cocodiff_shape* shape, int32_t n_tensors, int32_t* tile_tokens,
-                                        int32_t* tile_features, int32_t* n_tiles, int32_t* n_compute_units);
+ * whole_heads != 0: the choice cocodiff_qkv_proj_fused makes (its tiles are 256 features wide), else that of the
+ * other projection calls.  Any out pointer may be NULL.  Host arithmetic only; it needs a current HIP device for
+ * the unit count (COCODIFF_ERR_HIP without one).  For reports and for tests that must land on a given tile shape. */
+COCODIFF_API int cocodiff_qkv_proj_plan(const cocodiff_shape* shape, int32_t n_tensors, int32_t whole_heads,
+                                        int32_t* tile_tokens, int32_t* tile_features, int32_t* n_tiles,
+                                        int32_t* n_compute_units);
 
 /* Bytes of the cos/sin table described at cocodiff_rope (0 on a bad description; `cs` is ignored). */
 COCODIFF_API size_t cocodiff_rope_table_bytes(const cocodiff_rope* rope);

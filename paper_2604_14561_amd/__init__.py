@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     qk_norm_rope,
     qk_norm_rope_pack,
     qkv_proj,
+    qkv_proj_fused,
     qkv_proj_hs,
     qkv_proj_pack,
     qkv_proj_plan,

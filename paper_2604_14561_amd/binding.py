@@ -20,7 +20,7 @@ ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_CAPACITY, ERR_HIP = -1, -2, -3, -4, -5
 SEND_MAJOR, RECV_MAJOR = 0, 1
 
 EXPORTS = (
-    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qkv_proj_hs", "cocodiff_qk_norm_rope_pack",
+    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qkv_proj_hs", "cocodiff_qkv_proj_fused", "cocodiff_qk_norm_rope_pack",
     "cocodiff_a2a_unpack_select", "cocodiff_a2a_unpack_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_static", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
@@ -99,7 +99,9 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_rope_table_bytes.restype = sz
         L.cocodiff_rope_table_fill.argtypes = [rp, vp]
         L.cocodiff_util_copy.argtypes = [vp, vp, sz, vp]
-        L.cocodiff_qkv_proj_plan.argtypes = [sp, i32, vp, vp, vp, vp]
+        L.cocodiff_qkv_proj_plan.argtypes = [sp, i32, i32, vp, vp, vp, vp]
+        L.cocodiff_qkv_proj_fused.argtypes = [sp, vp, vp, vp, vp, vp, vp, f32, rp, vp, vp, vp, ci, vp, vp, vp, vp]
+        L.cocodiff_qkv_proj_fused.restype = ci
         L.cocodiff_qkv_proj_plan.restype = ci
         L.cocodiff_version.restype = ctypes.c_char_p
         L.cocodiff_last_error.restype = ctypes.c_char_p
@@ -111,7 +113,7 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_a2a_unpack_norm_rope.restype = ci
         L.cocodiff_qkv_proj_pack.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ci, vp]
         L.cocodiff_qk_norm_rope_pack.argtypes = [sp, vp, vp, vp, vp, ctypes.c_float, rp, vp, vp, ci, vp]
-        for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qkv_proj_hs", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
+        for name in ("cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qkv_proj_hs", "cocodiff_qkv_proj_fused", "cocodiff_qk_norm_rope_pack", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
                      "cocodiff_vmajor_select", "cocodiff_vmajor_gather", "cocodiff_vmajor_scatter",
                      "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk",
                      "cocodiff_a2a_pack_hs", "cocodiff_a2a_unpack_seq", "cocodiff_rope_table_fill", "cocodiff_util_copy"):
@@ -265,10 +267,18 @@ def rope_table(grid: Sequence[int], pairs: Sequence[int], theta: float) -> np.nd
     return out
 
 
-def qkv_proj_plan(shape: Shape, n_tensors: int) -> dict:
-    """Tile shape and workgroup count the projection takes for this shape and number of weights per launch."""
+def qkv_proj_fused(shape: Shape, x, wq, wk, wv, gamma_q, gamma_k, eps: float, rope: Optional[Rope], qbuf, kbuf, vbuf,
+                   slot_order: int, q_hs, k_hs, v_hs, stream=None) -> None:
+    _check(lib().cocodiff_qkv_proj_fused(ctypes.byref(shape), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(gamma_q), _ptr(gamma_k),
+                                         float(eps), ctypes.byref(rope) if rope is not None else None, _ptr(qbuf), _ptr(kbuf),
+                                         _ptr(vbuf), int(slot_order), _ptr(q_hs), _ptr(k_hs), _ptr(v_hs), _stream(stream)))
+
+
+def qkv_proj_plan(shape: Shape, n_tensors: int, whole_heads: bool = False) -> dict:
+    """Tile shape and workgroup count the projection takes for this shape and number of weights per launch
+    (whole_heads: the choice of qkv_proj_fused)."""
     out = [ctypes.c_int32(0) for _ in range(4)]
-    _check(lib().cocodiff_qkv_proj_plan(ctypes.byref(shape), int(n_tensors), *(ctypes.byref(o) for o in out)))
+    _check(lib().cocodiff_qkv_proj_plan(ctypes.byref(shape), int(n_tensors), int(bool(whole_heads)), *(ctypes.byref(o) for o in out)))
     return {"tile_tokens": out[0].value, "tile_features": out[1].value, "n_tiles": out[2].value, "compute_units": out[3].value}
 
 

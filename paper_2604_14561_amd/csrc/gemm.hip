@@ -48,11 +48,20 @@ struct GemmArgs {
     int32_t recv_major;
     // outputs in head-parallel order [H][N][d]: all tokens, 16-byte vectors per head row
     uint32_t N_all, d8;
+    // OUT_FUSED: second destination (head-parallel; y[] is then the exchange buffer; either may be null), RMSNorm + RoPE
+    // of the tensors that have a gamma
+    uint16_t* y2[3];
+    const uint16_t* gamma[3];
+    uint32_t d;                // features per head
+    float inv_d, eps;
+    RopeDev rope;
 };
 
 // Where the epilogue writes: token-major [N][D]; the exchange-buffer chunks of the first all-to-all; or the
 // head-parallel tensor [H][N][d] that all-to-all ends in (pack, exchange and unpack folded into the store address).
-enum OutLayout { OUT_SEQ = 0, OUT_CHUNKS = 1, OUT_HEADS = 2 };
+// OUT_FUSED: Q and K are normalised and rotated in the epilogue (on the fp32 accumulators), and every tensor goes to its
+// exchange buffer and to its head-parallel tensor (whichever are given).
+enum OutLayout { OUT_SEQ = 0, OUT_CHUNKS = 1, OUT_HEADS = 2, OUT_FUSED = 3 };
 
 // [rows][64] bf16 tiles (128-byte rows): any 16 consecutive rows of one column land in 16 different
 // 16-byte slots of the 256-byte bank span.
@@ -124,8 +133,8 @@ struct EpilogueRows {
 // of the exchange buffer Y, row m (Hp*d is a multiple of 8, so a 16-byte vector never straddles two chunks).
 // OUT_HEADS: they go to row n of head feature / d of Y = [H][N][d] (d is a multiple of 8).
 template <uint32_t COLS, uint32_t ROWS, int LAYOUT>
-__device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lane, uint16_t* __restrict__ Y, size_t row0,
-                                           uint32_t tok0, uint32_t feat0, uint32_t M, uint32_t D, const GemmArgs& a) {
+__device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lane, uint16_t* __restrict__ Y, uint16_t* __restrict__ Y2,
+                                           size_t row0, uint32_t tok0, uint32_t feat0, uint32_t M, uint32_t D, const GemmArgs& a) {
     constexpr uint32_t CP = EpilogueRows<COLS>::CP, ROWB = EpilogueRows<COLS>::ROWB;
     constexpr uint32_t RPI = 64 / CP;            // rows per read instruction
     const uint32_t c16 = lane % CP, rsub = lane / CP;
@@ -136,16 +145,18 @@ __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lan
         const uint32_t feat = feat0 + c16 * 8u;
         if (c16 < COLS && tok < M && feat < D) {
             const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & (CP - 1u))) << 4));
-            if (LAYOUT == OUT_CHUNKS) {
+            if (LAYOUT == OUT_CHUNKS || (LAYOUT == OUT_FUSED && Y)) {
                 const uint32_t n = (uint32_t)row0 + tok, r = n / a.Ns, m = n - r * a.Ns;
                 const uint32_t v8 = feat >> 3, p = v8 / a.row8, c = v8 - p * a.row8;
                 const size_t slot = a.recv_major ? (size_t)p * a.P + r : (size_t)r * a.P + p;
                 reinterpret_cast<vec16*>(Y)[slot * a.chunk8 + (size_t)m * a.row8 + c] = v;
-            } else if (LAYOUT == OUT_HEADS) {
+            }
+            if (LAYOUT == OUT_HEADS || (LAYOUT == OUT_FUSED && Y2)) {
                 const uint32_t n = (uint32_t)row0 + tok;
                 const uint32_t v8 = feat >> 3, h = v8 / a.d8, c = v8 - h * a.d8;
-                reinterpret_cast<vec16*>(Y)[((size_t)h * a.N_all + n) * a.d8 + c] = v;
-            } else {
+                reinterpret_cast<vec16*>(LAYOUT == OUT_HEADS ? Y : Y2)[((size_t)h * a.N_all + n) * a.d8 + c] = v;
+            }
+            if (LAYOUT == OUT_SEQ) {
                 *reinterpret_cast<vec16*>(Y + (row0 + tok) * D + feat) = v;
             }
         }
@@ -156,8 +167,8 @@ __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lan
 // 32i + 8*(e/4) + 4*(l/32) + e%4 of token 32j + l%32.
 template <int NI, int NJ, int LAYOUT>
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane,
-                                           uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
-                                           uint32_t M, uint32_t D, const GemmArgs& a) {
+                                           uint16_t* __restrict__ Y, uint16_t* __restrict__ Y2, size_t row0, uint32_t tok0,
+                                           uint32_t feat0, uint32_t M, uint32_t D, const GemmArgs& a) {
     const uint32_t frag_row = lane & 31u, frag_half = lane >> 5;
 #pragma unroll
     for (int i = 0; i < NI; ++i)
@@ -167,15 +178,13 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[NI][NJ], unsigned
             for (int g = 0; g < 4; ++g)
                 EpilogueRows<NI * 4>::put4(ep, 32u * j + frag_row, 32u * i + 8u * g + 4u * frag_half, acc[i][j][4 * g + 0],
                                            acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-    store_rows<NI * 4, NJ * 32, LAYOUT>(ep, lane, Y, row0, tok0, feat0, M, D, a);
+    store_rows<NI * 4, NJ * 32, LAYOUT>(ep, lane, Y, Y2, row0, tok0, feat0, M, D, a);
 }
 
 // 16 x 16 accumulator tiles (v_mfma_f32_16x16x32_bf16): element e of lane l in tile (i, j) is feature
 // 16i + 4*(l/16) + e of token 16j + l%16.
-template <int NI, int NJ, int LAYOUT>
-__device__ __forceinline__ void store_tile16(const f32x4 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane,
-                                             uint16_t* __restrict__ Y, size_t row0, uint32_t tok0, uint32_t feat0,
-                                             uint32_t M, uint32_t D, const GemmArgs& a) {
+template <int NI, int NJ>
+__device__ __forceinline__ void stage_tile16(const f32x4 (&acc)[NI][NJ], unsigned char* ep, uint32_t lane) {
     const uint32_t frag_row = lane & 15u, frag_q = lane >> 4;
 #pragma unroll
     for (int i = 0; i < NI; ++i)
@@ -183,7 +192,125 @@ __device__ __forceinline__ void store_tile16(const f32x4 (&acc)[NI][NJ], unsigne
         for (int j = 0; j < NJ; ++j)
             EpilogueRows<NI * 2>::put4(ep, 16u * j + frag_row, 16u * i + 4u * frag_q, acc[i][j][0], acc[i][j][1], acc[i][j][2],
                                        acc[i][j][3]);
-    store_rows<NI * 2, NJ * 16, LAYOUT>(ep, lane, Y, row0, tok0, feat0, M, D, a);
+}
+
+// RMSNorm over every head row and RoPE, on a wavefront's fp32 accumulators (NI feature tiles x NJ token tiles of 16 x 16:
+// lane l holds features 16i + 4(l/16) + e, e = 0..3, of token 16j + l%16), in the arithmetic order of the stand-alone
+// norm + RoPE kernel (x * rinv * gamma, then the rotation) -- but on the unrounded projection, so Q and K are rounded
+// to bf16 once instead of twice -- and straight on into the epilogue's staging rows (the first half of store_tile16).
+// A head of d features is `d / (16 NI)` wavefronts wide (1, 2 or 4, neighbours along the features): each writes its
+// partial sums of squares to `xch` ([wavefront][token]) and, after a workgroup barrier, adds the group's partial sums
+// in a fixed order, so every wavefront of a head works with the same bits.
+// The rotation goes token tile by token tile: the 2 NI (cos, sin) values of a lane's token are loaded one token tile
+// ahead, and a token tile's accumulators are dead once it is staged, so the whole thing fits the registers the K loop had.
+// n_first: global index of the wavefront's token 0; tokens beyond n_last (rows past the end of a ragged tile, never
+// stored) take n_last's rotation.  feat0: the wavefront's first feature within its tensor.
+template <int NI, int NJ, int WN>
+__device__ __forceinline__ void norm_rope_stage(f32x4 (&acc)[NI][NJ], unsigned char* ep, const GemmArgs& a, const uint16_t* __restrict__ gamma,
+                                                uint32_t lane, uint32_t wave, uint32_t n_first, uint32_t n_last, uint32_t feat0, float* xch) {
+    constexpr uint32_t WF = NI * 16;                 // features per wavefront
+    const uint32_t g4 = lane >> 4, tl = lane & 15u;
+    float rinv[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s += acc[i][j][e] * acc[i][j][e];
+        s += __shfl_xor(s, 16, 64);
+        s += __shfl_xor(s, 32, 64);
+        rinv[j] = s;
+    }
+    const uint32_t group = a.d / WF;                 // the same for the whole launch
+    if (group > 1) {
+        if (lane < 16) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) xch[wave * (NJ * 16) + 16 * j + lane] = rinv[j];
+        }
+        __syncthreads();
+        const uint32_t wf = wave % WN;
+        const uint32_t w0 = wave - wf + (wf / group) * group;     // the head's first wavefront (same token half)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            float s = 0.f;
+            for (uint32_t w = 0; w < group; ++w) s += xch[(w0 + w) * (NJ * 16) + 16 * j + tl];
+            rinv[j] = s;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) rinv[j] = 1.0f / sqrtf(rinv[j] * a.inv_d + a.eps);
+
+    // the lane's 2 NI rotary pairs (two per feature tile): which axis' table, and the float offset inside a table row
+    const uint32_t fh0 = feat0 % a.d + 4u * g4;      // this lane's first feature inside its head, for feature tile 0
+    uint32_t axis[NI][2], col[NI][2];
+    float g[NI][4];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const uint2 gw = *reinterpret_cast<const uint2*>(gamma + fh0 + 16u * i);
+        g[i][0] = bf16_lo(gw.x); g[i][1] = bf16_hi(gw.x); g[i][2] = bf16_lo(gw.y); g[i][3] = bf16_hi(gw.y);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            uint32_t jl = (fh0 + 16u * i) / 2u + q;
+            int x = 0;
+            while (x < a.rope.n_axes - 1 && jl >= (uint32_t)a.rope.pairs[x]) {
+                jl -= (uint32_t)a.rope.pairs[x];
+                ++x;
+            }
+            axis[i][q] = (uint32_t)x;
+            col[i][q] = 2u * jl;
+        }
+    }
+    // (cos, sin) of the lane's pairs for its token of token tile j
+    auto load_cs = [&](int j, float2 (&cs)[NI][2]) {
+        uint32_t rem = min(n_first + 16u * j + tl, n_last);     // grid coordinates, last axis fastest
+        uint32_t row0, row1 = 0, row2 = 0;                      // where the token's row starts in each axis' table
+        if (a.rope.n_axes > 2) {
+            row2 = (uint32_t)a.rope.offset[2] + rem % (uint32_t)a.rope.grid[2] * (2u * (uint32_t)a.rope.pairs[2]);
+            rem /= (uint32_t)a.rope.grid[2];
+        }
+        if (a.rope.n_axes > 1) {
+            row1 = (uint32_t)a.rope.offset[1] + rem % (uint32_t)a.rope.grid[1] * (2u * (uint32_t)a.rope.pairs[1]);
+            rem /= (uint32_t)a.rope.grid[1];
+        }
+        row0 = (uint32_t)a.rope.offset[0] + rem % (uint32_t)a.rope.grid[0] * (2u * (uint32_t)a.rope.pairs[0]);
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const uint32_t row = axis[i][q] == 0 ? row0 : axis[i][q] == 1 ? row1 : row2;
+                cs[i][q] = *reinterpret_cast<const float2*>(a.rope.cs + row + col[i][q]);
+            }
+    };
+    auto rotate_stage = [&](int j, const float2 (&cs)[NI][2]) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            float o[4];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const float ev = acc[i][j][2 * q] * rinv[j] * g[i][2 * q];
+                const float od = acc[i][j][2 * q + 1] * rinv[j] * g[i][2 * q + 1];
+                o[2 * q] = ev * cs[i][q].x - od * cs[i][q].y;
+                o[2 * q + 1] = ev * cs[i][q].y + od * cs[i][q].x;
+            }
+            EpilogueRows<NI * 2>::put4(ep, 16u * j + tl, 16u * i + 4u * g4, o[0], o[1], o[2], o[3]);
+        }
+    };
+    float2 cs_a[NI][2], cs_b[NI][2];
+    load_cs(0, cs_a);
+#pragma unroll
+    for (int j = 0; j < NJ; j += 2) {
+        if (j + 1 < NJ) load_cs(j + 1, cs_b);
+        __builtin_amdgcn_sched_barrier(0);
+        rotate_stage(j, cs_a);
+        __builtin_amdgcn_sched_barrier(0);
+        if (j + 1 < NJ) {
+            if (j + 2 < NJ) load_cs(j + 2, cs_a);
+            __builtin_amdgcn_sched_barrier(0);
+            rotate_stage(j + 1, cs_b);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 }
 
 // s_waitcnt: at most WAIT global->LDS loads of this wavefront still in flight (LDS-read counter untouched)
@@ -390,9 +517,21 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     k_step(kt, xs, ws, no{}, no{}, w0, no{});      // step n_k-1
     __syncthreads();
     constexpr int kEpilogueBytes = NJ * 16 * EpilogueRows<NI * 2>::ROWB;   // per wavefront, see store_tile16
-    static_assert(WAVES * kEpilogueBytes <= ring_lds_bytes(TM, TN), "the epilogue reuses the ring's LDS");
-    store_tile16<NI, NJ, LAYOUT>(acc, smem + wave * kEpilogueBytes, lane, a.y[tc.tensor], (size_t)a.row_begin,
-                                 tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
+    constexpr int kExchangeBytes = LAYOUT == OUT_FUSED ? WAVES * NJ * 16 * 4 : 0;   // partial sums of squares, see norm_rope_acc
+    static_assert(WAVES * kEpilogueBytes + kExchangeBytes <= ring_lds_bytes(TM, TN), "the epilogue reuses the ring's LDS");
+    unsigned char* ep = smem + wave * kEpilogueBytes;
+    bool staged = false;
+    if constexpr (LAYOUT == OUT_FUSED) {
+        if (a.gamma[tc.tensor]) {     // the same for the whole workgroup: its barrier is taken by all or by none
+            norm_rope_stage<NI, NJ, WN>(acc, ep, a, a.gamma[tc.tensor], lane, wave, (uint32_t)a.row_begin + tc.m0 + wave_t,
+                                        (uint32_t)a.row_begin + (uint32_t)a.M - 1u, tc.f0 + wave_f,
+                                        reinterpret_cast<float*>(smem + WAVES * kEpilogueBytes));
+            staged = true;
+        }
+    }
+    if (!staged) stage_tile16<NI, NJ>(acc, ep, lane);
+    store_rows<NI * 2, NJ * 16, LAYOUT>(ep, lane, a.y[tc.tensor], LAYOUT == OUT_FUSED ? a.y2[tc.tensor] : nullptr, (size_t)a.row_begin,
+                                        tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -474,7 +613,7 @@ __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArg
         if (kt + 1 < n_k) store_stage(cur ^ 1u);
         __syncthreads();
     }
-    store_tile<4, 4, LAYOUT>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], (size_t)a.row_begin, tc.m0 + wave_t,
+    store_tile<4, 4, LAYOUT>(acc, smem + wave * (128 * 256), lane, a.y[tc.tensor], nullptr, (size_t)a.row_begin, tc.m0 + wave_t,
                           tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
 
@@ -483,13 +622,19 @@ __global__ void __launch_bounds__(kStagedThreads) qkv_gemm_staged_kernel(GemmArg
 struct TileKernel {
     int bm, bn, threads, lds;
     double penalty;               // measured per-flop cost against the 256 x 256 tile
-    const void* entry[3];         // by OutLayout
+    const void* entry[4];         // by OutLayout (OUT_FUSED only for the shapes of whole 256-feature tiles)
 };
 template <int WN, int NI, int NJ>
 TileKernel tile_kernel(double penalty) {
     return {2 * NJ * 16, WN * NI * 16, 128 * WN, ring_lds_bytes(2 * NJ * 16, WN * NI * 16), penalty,
             {(const void*)qkv_gemm_direct_kernel<WN, NI, NJ, OUT_SEQ>, (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, OUT_CHUNKS>,
-             (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, OUT_HEADS>}};
+             (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, OUT_HEADS>, nullptr}};
+}
+// a shape for the fused call only (tiles 256 features wide: whole heads of 64, 128 or 256)
+template <int WN, int NI, int NJ>
+TileKernel fused_tile_kernel(double penalty) {
+    return {2 * NJ * 16, WN * NI * 16, 128 * WN, ring_lds_bytes(2 * NJ * 16, WN * NI * 16), penalty,
+            {nullptr, nullptr, nullptr, (const void*)qkv_gemm_direct_kernel<WN, NI, NJ, OUT_FUSED>}};
 }
 
 // The tile shapes of the main kernel, and which one a launch of M tokens x D features x n_tensors weights takes.
@@ -497,10 +642,13 @@ TileKernel tile_kernel(double penalty) {
 // units so much better that they win all the same.  Cost = rounds x tile area x a measured per-flop penalty, a round
 // being one tile on every unit.  (Measured and left out: 224 x 256 equals 288 x 192 at 9216 tokens and nothing else
 // gains from it; 160 x 192, 256 x 192 and 192 x 256 win a few percent at 2304 tokens only.)
-static const TileKernel* tile_shapes(int* count) {
+// whole_heads: the shapes of the fused call, all 256 features wide (a head row must lie inside one tile); their
+// penalties follow the same two ratios (operand bytes and fragment reads per flop) as the measured ones.
+static const TileKernel* tile_shapes(bool whole_heads, int* count) {
     static const TileKernel shapes[] = {tile_kernel<4, 4, 8>(1.0), tile_kernel<4, 3, 9>(kPenalty288), tile_kernel<4, 3, 6>(kPenalty192)};
-    *count = (int)(sizeof(shapes) / sizeof(shapes[0]));
-    return shapes;
+    static const TileKernel fused[] = {fused_tile_kernel<4, 4, 8>(1.0), fused_tile_kernel<4, 4, 7>(1.035), fused_tile_kernel<4, 4, 6>(1.08)};
+    *count = 3;
+    return whole_heads ? fused : shapes;
 }
 
 struct LaunchPlan {
@@ -509,7 +657,7 @@ struct LaunchPlan {
     int32_t bm, bn, tiles_m, tiles_n_per_tensor, n_cu;
 };
 
-static LaunchPlan plan_launch(int32_t M, int32_t D, int32_t n_tensors) {
+static LaunchPlan plan_launch(int32_t M, int32_t D, int32_t n_tensors, bool whole_heads) {
     static const int n_cu = [] {     // asked once (thread-safe initialisation); 0 = could not be read
         int dev = 0, val = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&val, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
@@ -520,7 +668,7 @@ static LaunchPlan plan_launch(int32_t M, int32_t D, int32_t n_tensors) {
     p.n_cu = n_cu;
     if (n_cu <= 0) return p;
     int n_shapes = 0;
-    const TileKernel* shapes = tile_shapes(&n_shapes);
+    const TileKernel* shapes = tile_shapes(whole_heads, &n_shapes);
     p.pick = &shapes[0];
     static const int forced_tile = (int)tune_value("COCODIFF_GEMM_TILE", 0);     // tuning builds only
     double best = 0.0;
@@ -546,18 +694,41 @@ static LaunchPlan plan_launch(int32_t M, int32_t D, int32_t n_tensors) {
 using namespace cocodiff;
 
 // layout OUT_SEQ: q, k, v are [N][D]; OUT_CHUNKS: they are exchange buffers, written in chunk order; OUT_HEADS: [H][N][d].
+// OUT_FUSED: q, k, v are the exchange buffers and `fused` holds the head-parallel tensors, the gammas and the rotation.
+struct FusedExtras {
+    cocodiff_bf16* hs[3];              // q_hs, k_hs, v_hs
+    const cocodiff_bf16* gamma[2];     // gamma_q, gamma_k
+    float eps;
+    RopeDev rope;
+};
+
 static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
                        const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
-                       cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, OutLayout layout, int slot_order, void* stream) {
-    const bool packed = layout == OUT_CHUNKS;
+                       cocodiff_bf16* q, cocodiff_bf16* k, cocodiff_bf16* v, OutLayout layout, int slot_order, void* stream,
+                       const FusedExtras* fused = nullptr) {
+    const bool packed = layout == OUT_CHUNKS || layout == OUT_FUSED;
     int rc = check_shape(shape);
     if (rc != COCODIFF_OK) return rc;
     if (packed && slot_order != COCODIFF_SEND_MAJOR && slot_order != COCODIFF_RECV_MAJOR)
         return fail(COCODIFF_ERR_SHAPE, "qkv_proj_pack: slot_order (%d) must be SEND_MAJOR or RECV_MAJOR", slot_order);
     if (!x) return fail(COCODIFF_ERR_NULL, "qkv_proj: x is NULL");
-    if ((wq == nullptr) != (q == nullptr) || (wk == nullptr) != (k == nullptr) || (wv == nullptr) != (v == nullptr))
-        return fail(COCODIFF_ERR_NULL, "qkv_proj: a weight and its output must be given together");
-    if (!q && !k && !v) return fail(COCODIFF_ERR_NULL, "qkv_proj: no (weight, output) pair given");
+    if (fused) {
+        const cocodiff_bf16* w3[3] = {wq, wk, wv};
+        cocodiff_bf16* b3[3] = {q, k, v};
+        for (int i = 0; i < 3; ++i) {
+            const bool any_out = b3[i] || fused->hs[i];
+            if ((w3[i] != nullptr) != any_out)
+                return fail(COCODIFF_ERR_NULL, "qkv_proj_fused: a weight needs at least one of its two outputs, and outputs need their weight");
+            if (i < 2 && w3[i] && !fused->gamma[i]) return fail(COCODIFF_ERR_NULL, "qkv_proj_fused: gamma missing for a given Q or K");
+            if (!aligned16(fused->hs[i]) || (i < 2 && !aligned16(fused->gamma[i])))
+                return fail(COCODIFF_ERR_ALIGN, "qkv_proj_fused: pointers must be 16-byte aligned");
+        }
+        if (!wq && !wk && !wv) return fail(COCODIFF_ERR_NULL, "qkv_proj_fused: no weight given");
+    } else {
+        if ((wq == nullptr) != (q == nullptr) || (wk == nullptr) != (k == nullptr) || (wv == nullptr) != (v == nullptr))
+            return fail(COCODIFF_ERR_NULL, "qkv_proj: a weight and its output must be given together");
+        if (!q && !k && !v) return fail(COCODIFF_ERR_NULL, "qkv_proj: no (weight, output) pair given");
+    }
     if (!aligned16(x) || !aligned16(wq) || !aligned16(wk) || !aligned16(wv) || !aligned16(q) || !aligned16(k) || !aligned16(v))
         return fail(COCODIFF_ERR_ALIGN, "qkv_proj: pointers must be 16-byte aligned");
 
@@ -573,23 +744,35 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.n_tensors = 0;
     const cocodiff_bf16* ws[3] = {wv, wq, wk};   // V first: its tiles are dealt out before Q's and K's
     cocodiff_bf16* ys[3] = {v, q, k};
+    cocodiff_bf16* y2s[3] = {fused ? fused->hs[2] : nullptr, fused ? fused->hs[0] : nullptr, fused ? fused->hs[1] : nullptr};
+    const cocodiff_bf16* gs[3] = {nullptr, fused ? fused->gamma[0] : nullptr, fused ? fused->gamma[1] : nullptr};
     for (int i = 0; i < 3; ++i) {
         a.w[i] = nullptr;
         a.y[i] = nullptr;
+        a.y2[i] = nullptr;
+        a.gamma[i] = nullptr;
     }
     for (int i = 0; i < 3; ++i)
         if (ws[i]) {
             a.w[a.n_tensors] = ws[i];
             a.y[a.n_tensors] = ys[i];
+            a.y2[a.n_tensors] = y2s[i];
+            a.gamma[a.n_tensors] = gs[i];
             ++a.n_tensors;
         }
+    a.d = (uint32_t)shape->d;
+    a.inv_d = 1.0f / (float)shape->d;
+    a.eps = fused ? fused->eps : 0.f;
+    a.rope = fused ? fused->rope : RopeDev{};
     const int32_t Ns = shape->N / shape->P;
     a.row_begin = shape->rank_begin * Ns;
     a.M = shape->rank_count * Ns;
     a.D = shape->D;
     if ((int64_t)288 * a.D * 2 >= ((int64_t)1 << 32)) return fail(COCODIFF_ERR_SHAPE, "qkv_proj: D (%d) too large", a.D);
-    const LaunchPlan plan = plan_launch(a.M, a.D, a.n_tensors);
+    const LaunchPlan plan = plan_launch(a.M, a.D, a.n_tensors, layout == OUT_FUSED);
     if (!plan.pick) return fail(COCODIFF_ERR_HIP, "qkv_proj: cannot read the compute-unit count");
+    if (layout == OUT_FUSED && !plan.ring_kernel)
+        return fail(COCODIFF_ERR_SHAPE, "qkv_proj_fused: D (%d) must be a multiple of 64 and at least 192", a.D);
     const TileKernel* pick = plan.pick;
     const bool ring_kernel = plan.ring_kernel;
     a.bm = plan.bm;
@@ -601,11 +784,13 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     // dynamic LDS above 64 KB needs the attribute, once per process (thread-safe initialisation)
     static const hipError_t attr_rc = [] {
         hipError_t e = hipSuccess;
-        int n_shapes = 0;
-        const TileKernel* shapes = tile_shapes(&n_shapes);
-        for (int i = 0; i < n_shapes; ++i)
-            for (const void* k : shapes[i].entry)
-                if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, shapes[i].lds);
+        for (bool whole_heads : {false, true}) {
+            int n_shapes = 0;
+            const TileKernel* shapes = tile_shapes(whole_heads, &n_shapes);
+            for (int i = 0; i < n_shapes; ++i)
+                for (const void* k : shapes[i].entry)
+                    if (k && e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, shapes[i].lds);
+        }
         for (const void* k : {(const void*)qkv_gemm_staged_kernel<OUT_SEQ>, (const void*)qkv_gemm_staged_kernel<OUT_CHUNKS>,
                               (const void*)qkv_gemm_staged_kernel<OUT_HEADS>})
             if (e == hipSuccess) e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
@@ -615,8 +800,8 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     hipStream_t st = as_stream(stream);
     void* kernel_args[] = {&a};
     hipError_t le;
-    static const void* const staged[3] = {(const void*)qkv_gemm_staged_kernel<OUT_SEQ>, (const void*)qkv_gemm_staged_kernel<OUT_CHUNKS>,
-                                          (const void*)qkv_gemm_staged_kernel<OUT_HEADS>};
+    static const void* const staged[4] = {(const void*)qkv_gemm_staged_kernel<OUT_SEQ>, (const void*)qkv_gemm_staged_kernel<OUT_CHUNKS>,
+                                          (const void*)qkv_gemm_staged_kernel<OUT_HEADS>, nullptr};
     if (ring_kernel)
         le = hipLaunchKernel(pick->entry[layout], dim3(n_tiles), dim3(pick->threads), kernel_args, pick->lds, st);
     else
@@ -643,12 +828,35 @@ extern "C" int cocodiff_qkv_proj_hs(const cocodiff_shape* shape, const cocodiff_
     return proj_launch(shape, x, wq, wk, wv, q_hs, k_hs, v_hs, OUT_HEADS, COCODIFF_SEND_MAJOR, stream);
 }
 
-extern "C" int cocodiff_qkv_proj_plan(const cocodiff_shape* shape, int32_t n_tensors, int32_t* tile_tokens, int32_t* tile_features,
-                                      int32_t* n_tiles, int32_t* n_compute_units) {
+extern "C" int cocodiff_qkv_proj_fused(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                       const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                       const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps, const cocodiff_rope* rope,
+                                       cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, cocodiff_bf16* vbuf, int slot_order,
+                                       cocodiff_bf16* q_hs, cocodiff_bf16* k_hs, cocodiff_bf16* v_hs, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != COCODIFF_OK) return rc;
+    if (shape->d != 64 && shape->d != 128 && shape->d != 256)
+        return fail(COCODIFF_ERR_SHAPE, "qkv_proj_fused: d (%d) must be 64, 128 or 256 (a head row must fill whole wavefront tiles of 64 features)", shape->d);
+    FusedExtras f{};
+    f.hs[0] = q_hs;
+    f.hs[1] = k_hs;
+    f.hs[2] = v_hs;
+    f.gamma[0] = gamma_q;
+    f.gamma[1] = gamma_k;
+    f.eps = eps;
+    if (wq || wk) {
+        rc = fill_rope(shape, rope, "qkv_proj_fused", &f.rope);
+        if (rc != COCODIFF_OK) return rc;
+    }
+    return proj_launch(shape, x, wq, wk, wv, qbuf, kbuf, vbuf, OUT_FUSED, slot_order, stream, &f);
+}
+
+extern "C" int cocodiff_qkv_proj_plan(const cocodiff_shape* shape, int32_t n_tensors, int32_t whole_heads, int32_t* tile_tokens,
+                                      int32_t* tile_features, int32_t* n_tiles, int32_t* n_compute_units) {
     int rc = check_shape(shape);
     if (rc != COCODIFF_OK) return rc;
     if (n_tensors < 1 || n_tensors > 3) return fail(COCODIFF_ERR_SHAPE, "qkv_proj_plan: n_tensors (%d) must be 1, 2 or 3", n_tensors);
-    const LaunchPlan p = plan_launch(shape->rank_count * (shape->N / shape->P), shape->D, n_tensors);
+    const LaunchPlan p = plan_launch(shape->rank_count * (shape->N / shape->P), shape->D, n_tensors, whole_heads != 0);
     if (!p.pick) return fail(COCODIFF_ERR_HIP, "qkv_proj_plan: cannot read the compute-unit count");
     if (tile_tokens) *tile_tokens = p.bm;
     if (tile_features) *tile_features = p.bn;

@@ -22,6 +22,19 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Check the launch that was just issued.
 int check_launch(const char* what);
 
+// The rotary description as the kernels take it: per-axis float offsets into the cos/sin table.
+struct RopeDev {
+    int32_t n_axes;
+    int32_t grid[3];
+    int32_t pairs[3];
+    int32_t offset[3];   // float offset of each axis' [grid][pairs][2] table
+    const float* cs;
+};
+
+// Rules of cocodiff_rope against `shape` (table present and aligned, 1..3 axes, grid cells == N, pairs == d/2);
+// fills `out` or records the violated rule under the caller's name `who`.
+int fill_rope(const cocodiff_shape* shape, const cocodiff_rope* rope, const char* who, RopeDev* out);
+
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 // Cache policy of the HBM-bound kernels, from measurements on data that is not in the 256 MB last-level cache

@@ -13,14 +13,6 @@
 
 namespace cocodiff {
 
-struct RopeDev {
-    int32_t n_axes;
-    int32_t grid[3];
-    int32_t pairs[3];
-    int32_t offset[3];   // float offset of each axis' [grid][pairs][2] table
-    const float* cs;
-};
-
 struct NormRopeArgs {
     uint16_t* tensor[2];
     uint16_t* packed[2];              // PACK: the exchange buffers the result goes to (tensor[] is then read only)
@@ -214,11 +206,7 @@ __global__ void __launch_bounds__(256) unpack_norm_rope_kernel(UnpackNormArgs a)
     }
 }
 
-}  // namespace cocodiff
-
-using namespace cocodiff;
-
-static int fill_rope(const cocodiff_shape* shape, const cocodiff_rope* rope, const char* who, RopeDev* out) {
+int fill_rope(const cocodiff_shape* shape, const cocodiff_rope* rope, const char* who, RopeDev* out) {
     if (!rope || !rope->cs) return fail(COCODIFF_ERR_NULL, "%s: rope description or its table is NULL", who);
     if (!aligned16(rope->cs)) return fail(COCODIFF_ERR_ALIGN, "%s: the rope table must be 16-byte aligned", who);
     if (rope->n_axes < 1 || rope->n_axes > 3) return fail(COCODIFF_ERR_SHAPE, "%s: rope n_axes (%d) must be 1..3", who, rope->n_axes);
@@ -242,6 +230,10 @@ static int fill_rope(const cocodiff_shape* shape, const cocodiff_rope* rope, con
     out->cs = rope->cs;
     return COCODIFF_OK;
 }
+
+}  // namespace cocodiff
+
+using namespace cocodiff;
 
 extern "C" int cocodiff_a2a_unpack_norm_rope(const cocodiff_shape* shape, const cocodiff_bf16* qbuf, const cocodiff_bf16* kbuf,
                                              cocodiff_bf16* q_hs, cocodiff_bf16* k_hs,
@@ -304,24 +296,16 @@ static int norm_rope_launch(const cocodiff_shape* shape, cocodiff_bf16* q, cocod
     }
     if (!q && !k) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: q and k are both NULL");
     if ((q && !gamma_q) || (k && !gamma_k)) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: gamma missing for a given tensor");
-    if (!rope || !rope->cs) return fail(COCODIFF_ERR_NULL, "qk_norm_rope: rope description or its table is NULL");
-    if (!aligned16(q) || !aligned16(k) || !aligned16(gamma_q) || !aligned16(gamma_k) || !aligned16(rope->cs))
+    if (!aligned16(q) || !aligned16(k) || !aligned16(gamma_q) || !aligned16(gamma_k))
         return fail(COCODIFF_ERR_ALIGN, "qk_norm_rope: pointers must be 16-byte aligned");
     const uint32_t d8 = shape->d / 8, D8 = shape->D / 8;
     if ((d8 & (d8 - 1)) || d8 > 64)
         return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: d (%d) must be 8 times a power of two, at most 512", shape->d);
     if (!(D8 % 64 == 0 || 64 % D8 == 0))
         return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: D/8 (%u) must divide 64 or be a multiple of 64", D8);
-    if (rope->n_axes < 1 || rope->n_axes > 3) return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: rope n_axes (%d) must be 1..3", rope->n_axes);
-    int64_t cells = 1, npairs = 0;
-    for (int ax = 0; ax < rope->n_axes; ++ax) {
-        if (rope->grid[ax] <= 0 || rope->pairs[ax] <= 0)
-            return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: rope axis %d needs positive grid and pairs", ax);
-        cells *= rope->grid[ax];
-        npairs += rope->pairs[ax];
-    }
-    if (cells != shape->N) return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: grid has %lld cells, N is %d", (long long)cells, shape->N);
-    if (npairs * 2 != shape->d) return fail(COCODIFF_ERR_SHAPE, "qk_norm_rope: rope pairs sum to %lld, d/2 is %d", (long long)npairs, shape->d / 2);
+    RopeDev rope_dev;
+    rc = fill_rope(shape, rope, "qk_norm_rope", &rope_dev);
+    if (rc != COCODIFF_OK) return rc;
 
     NormRopeArgs a;
     int nt = 0;
@@ -341,15 +325,7 @@ static int norm_rope_launch(const cocodiff_shape* shape, cocodiff_bf16* q, cocod
     a.steps = D8 >= 64 ? D8 / 64 : 1;
     a.inv_d = 1.0f / (float)shape->d;
     a.eps = eps;
-    a.rope.n_axes = rope->n_axes;
-    int32_t off = 0;
-    for (int ax = 0; ax < 3; ++ax) {
-        a.rope.grid[ax] = ax < rope->n_axes ? rope->grid[ax] : 1;
-        a.rope.pairs[ax] = ax < rope->n_axes ? rope->pairs[ax] : 0;
-        a.rope.offset[ax] = off;
-        if (ax < rope->n_axes) off += rope->grid[ax] * rope->pairs[ax] * 2;
-    }
-    a.rope.cs = rope->cs;
+    a.rope = rope_dev;
 
     const uint32_t tokens_per_wave = D8 >= 64 ? 1 : 64 / D8;
     const uint32_t runs = (a.n_tokens + tokens_per_wave - 1) / tokens_per_wave;

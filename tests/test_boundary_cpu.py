@@ -170,6 +170,32 @@ def test_fused_entry_points_check_arguments_before_any_launch():
     assert h(ctypes.byref(s), fake, None, fake, None, fake, None, 1e-6, ctypes.byref(wrong), 0, None) == B.ERR_SHAPE
 
 
+def test_fused_projection_argument_errors():
+    """cocodiff_qkv_proj_fused: every rule is checked on the host before anything is enqueued (no GPU needed up to the
+    launch plan, which is the last step)."""
+    L = B.lib()
+    fake, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    f = L.cocodiff_qkv_proj_fused
+    s = cd.Shape.make(256, 256, 4, 64, 2)
+    rope = cd.Rope.make((16, 16), (16, 16), 10000.0, 0x1000)
+    r = ctypes.byref(rope)
+    # a head size the wavefront tiles cannot hold whole
+    s40 = cd.Shape.make(256, 320, 8, 40, 2)
+    assert f(ctypes.byref(s40), fake, fake, None, None, fake, None, 1e-6, r, fake, None, None, 0, None, None, None, None) == B.ERR_SHAPE
+    assert b"64, 128 or 256" in L.cocodiff_last_error()
+    # no weight; weight without destination; destination without weight; gamma missing; rope missing
+    assert f(ctypes.byref(s), fake, None, None, None, None, None, 1e-6, r, None, None, None, 0, None, None, None, None) == B.ERR_NULL
+    assert f(ctypes.byref(s), fake, fake, None, None, fake, None, 1e-6, r, None, None, None, 0, None, None, None, None) == B.ERR_NULL
+    assert f(ctypes.byref(s), fake, None, None, None, None, None, 1e-6, r, None, None, fake, 0, None, None, None, None) == B.ERR_NULL
+    assert f(ctypes.byref(s), fake, fake, None, None, None, None, 1e-6, r, fake, None, None, 0, None, None, None, None) == B.ERR_NULL
+    assert f(ctypes.byref(s), fake, fake, None, None, fake, None, 1e-6, None, fake, None, None, 0, None, None, None, None) == B.ERR_NULL
+    # alignment, slot order, rope that does not cover N
+    assert f(ctypes.byref(s), fake, fake, None, None, fake, None, 1e-6, r, None, None, None, 0, odd, None, None, None) == B.ERR_ALIGN
+    assert f(ctypes.byref(s), fake, fake, None, None, fake, None, 1e-6, r, fake, None, None, 7, None, None, None, None) == B.ERR_SHAPE
+    wrong = cd.Rope.make((16, 8), (16, 16), 10000.0, 0x1000)
+    assert f(ctypes.byref(s), fake, fake, None, None, fake, None, 1e-6, ctypes.byref(wrong), fake, None, None, 0, None, None, None, None) == B.ERR_SHAPE
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     """No fallback: without the built HIP library the binding raises instead of computing anything elsewhere."""
     monkeypatch.setattr(B, "_lib", None)

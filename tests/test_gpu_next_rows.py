@@ -349,6 +349,139 @@ def test_proj_hs_off_grid_shapes_and_bounds(oracle):
         assert_float_parity(to_host_bits(seq)[ids], oracle.qkv_proj(x[ids], w), f"proj {N}x{D}")
 
 
+# ---------------------------------------------------------------------------
+# the sender's whole share in the projection kernel: norm + RoPE on the accumulators, both destinations
+# ---------------------------------------------------------------------------
+
+def _fused_case(oracle, N, D, H, d, P, grid, pairs, inp, ids, rank=None, what=""):
+    """Runs cocodiff_qkv_proj_fused (Q, K, V in one launch, both destinations) and checks: V bit-identical to the plain
+    projection; both destinations of every tensor hold the same bits; Q and K against the fp64 chain
+    projection -> RMSNorm -> RoPE within the float tolerance (one rounding: the tolerance of a single stage holds end to
+    end), and close to the twice-rounded stand-alone chain."""
+    import torch
+    from parity_util import widen_bits
+    sh = cd.Shape.make(N, D, H, d, P) if rank is None else cd.Shape.make(N, D, H, d, P, rank, 1)
+    full = cd.Shape.make(N, D, H, d, P)
+    table = torch.from_numpy(cd.rope_table(grid, pairs, 10000.0)).to("cuda:0")
+    rope = cd.Rope.make(grid, pairs, 10000.0, table.data_ptr())
+    X, Wq, Wk, Wv = (to_dev(inp[k_]) for k_ in ("X", "Wq", "Wk", "Wv"))
+    gq, gk = to_dev(inp["gamma_q"]), to_dev(inp["gamma_k"])
+    eps = 1e-6
+    bufs = [dev_empty((N * D,)) for _ in range(3)]
+    hss = [dev_empty((H, N, d)) for _ in range(3)]
+    for t in bufs + hss:
+        t.fill_(-1)
+    cd.qkv_proj_fused(sh, X, Wq, Wk, Wv, gq, gk, eps, rope, bufs[0], bufs[1], bufs[2], cd.RECV_MAJOR, hss[0], hss[1], hss[2])
+    # the stand-alone chain on the same rank range
+    q, k, v = (dev_empty((N, D)) for _ in range(3))
+    for t in (q, k, v):
+        t.fill_(-1)
+    cd.qkv_proj(sh, X, Wq, Wk, Wv, q, k, v)
+    _sync()
+    v_plain = to_host_bits(v).copy()
+    have_chain = True
+    try:
+        cd.qk_norm_rope(sh, q, k, gq, gk, eps, rope)
+    except cd.CocodiffError:          # the stand-alone kernel takes fewer shapes (D/8 must divide or be a multiple of 64)
+        have_chain = False
+    _sync()
+    rows = slice(0, N) if rank is None else slice(rank * (N // P), (rank + 1) * (N // P))
+    for name, buf, hs, seq in (("Q", bufs[0], hss[0], q), ("K", bufs[1], hss[1], k), ("V", bufs[2], hss[2], v)):
+        got_hs = to_host_bits(hs)                                     # [H][N][d]
+        # destination 2 == unpack(destination 1), and nothing outside the rank range was written
+        un = dev_empty((H, N, d))
+        un.fill_(-1)
+        cd.a2a_unpack(full, buf, un, cd.RECV_MAJOR)
+        _sync()
+        un_h = to_host_bits(un)
+        assert np.array_equal(un_h[:, rows], got_hs[:, rows]), f"{what} {name}: the two destinations differ"
+        if rank is not None:
+            outside = np.ones(N, dtype=bool)
+            outside[rows] = False
+            assert np.all(got_hs[:, outside] == 0xFFFF), f"{what} {name}: rows outside the rank range were written"
+        got_seq = got_hs.transpose(1, 0, 2).reshape(N, D)
+        chain = to_host_bits(seq)
+        if name == "V":
+            assert np.array_equal(got_seq[rows], v_plain[rows]), f"{what}: V differs from the plain projection"
+            continue
+        # against the oracle chain (fp64, nothing rounded)
+        wname, gname = ("Wq", "gamma_q") if name == "Q" else ("Wk", "gamma_k")
+        o = oracle.rope_rotate(oracle.rms_norm(oracle.qkv_proj(inp["X"][ids], inp[wname]).reshape(len(ids), H, d),
+                                               oracle.widen(inp[gname]), eps), ids, grid, pairs, 10000.0).reshape(len(ids), D)
+        e = assert_float_parity(got_seq[ids], o, f"{what} fused {name} against the oracle chain")
+        print(f"  {what} fused {name}: {len(ids)} tokens, abs {e[0]:.3g} rel {e[1]:.3g}", flush=True)
+        # against the twice-rounded stand-alone chain: apart by what that chain's extra rounding of the projection can
+        # move a normalised, rotated element (2^-8 sqrt(2) of its rotary pair's norm) plus the two final roundings
+        if not have_chain:
+            continue
+        a_, b_ = widen_bits(got_seq[rows]), widen_bits(chain[rows])
+        pair = np.repeat(np.sqrt(b_[:, 0::2] ** 2 + b_[:, 1::2] ** 2), 2, axis=1)
+        bound = 2.0 ** -8 * np.sqrt(2.0) * pair + 2.0 ** -8 * np.abs(b_) + 1e-3
+        assert np.all(np.abs(a_ - b_) <= bound), f"{what} {name}: too far from the stand-alone chain"
+
+
+@gpu
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_proj_fused_matches_the_chain_oracle(oracle, name):
+    from synth import make_layer_inputs, sample_token_ids
+    cfg = CONFIGS[name]
+    print(f"proj_fused {name}: plan {cd.qkv_proj_plan(cd.Shape.make(cfg.N, cfg.D, cfg.H, cfg.d, cfg.P), 3, True)}", flush=True)
+    inp = make_layer_inputs(cfg)
+    ids = np.arange(cfg.N) if name in ("C1", "C2", "C3") else sample_token_ids(cfg, random_tiles_per_rank=(4 if name == "C4" else 1))
+    _fused_case(oracle, cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, cfg.grid, cfg.pairs, inp, ids, what=name)
+
+
+@gpu
+@pytest.mark.parametrize("N,H,d,P,grid,pairs,rank", [
+    (272, 4, 64, 1, (17, 16), (16, 16), None),          # a head per wavefront; ragged token tile
+    (528, 3, 256, 1, (22, 24), (64, 64), None),         # a head across four wavefronts; D = 768: three tiles of 256
+    (96, 5, 64, 1, (2, 4, 12), (10, 11, 11), None),     # three axes, pair split off the 2-pair grid; D = 320: ragged feature tile
+    (512, 4, 128, 4, (16, 32), (40, 24), 2),            # one rank of four
+])
+def test_proj_fused_other_shapes(oracle, N, H, d, P, grid, pairs, rank):
+    from synth import f32_to_bf16_bits
+    D = H * d
+    rng = np.random.default_rng(N + d)
+    inp = {"X": f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32))}
+    for w in ("Wq", "Wk", "Wv"):
+        inp[w] = f32_to_bf16_bits(rng.standard_normal((D, D), dtype=np.float32) * np.float32(D ** -0.5))
+    for g_ in ("gamma_q", "gamma_k"):
+        inp[g_] = f32_to_bf16_bits((1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32))
+    ids = np.arange(N) if rank is None else np.arange(rank * (N // P), (rank + 1) * (N // P))
+    _fused_case(oracle, N, D, H, d, P, grid, pairs, inp, ids, rank=rank, what=f"{N}x{D}")
+
+
+@gpu
+def test_proj_fused_single_destinations_and_subsets(oracle):
+    """Either destination alone, and Q alone: the same bits as the call with everything."""
+    import torch
+    from synth import make_layer_inputs
+    cfg = CONFIGS["C2"]
+    N, D, H, d, P = cfg.N, cfg.D, cfg.H, cfg.d, cfg.P
+    inp = make_layer_inputs(cfg)
+    sh = cd.Shape.make(N, D, H, d, P)
+    table = torch.from_numpy(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta)).to("cuda:0")
+    rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, table.data_ptr())
+    X, Wq, Wk, Wv = (to_dev(inp[k_]) for k_ in ("X", "Wq", "Wk", "Wv"))
+    gq, gk = to_dev(inp["gamma_q"]), to_dev(inp["gamma_k"])
+    ref_b = [dev_empty((N * D,)) for _ in range(3)]
+    ref_h = [dev_empty((H, N, d)) for _ in range(3)]
+    cd.qkv_proj_fused(sh, X, Wq, Wk, Wv, gq, gk, cfg.eps, rope, ref_b[0], ref_b[1], ref_b[2], cd.SEND_MAJOR, ref_h[0], ref_h[1], ref_h[2])
+    b_only = [dev_empty((N * D,)) for _ in range(3)]
+    h_only = [dev_empty((H, N, d)) for _ in range(3)]
+    cd.qkv_proj_fused(sh, X, Wq, Wk, Wv, gq, gk, cfg.eps, rope, b_only[0], b_only[1], b_only[2], cd.SEND_MAJOR, None, None, None)
+    cd.qkv_proj_fused(sh, X, None, None, Wv, None, None, cfg.eps, None, None, None, None, cd.SEND_MAJOR, None, None, h_only[2])   # V needs no rope
+    cd.qkv_proj_fused(sh, X, Wq, None, None, gq, None, cfg.eps, rope, None, None, None, cd.SEND_MAJOR, h_only[0], None, None)
+    cd.qkv_proj_fused(sh, X, None, Wk, None, None, gk, cfg.eps, rope, None, None, None, cd.SEND_MAJOR, None, h_only[1], None)
+    _sync()
+    for i in range(3):
+        assert torch.equal(b_only[i], ref_b[i]) and torch.equal(h_only[i], ref_h[i]), i
+    with pytest.raises(cd.CocodiffError):          # a weight without any destination
+        cd.qkv_proj_fused(sh, X, Wq, None, None, gq, None, cfg.eps, rope, None, None, None, cd.SEND_MAJOR, None, None, None)
+    with pytest.raises(cd.CocodiffError):          # Q without its gamma
+        cd.qkv_proj_fused(sh, X, Wq, None, None, None, None, cfg.eps, rope, ref_b[0], None, None, cd.SEND_MAJOR, None, None, None)
+
+
 @gpu
 @pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C4", 0), ("C5", 1)])
 def test_norm_rope_pack_equals_norm_rope_then_pack(oracle, name, order):
