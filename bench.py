@@ -13,9 +13,10 @@ head-parallel Q (normalised, rotated), K (same) and V, and the selection's flags
   fused1qkv  one stream:  qkv_proj_pack(V, Q, K in one launch, V's tiles first) -> a2a_unpack_select -> a2a_unpack_norm_rope
   fused2     two streams: main qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K);
                           side [after V's projection] a2a_unpack_select(V); joined at the end of the step
+  fused3     three streams: V, Q, K projected by three launches of qkv_proj_pack, each tensor's unpack under the next projection
 (in fused0 / fused0v the exchange buffers of Q and K carry normalised values -- norm + RoPE on the sending side, the paper's
 order -- in the others the projection itself, normalised by the receiver's unpack).
-The default run times all five with the same --warmup / --steps (three times each, interleaved, after a clock
+The default run times all six with the same --warmup / --steps (three times each, interleaved, after a clock
 ramp: see time_headline) and reports each; `value` is the fastest one measured in this run (named in config.schedule).  Also timed and reported beside it: the same step through the five
 stand-alone calls only ("vfirst", two streams; "serial", one), the single-GPU direct form that writes V straight
 into the head-parallel layout ("fused1_vdirect": no exchange buffer for V), a HIP-graph replay of the headline
@@ -39,7 +40,7 @@ METRIC = "tokens/s per layer (QKV+norm+RoPE+pack); pack/select GB/s vs HBM peak"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "qkv_gemm_hbm_traffic.txt")
-HEADLINE_CANDIDATES = ("fused0", "fused0v", "fused1", "fused1qkv", "fused2")
+HEADLINE_CANDIDATES = ("fused0", "fused0v", "fused1", "fused1qkv", "fused2", "fused3")
 
 
 def measured_traffic(workload: str, kernel_tile: str, launches_per_step: int):
