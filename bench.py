@@ -475,8 +475,8 @@ def main() -> int:
     ap.add_argument("--no-other-workloads", action="store_true")
     ap.add_argument("--profile-projection", type=int, default=0, metavar="N",
                     help="profiling aid for rocprofv3 counter runs: N launches each of the projection with one, two and three "
-                         "weights (exchange-buffer epilogue), of the fused form with three weights and of a 1000 MiB calibration "
-                         "copy, and nothing else")
+                         "weights (exchange-buffer epilogue), of the fused form with three weights, of a2a_unpack_select and "
+                         "vmajor_select, and of a 1000 MiB calibration copy, and nothing else")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs all P logical ranks of the path on ONE GPU; "
@@ -513,6 +513,8 @@ def main() -> int:
             cd.qkv_proj_pack(w.sh, w.X, w.Wq, w.Wk, None, w.bq, w.bk, None, w.ORDER)
             cd.qkv_proj_pack(w.sh, w.X, w.Wq, w.Wk, w.Wv, w.bq, w.bk, w.bv, w.ORDER)
             cd.qkv_proj_fused(w.sh, w.X, w.Wq, w.Wk, w.Wv, w.gq, w.gk, cfg.eps, w.rope, w.bq, w.bk, w.bv, w.ORDER, w.hq, w.hk, w.hv)
+            w.unpack_select(None)
+            w.select(None)
             cd.util_copy(src_big, dst_big, big)
         torch.cuda.synchronize()
         sampler.stop()

@@ -208,6 +208,48 @@ def test_select_edge_cases(oracle):
     assert n == 9 and np.array_equal(idx[:n], changed)
 
 
+def test_select_unusual_thresholds(oracle):
+    """tau = 0, a negative tau, an infinite tau and a NaN tau: the same answers as the definition
+    NOT(|cur - prev| <= tau) gives on the CPU (every tile with a difference / every tile / none / every tile)."""
+    rng = np.random.default_rng(81)
+    S, N, W, T = 2, 640, 64, 16
+    NT = N // T
+    cur = f32_to_bf16_bits(rng.standard_normal((S, N, W)).astype(np.float32))
+    prev, changed = perturb_tiles(cur, 1, T, 6, rng)
+    assert np.array_equal(_check_select(oracle, cur, prev, 0.0, T)[0], changed)
+    assert _check_select(oracle, cur, prev, -1.0, T)[1] == NT
+    assert _check_select(oracle, cur, prev, float("inf"), T)[1] == 0
+    assert _check_select(oracle, cur, prev, float("nan"), T)[1] == NT
+    # denormal differences against tau = 0 and against the smallest normal number
+    tiny = np.zeros((S, N, W), dtype=np.uint16)
+    tiny_prev = tiny.copy()
+    tiny_prev[1, 16 * 7 + 3, 5] = 0x0001                     # the smallest bf16 denormal, 2^-133
+    assert _check_select(oracle, tiny, tiny_prev, 0.0, T)[0].tolist() == [7]
+    assert _check_select(oracle, tiny, tiny_prev, 2.0 ** -126, T)[1] == 0
+
+
+def test_select_static_and_workspace_forms_agree_at_full_size(oracle):
+    """The largest workload through both forms of the selection (caller workspace / library-owned flag words)."""
+    import torch
+    cfg = CONFIGS["C5"]
+    cur, prev, changed = make_v_pair(cfg, layout="hs")
+    S, N, W, T, NT = cfg.H, cfg.N, cfg.d, cfg.tile_tokens, cfg.NT
+    cur_d, prev_d = to_dev(cur), to_dev(prev)
+    res = []
+    for static in (False, True):
+        idx, n_act = dev_empty((NT,), "i32"), dev_empty((1,), "i32")
+        idx.fill_(-1)
+        if static:
+            cd.vmajor_select_static(S, N, W, T, cur_d, prev_d, cfg.tau, None, idx, n_act, None, 0)
+        else:
+            ws = torch.empty(cd.vmajor_select_workspace_bytes(S, N, W, T), dtype=torch.uint8, device="cuda:0")
+            cd.vmajor_select(S, N, W, T, cur_d, prev_d, cfg.tau, None, idx, n_act, None, 0, ws)
+        _sync()
+        res.append((int(n_act.cpu()[0]), idx.cpu().numpy()))
+    assert res[0][0] == res[1][0] == cfg.n_changed
+    assert np.array_equal(res[0][1], res[1][1]) and np.array_equal(res[0][1][:cfg.n_changed], changed)
+
+
 def test_select_more_than_one_scan_round(oracle):
     # 2500 tiles: the scan workgroup walks them 1024 at a time
     rng = np.random.default_rng(78)
