@@ -43,18 +43,18 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "qkv_gemm_hbm_traffic.txt")
 HEADLINE_CANDIDATES = ("fused0", "fused0v", "fused1", "fused1qkv", "fused2", "fused3")
 
 
-def measured_traffic(workload: str, kernel_tile: str, launches_per_step: int):
+def measured_traffic(workload: str, form: str, kernel_tile: str, launches_per_step: int):
     """Bytes per launch that crossed the L2 <-> memory-fabric boundary for the projection kernel, from the
     committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs of this script's --profile-projection mode);
-    None if the summary has no line for this workload, this tile shape and this number of launches per step (a
-    summary of another kernel form does not count)."""
+    None if the summary has no line for this workload, this kernel form ("plain" / "fused"), this tile shape and
+    this number of launches per step (a summary of another kernel form does not count)."""
     try:
         with open(TRAFFIC_FILE) as f:
             for line in f:
                 parts = line.split()
-                if (len(parts) >= 5 and parts[0] == "traffic_bytes_per_launch" and parts[1] == workload and parts[2] == kernel_tile
-                        and parts[3] == str(launches_per_step)):
-                    return int(parts[4])
+                if (len(parts) >= 6 and parts[0] == "traffic_bytes_per_launch" and parts[1] == workload and parts[2] == form
+                        and parts[3] == kernel_tile and parts[4] == str(launches_per_step)):
+                    return int(parts[5])
     except OSError:
         pass
     return None
@@ -180,15 +180,26 @@ class Workload:
 
     # -- helpers ---------------------------------------------------------------------------------------------
     def proj(self, rec, stream, call):
-        """One projection launch; with a recorder, bracketed by HIP events on the launch stream."""
+        """One projection launch.  With a recorder: a timing event on the launch stream before the step's first
+        projection launch and one after its last (none between the launches: an event between two kernels costs the
+        step about a percent, and a schedule with a kernel on a second stream more)."""
         if rec is None:
             call(stream)
             return
-        e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
+        if rec.launches_per_step is None:          # counting pass
+            rec.count += 1
+            call(stream)
+            return
+        k = rec.count % rec.launches_per_step
+        if k == 0:
+            rec.begin = self.torch.cuda.Event(enable_timing=True)
+            rec.begin.record(stream)
         call(stream)
-        e1.record(stream)
-        rec.append((e0, e1))
+        if k == rec.launches_per_step - 1:
+            end = self.torch.cuda.Event(enable_timing=True)
+            end.record(stream)
+            rec.spans.append((rec.begin, end))
+        rec.count += 1
 
     def fork(self, src, dst):
         ev = self.torch.cuda.Event()
@@ -370,21 +381,33 @@ class Workload:
         return (t1 - t0) * 1e3 / steps, (t0, t1)
 
     def projection_in_step(self, step_fn, steps):
-        """A pass of its own (outside every headline timing): `steps` steps with every projection launch bracketed by
-        HIP events on its launch stream.  Returns (average launch duration in us, launches per step, ms per step of
-        this instrumented pass)."""
+        """A pass of its own (outside every headline timing): `steps` steps with two HIP events each, one before the
+        step's first projection launch and one after its last, each on its launch stream.  Returns (average launch
+        duration in us = span / launches, launches per step, ms per step of this instrumented pass).  When a step's
+        projections sit on one stream back to back (every schedule but fused3 / fused3s / vfirst3) the span holds nothing
+        but them."""
         torch = self.torch
+
+        class Rec:
+            launches_per_step = None
+            count = 0
+            begin = None
+            spans = []
+
+        rec = Rec()
+        rec.spans = []
+        step_fn(rec)                               # counts the projection launches of a step
+        rec.launches_per_step, rec.count = rec.count, 0
         for _ in range(3):
             step_fn()
         torch.cuda.synchronize()
-        rec = []
         t0 = time.perf_counter()
         for _ in range(steps):
             step_fn(rec)
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / steps
-        total_us = sum(e0.elapsed_time(e1) for e0, e1 in rec) * 1e3
-        return total_us / len(rec), len(rec) / steps, ms
+        total_us = sum(e0.elapsed_time(e1) for e0, e1 in rec.spans) * 1e3
+        return total_us / (len(rec.spans) * rec.launches_per_step), float(rec.launches_per_step), ms
 
     def tile_name(self, n_tensors, whole_heads=False):
         p = self.cd.qkv_proj_plan(self.sh, n_tensors, whole_heads)
@@ -458,7 +481,7 @@ def roofline_of(w, schedule, steps):
     fused = schedule.startswith("fused0")
     tile = w.tile_name(3 if per_step == 1 else 2, fused)
     return {"kernel": "qkv_gemm_direct_kernel" + (" (norm + RoPE epilogue, two destinations)" if fused else ""), "tile": tile, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(cfg.name, tile, int(round(per_step))),
+            "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(cfg.name, "fused" if fused else "plain", tile, int(round(per_step))),
             "avg_launch_us": round(us, 2), "launches_per_step": round(per_step, 2), "event_steps": steps,
             "ms_per_step_instrumented": round(ms_instr, 4)}
 
