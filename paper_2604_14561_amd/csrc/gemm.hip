@@ -55,6 +55,13 @@ struct GemmArgs {
     uint32_t d;                // features per head
     float inv_d, eps;
     RopeDev rope;
+    // How the normalising epilogue walks the rotation table, in floats: axis x' rows start at row_base[x], row_stride[x]
+    // apart, row_span[x] = grid x stride in all, up to row_end[x] (absent axes: never reached); row_step16[x] = the axis' digit of 16 tokens in the grid's mixed radix
+    // (last axis fastest) times the stride.  tab_lds != 0: every workgroup that normalises stages the table in LDS, rows
+    // 2 pairs + 2 floats apart (the two extra floats spread consecutive rows over the banks), and the four arrays describe
+    // that copy; axis x is pairs [tab_cum[x], ...) of the caller's table and tab_magic[x] = ceil(2^32 / pairs[x])
+    // divides a pair index by the row length.  tab_lds == 0: the arrays describe the caller's table in global memory.
+    uint32_t tab_lds, row_base[3], row_stride[3], row_span[3], row_end[3], row_step16[3], tab_cum[3], tab_magic[3];
 };
 
 // Where the epilogue writes: token-major [N][D]; the exchange-buffer chunks of the first all-to-all; or the
@@ -128,36 +135,63 @@ struct EpilogueRows {
 };
 
 // Second half of the epilogue: the wavefront reads back the rows it staged (a wavefront's LDS accesses complete in
-// order: no workgroup barrier is needed) and writes them out.
+// order: no workgroup barrier is needed) and writes them out, RPI rows per instruction.  A lane keeps its 16-byte
+// feature column and walks down the rows, so every destination address is formed once (the divisions below) and then
+// stepped: the epilogue's time is its instruction count, not the stores' bandwidth.
 // OUT_CHUNKS: the 8 features a lane writes for token n = r*Ns + m go to chunk (sender r, receiver p = feature / (Hp*d))
-// of the exchange buffer Y, row m (Hp*d is a multiple of 8, so a 16-byte vector never straddles two chunks).
+// of the exchange buffer Y, row m (Hp*d is a multiple of 8, so a 16-byte vector never straddles two chunks); RPI rows
+// further down is RPI chunk rows further, and into sender r+1's chunk where m passes Ns (Ns >= 16 >= RPI: once at most).
 // OUT_HEADS: they go to row n of head feature / d of Y = [H][N][d] (d is a multiple of 8).
 template <uint32_t COLS, uint32_t ROWS, int LAYOUT>
 __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lane, uint16_t* __restrict__ Y, uint16_t* __restrict__ Y2,
                                            size_t row0, uint32_t tok0, uint32_t feat0, uint32_t M, uint32_t D, const GemmArgs& a) {
     constexpr uint32_t CP = EpilogueRows<COLS>::CP, ROWB = EpilogueRows<COLS>::ROWB;
     constexpr uint32_t RPI = 64 / CP;            // rows per read instruction
+    static_assert(RPI <= 16 && ROWS % RPI == 0, "a lane moves at most one sender's chunk further per step");
     const uint32_t c16 = lane % CP, rsub = lane / CP;
+    const uint32_t feat = feat0 + c16 * 8u;
+    if (c16 >= COLS || feat >= D) return;
+    const bool to_chunks = LAYOUT == OUT_CHUNKS || (LAYOUT == OUT_FUSED && Y);
+    const bool to_heads = LAYOUT == OUT_HEADS || (LAYOUT == OUT_FUSED && Y2);
+    uint32_t tok = tok0 + rsub;
+    const uint32_t n = (uint32_t)row0 + tok, v8 = feat >> 3;
+    vec16* yc = nullptr;       // exchange buffer
+    vec16* yh = nullptr;       // head-parallel tensor, or the token-major one
+    uint32_t m = 0;
+    size_t step_c = 0, wrap_c = 0, step_h = 0;
+    if (to_chunks) {
+        const uint32_t r = n / a.Ns, p = v8 / a.row8, c = v8 - p * a.row8;
+        m = n - r * a.Ns;
+        const size_t slot = a.recv_major ? (size_t)p * a.P + r : (size_t)r * a.P + p;
+        yc = reinterpret_cast<vec16*>(Y) + slot * a.chunk8 + (size_t)m * a.row8 + c;
+        step_c = (size_t)RPI * a.row8;
+        wrap_c = a.recv_major ? 0 : (size_t)(a.P - 1u) * a.chunk8;      // slot(r + 1) - slot(r) chunks, less the Ns rows stepped over
+    }
+    if (to_heads) {
+        const uint32_t h = v8 / a.d8, c = v8 - h * a.d8;
+        yh = reinterpret_cast<vec16*>(LAYOUT == OUT_HEADS ? Y : Y2) + ((size_t)h * a.N_all + n) * a.d8 + c;
+        step_h = (size_t)RPI * a.d8;
+    }
+    if (LAYOUT == OUT_SEQ) {
+        yh = reinterpret_cast<vec16*>(Y + (row0 + tok) * D + feat);
+        step_h = (size_t)RPI * (D / 8u);
+    }
 #pragma unroll 8
     for (uint32_t it = 0; it < ROWS / RPI; ++it) {
-        const uint32_t row = RPI * it + rsub;
-        const uint32_t tok = tok0 + row;
-        const uint32_t feat = feat0 + c16 * 8u;
-        if (c16 < COLS && tok < M && feat < D) {
+        if (tok < M) {
+            const uint32_t row = RPI * it + rsub;
             const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & (CP - 1u))) << 4));
-            if (LAYOUT == OUT_CHUNKS || (LAYOUT == OUT_FUSED && Y)) {
-                const uint32_t n = (uint32_t)row0 + tok, r = n / a.Ns, m = n - r * a.Ns;
-                const uint32_t v8 = feat >> 3, p = v8 / a.row8, c = v8 - p * a.row8;
-                const size_t slot = a.recv_major ? (size_t)p * a.P + r : (size_t)r * a.P + p;
-                reinterpret_cast<vec16*>(Y)[slot * a.chunk8 + (size_t)m * a.row8 + c] = v;
-            }
-            if (LAYOUT == OUT_HEADS || (LAYOUT == OUT_FUSED && Y2)) {
-                const uint32_t n = (uint32_t)row0 + tok;
-                const uint32_t v8 = feat >> 3, h = v8 / a.d8, c = v8 - h * a.d8;
-                reinterpret_cast<vec16*>(LAYOUT == OUT_HEADS ? Y : Y2)[((size_t)h * a.N_all + n) * a.d8 + c] = v;
-            }
-            if (LAYOUT == OUT_SEQ) {
-                *reinterpret_cast<vec16*>(Y + (row0 + tok) * D + feat) = v;
+            if (to_chunks) *yc = v;
+            if (to_heads || LAYOUT == OUT_SEQ) *yh = v;
+        }
+        tok += RPI;
+        yh += step_h;
+        if (to_chunks) {
+            yc += step_c;
+            m += RPI;
+            if (m >= a.Ns) {
+                m -= a.Ns;
+                yc += wrap_c;
             }
         }
     }
@@ -197,19 +231,42 @@ __device__ __forceinline__ void stage_tile16(const f32x4 (&acc)[NI][NJ], unsigne
 // RMSNorm over every head row and RoPE, on a wavefront's fp32 accumulators (NI feature tiles x NJ token tiles of 16 x 16:
 // lane l holds features 16i + 4(l/16) + e, e = 0..3, of token 16j + l%16), in the arithmetic order of the stand-alone
 // norm + RoPE kernel (x * rinv * gamma, then the rotation) -- but on the unrounded projection, so Q and K are rounded
-// to bf16 once instead of twice -- and straight on into the epilogue's staging rows (the first half of store_tile16).
+// to bf16 once instead of twice -- and straight on through the epilogue's staging rows to both destinations.
 // A head of d features is `d / (16 NI)` wavefronts wide (1, 2 or 4, neighbours along the features): each writes its
 // partial sums of squares to `xch` ([wavefront][token]) and, after a workgroup barrier, adds the group's partial sums
 // in a fixed order, so every wavefront of a head works with the same bits.
-// The rotation goes token tile by token tile: the 2 NI (cos, sin) values of a lane's token are loaded one token tile
-// ahead, and a token tile's accumulators are dead once it is staged, so the whole thing fits the registers the K loop had.
-// n_first: global index of the wavefront's token 0; tokens beyond n_last (rows past the end of a ragged tile, never
-// stored) take n_last's rotation.  feat0: the wavefront's first feature within its tensor.
-template <int NI, int NJ, int WN>
-__device__ __forceinline__ void norm_rope_stage(f32x4 (&acc)[NI][NJ], unsigned char* ep, const GemmArgs& a, const uint16_t* __restrict__ gamma,
-                                                uint32_t lane, uint32_t wave, uint32_t n_first, uint32_t n_last, uint32_t feat0, float* xch) {
+// The rotation table: where it fits beside the staging rows (IN_LDS) the workgroup copies it into LDS (`tab`) while the
+// sums of squares are formed, and the barrier publishes it; a token's (cos, sin) values then cost an LDS read instead
+// of a trip to L2.  Otherwise they are loaded from global memory one token tile ahead.
+// This stage's time is its instruction count (the workgroup's successor cannot start before it ends, and nothing else
+// runs on the unit), so the token's grid coordinates are divided out once, for token tile 0, and then stepped as table
+// row offsets: 16 tokens further is a.row_step16[] further in mixed radix, with carries (the absent axes of a one- or
+// two-axis grid are grids of one cell behind the last axis: they never carry).
+// The token tiles go through the staging rows in two halves (the first (NJ+1)/2, then the rest), which is what leaves
+// room for the table; a token tile's accumulators are dead once it is staged, so the whole thing fits the registers
+// the K loop had.
+// tok0 / feat0: the wavefront's first token within the launch's rows / first feature within its tensor.  Rows past the
+// launch's last token (ragged tile; never stored) rotate by some row of the table.
+template <int NI, int NJ, int WN, bool IN_LDS>
+__device__ __forceinline__ void norm_rope_store(f32x4 (&acc)[NI][NJ], unsigned char* ep, float* xch, float* tab, const GemmArgs& a,
+                                                const uint16_t* __restrict__ gamma, uint16_t* __restrict__ Y, uint16_t* __restrict__ Y2,
+                                                uint32_t lane, uint32_t wave, uint32_t tok0, uint32_t feat0) {
     constexpr uint32_t WF = NI * 16;                 // features per wavefront
+    constexpr int JH = (NJ + 1) / 2;                 // token tiles in the first half
     const uint32_t g4 = lane >> 4, tl = lane & 15u;
+    if (IN_LDS) {
+        const float2* __restrict__ src = reinterpret_cast<const float2*>(a.rope.cs);
+        for (int x = 0; x < a.rope.n_axes; ++x) {
+            const uint32_t first = a.tab_cum[x], count = (uint32_t)a.rope.grid[x] * (uint32_t)a.rope.pairs[x];
+            float* dst = tab + a.row_base[x];
+#pragma unroll 4
+            for (uint32_t e = wave * 64u + lane; e < count; e += 128u * WN) {
+                const uint32_t r = __umulhi(e, a.tab_magic[x]);             // e / pairs[x]
+                const uint32_t p = e - r * (uint32_t)a.rope.pairs[x];
+                *reinterpret_cast<float2*>(dst + r * a.row_stride[x] + 2u * p) = src[first + e];
+            }
+        }
+    }
     float rinv[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
@@ -223,12 +280,12 @@ __device__ __forceinline__ void norm_rope_stage(f32x4 (&acc)[NI][NJ], unsigned c
         rinv[j] = s;
     }
     const uint32_t group = a.d / WF;                 // the same for the whole launch
-    if (group > 1) {
-        if (lane < 16) {
+    if (group > 1 && lane < 16) {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) xch[wave * (NJ * 16) + 16 * j + lane] = rinv[j];
-        }
-        __syncthreads();
+        for (int j = 0; j < NJ; ++j) xch[wave * (NJ * 16) + 16 * j + lane] = rinv[j];
+    }
+    if (IN_LDS || group > 1) __syncthreads();
+    if (group > 1) {
         const uint32_t wf = wave % WN;
         const uint32_t w0 = wave - wf + (wf / group) * group;     // the head's first wavefront (same token half)
 #pragma unroll
@@ -243,6 +300,7 @@ __device__ __forceinline__ void norm_rope_stage(f32x4 (&acc)[NI][NJ], unsigned c
 
     // the lane's 2 NI rotary pairs (two per feature tile): which axis' table, and the float offset inside a table row
     const uint32_t fh0 = feat0 % a.d + 4u * g4;      // this lane's first feature inside its head, for feature tile 0
+    const uint32_t p0 = (uint32_t)a.rope.pairs[0], p01 = p0 + (uint32_t)a.rope.pairs[1];
     uint32_t axis[NI][2], col[NI][2];
     float g[NI][4];
 #pragma unroll
@@ -251,38 +309,47 @@ __device__ __forceinline__ void norm_rope_stage(f32x4 (&acc)[NI][NJ], unsigned c
         g[i][0] = bf16_lo(gw.x); g[i][1] = bf16_hi(gw.x); g[i][2] = bf16_lo(gw.y); g[i][3] = bf16_hi(gw.y);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            uint32_t jl = (fh0 + 16u * i) / 2u + q;
-            int x = 0;
-            while (x < a.rope.n_axes - 1 && jl >= (uint32_t)a.rope.pairs[x]) {
-                jl -= (uint32_t)a.rope.pairs[x];
-                ++x;
-            }
-            axis[i][q] = (uint32_t)x;
-            col[i][q] = 2u * jl;
+            const uint32_t jl = (fh0 + 16u * i) / 2u + q;         // pair index inside the head
+            axis[i][q] = a.rope.n_axes > 2 && jl >= p01 ? 2u : a.rope.n_axes > 1 && jl >= p0 ? 1u : 0u;
+            col[i][q] = 2u * (jl - (axis[i][q] == 2u ? p01 : axis[i][q] == 1u ? p0 : 0u));
         }
     }
-    // (cos, sin) of the lane's pairs for its token of token tile j
-    auto load_cs = [&](int j, float2 (&cs)[NI][2]) {
-        uint32_t rem = min(n_first + 16u * j + tl, n_last);     // grid coordinates, last axis fastest
-        uint32_t row0, row1 = 0, row2 = 0;                      // where the token's row starts in each axis' table
-        if (a.rope.n_axes > 2) {
-            row2 = (uint32_t)a.rope.offset[2] + rem % (uint32_t)a.rope.grid[2] * (2u * (uint32_t)a.rope.pairs[2]);
-            rem /= (uint32_t)a.rope.grid[2];
-        }
-        if (a.rope.n_axes > 1) {
-            row1 = (uint32_t)a.rope.offset[1] + rem % (uint32_t)a.rope.grid[1] * (2u * (uint32_t)a.rope.pairs[1]);
-            rem /= (uint32_t)a.rope.grid[1];
-        }
-        row0 = (uint32_t)a.rope.offset[0] + rem % (uint32_t)a.rope.grid[0] * (2u * (uint32_t)a.rope.pairs[0]);
+    // float offsets of the token's row in each axis' table, for this lane's token of token tile 0
+    uint32_t row_a[3];
+    {
+        uint32_t rem = (uint32_t)a.row_begin + tok0 + tl;
+        const uint32_t c2 = rem % (uint32_t)a.rope.grid[2];
+        rem /= (uint32_t)a.rope.grid[2];
+        const uint32_t c1 = rem % (uint32_t)a.rope.grid[1];
+        rem /= (uint32_t)a.rope.grid[1];
+        row_a[0] = a.row_base[0] + rem * a.row_stride[0];
+        row_a[1] = a.row_base[1] + c1 * a.row_stride[1];
+        row_a[2] = a.row_base[2] + c2 * a.row_stride[2];
+    }
+    const uint32_t end0 = a.row_end[0] - a.row_stride[0];     // the table's last row of axis 0
+    // (cos, sin) of the lane's pairs for its token of the current token tile; then on to the next tile's token
+    auto load_cs = [&](float2 (&cs)[NI][2]) {
+        const uint32_t r0 = min(row_a[0], end0), r1 = row_a[1], r2 = row_a[2];
 #pragma unroll
         for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                const uint32_t row = axis[i][q] == 0 ? row0 : axis[i][q] == 1 ? row1 : row2;
-                cs[i][q] = *reinterpret_cast<const float2*>(a.rope.cs + row + col[i][q]);
+                const uint32_t off = (axis[i][q] == 0 ? r0 : axis[i][q] == 1 ? r1 : r2) + col[i][q];
+                if (IN_LDS)
+                    cs[i][q] = *reinterpret_cast<const float2*>(tab + off);
+                else
+                    cs[i][q] = *reinterpret_cast<const float2*>(a.rope.cs + off);
             }
+        row_a[2] += a.row_step16[2];
+        const bool carry2 = row_a[2] >= a.row_end[2];
+        row_a[2] -= carry2 ? a.row_span[2] : 0u;
+        row_a[1] += a.row_step16[1] + (carry2 ? a.row_stride[1] : 0u);
+        const bool carry1 = row_a[1] >= a.row_end[1];
+        row_a[1] -= carry1 ? a.row_span[1] : 0u;
+        row_a[0] += a.row_step16[0] + (carry1 ? a.row_stride[0] : 0u);
     };
     auto rotate_stage = [&](int j, const float2 (&cs)[NI][2]) {
+        const uint32_t row = 16u * (j < JH ? j : j - JH) + tl;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             float o[4];
@@ -293,19 +360,26 @@ __device__ __forceinline__ void norm_rope_stage(f32x4 (&acc)[NI][NJ], unsigned c
                 o[2 * q] = ev * cs[i][q].x - od * cs[i][q].y;
                 o[2 * q + 1] = ev * cs[i][q].y + od * cs[i][q].x;
             }
-            EpilogueRows<NI * 2>::put4(ep, 16u * j + tl, 16u * i + 4u * g4, o[0], o[1], o[2], o[3]);
+            EpilogueRows<NI * 2>::put4(ep, row, 16u * i + 4u * g4, o[0], o[1], o[2], o[3]);
         }
+        // a half is complete: out it goes (this wavefront's LDS accesses complete in order, so the next half may
+        // overwrite the rows right away)
+        if (j == JH - 1)
+            store_rows<NI * 2, JH * 16, OUT_FUSED>(ep, lane, Y, Y2, (size_t)a.row_begin, tok0, feat0, (uint32_t)a.M, (uint32_t)a.D, a);
+        if (j == NJ - 1 && NJ > JH)
+            store_rows<NI * 2, (NJ - JH) * 16, OUT_FUSED>(ep, lane, Y, Y2, (size_t)a.row_begin, tok0 + JH * 16u, feat0, (uint32_t)a.M,
+                                                          (uint32_t)a.D, a);
     };
     float2 cs_a[NI][2], cs_b[NI][2];
-    load_cs(0, cs_a);
+    load_cs(cs_a);
 #pragma unroll
     for (int j = 0; j < NJ; j += 2) {
-        if (j + 1 < NJ) load_cs(j + 1, cs_b);
+        if (j + 1 < NJ) load_cs(cs_b);
         __builtin_amdgcn_sched_barrier(0);
         rotate_stage(j, cs_a);
         __builtin_amdgcn_sched_barrier(0);
         if (j + 1 < NJ) {
-            if (j + 2 < NJ) load_cs(j + 2, cs_a);
+            if (j + 2 < NJ) load_cs(cs_a);
             __builtin_amdgcn_sched_barrier(0);
             rotate_stage(j + 1, cs_b);
             __builtin_amdgcn_sched_barrier(0);
@@ -341,6 +415,9 @@ constexpr double kPenalty288 = 1.07;   // measured per-flop cost of the 288 x 19
                                        // 11 % more operand bytes into LDS and 18 % more fragment reads per flop
 constexpr double kPenalty192 = 1.2;    // 192 x 192: a third more operand bytes and twice the fragment reads per flop
 constexpr int ring_lds_bytes(int bm, int bn) { return (kXSlots * bm + kWSlots * bn) * BK * 2; }
+// Floats of LDS left for the rotation table in a normalising tile of the fused call (bn = 256: 8 wavefronts of 64
+// features x bm/2 tokens): the ring minus a half tile of 128-byte staging rows and bm/2 partial sums per wavefront.
+constexpr int fused_table_floats(int bm, int bn) { return (ring_lds_bytes(bm, bn) - 8 * ((bm / 32 + 1) / 2 * 16 * 128 + bm / 2 * 4)) / 4; }
 
 // One global -> LDS load of 16 bytes per lane: lane l's vector lands at lds_addr + 16*l.  Written as inline
 // assembly so that the compiler does not tie later LDS reads to it with a full vmcnt wait (it cannot tell
@@ -516,20 +593,25 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
     advance();
     k_step(kt, xs, ws, no{}, no{}, w0, no{});      // step n_k-1
     __syncthreads();
-    constexpr int kEpilogueBytes = NJ * 16 * EpilogueRows<NI * 2>::ROWB;   // per wavefront, see store_tile16
-    constexpr int kExchangeBytes = LAYOUT == OUT_FUSED ? WAVES * NJ * 16 * 4 : 0;   // partial sums of squares, see norm_rope_acc
-    static_assert(WAVES * kEpilogueBytes + kExchangeBytes <= ring_lds_bytes(TM, TN), "the epilogue reuses the ring's LDS");
-    unsigned char* ep = smem + wave * kEpilogueBytes;
-    bool staged = false;
+    constexpr int kEpilogueBytes = NJ * 16 * EpilogueRows<NI * 2>::ROWB;   // per wavefront, see stage_tile16
+    static_assert(WAVES * kEpilogueBytes <= ring_lds_bytes(TM, TN), "the epilogue reuses the ring's LDS");
     if constexpr (LAYOUT == OUT_FUSED) {
         if (a.gamma[tc.tensor]) {     // the same for the whole workgroup: its barrier is taken by all or by none
-            norm_rope_stage<NI, NJ, WN>(acc, ep, a, a.gamma[tc.tensor], lane, wave, (uint32_t)a.row_begin + tc.m0 + wave_t,
-                                        (uint32_t)a.row_begin + (uint32_t)a.M - 1u, tc.f0 + wave_f,
-                                        reinterpret_cast<float*>(smem + WAVES * kEpilogueBytes));
-            staged = true;
+            // LDS of a normalising tile: a half tile of staging rows per wavefront, the partial sums of squares, the table
+            constexpr int kHalfBytes = (NJ + 1) / 2 * 16 * EpilogueRows<NI * 2>::ROWB;
+            static_assert(fused_table_floats(TM, TN) >= 0, "the staging rows and the partial sums fit the ring's LDS");
+            float* xch = reinterpret_cast<float*>(smem + WAVES * kHalfBytes);
+            if (a.tab_lds)
+                norm_rope_store<NI, NJ, WN, true>(acc, smem + wave * kHalfBytes, xch, xch + WAVES * NJ * 16, a, a.gamma[tc.tensor],
+                                                  a.y[tc.tensor], a.y2[tc.tensor], lane, wave, tc.m0 + wave_t, tc.f0 + wave_f);
+            else
+                norm_rope_store<NI, NJ, WN, false>(acc, smem + wave * kHalfBytes, xch, nullptr, a, a.gamma[tc.tensor], a.y[tc.tensor],
+                                                   a.y2[tc.tensor], lane, wave, tc.m0 + wave_t, tc.f0 + wave_f);
+            return;
         }
     }
-    if (!staged) stage_tile16<NI, NJ>(acc, ep, lane);
+    unsigned char* ep = smem + wave * kEpilogueBytes;
+    stage_tile16<NI, NJ>(acc, ep, lane);
     store_rows<NI * 2, NJ * 16, LAYOUT>(ep, lane, a.y[tc.tensor], LAYOUT == OUT_FUSED ? a.y2[tc.tensor] : nullptr, (size_t)a.row_begin,
                                         tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
 }
@@ -764,6 +846,7 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.inv_d = 1.0f / (float)shape->d;
     a.eps = fused ? fused->eps : 0.f;
     a.rope = fused ? fused->rope : RopeDev{};
+    a.tab_lds = 0;
     const int32_t Ns = shape->N / shape->P;
     a.row_begin = shape->rank_begin * Ns;
     a.M = shape->rank_count * Ns;
@@ -780,6 +863,40 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.tiles_m = plan.tiles_m;
     a.tiles_n_per_tensor = plan.tiles_n_per_tensor;
     const uint32_t n_tiles = (uint32_t)a.tiles_m * a.tiles_n_per_tensor * a.n_tensors;
+    for (int ax = 0; ax < 3; ++ax)
+        a.row_base[ax] = a.row_stride[ax] = a.row_span[ax] = a.row_end[ax] = a.row_step16[ax] = a.tab_cum[ax] = a.tab_magic[ax] = 0;
+    if (layout == OUT_FUSED && (a.gamma[0] || a.gamma[1] || a.gamma[2])) {      // (V alone comes without a rotation)
+        // the rotation table goes through LDS when it fits beside the tile's staging rows, padded by two floats a row
+        // (a row of one pair would need a divisor of 2^32: such tables stay in global memory)
+        uint32_t pairs_total = 0, floats = 0;
+        bool can = true;
+        for (int ax = 0; ax < 3; ++ax) {
+            const uint32_t pr = (uint32_t)a.rope.pairs[ax], rows = (uint32_t)a.rope.grid[ax];     // absent axes: 0 pairs, 1 row
+            can = can && (pr >= 2 || ax >= a.rope.n_axes);
+            a.tab_cum[ax] = pairs_total;
+            a.tab_magic[ax] = pr >= 2 ? (uint32_t)((((uint64_t)1 << 32) + pr - 1) / pr) : 0u;
+            a.row_base[ax] = floats;
+            a.row_stride[ax] = ax < a.rope.n_axes ? 2u * pr + 2u : 0u;
+            pairs_total += rows * pr;
+            if (floats <= (uint32_t)fused_table_floats(256, 256)) floats += rows * a.row_stride[ax];     // (no overflow: rows, pr < 2^31 / 2)
+            can = can && floats <= (uint32_t)fused_table_floats(256, 256);
+        }
+        const int room = pick->bm == 256 ? fused_table_floats(256, 256) : pick->bm == 224 ? fused_table_floats(224, 256) : fused_table_floats(192, 256);
+        a.tab_lds = can && (int)floats <= room;
+        if (!a.tab_lds)
+            for (int ax = 0; ax < 3; ++ax) {
+                a.row_base[ax] = (uint32_t)a.rope.offset[ax];
+                a.row_stride[ax] = 2u * (uint32_t)a.rope.pairs[ax];
+            }
+        uint32_t rest = 16;     // 16 tokens in the grid's mixed radix, last axis fastest
+        for (int ax = 2; ax >= 0; --ax) {
+            const uint32_t rows = (uint32_t)a.rope.grid[ax];
+            a.row_span[ax] = rows * a.row_stride[ax];
+            a.row_end[ax] = ax < a.rope.n_axes ? a.row_base[ax] + a.row_span[ax] : UINT32_MAX;     // an absent axis never carries
+            a.row_step16[ax] = (ax > 0 ? rest % rows : rest) * a.row_stride[ax];
+            rest /= rows;
+        }
+    }
 
     // dynamic LDS above 64 KB needs the attribute, once per process (thread-safe initialisation)
     static const hipError_t attr_rc = [] {

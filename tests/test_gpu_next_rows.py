@@ -437,6 +437,10 @@ def test_proj_fused_matches_the_chain_oracle(oracle, name):
     (528, 3, 256, 1, (22, 24), (64, 64), None),         # a head across four wavefronts; D = 768: three tiles of 256
     (96, 5, 64, 1, (2, 4, 12), (10, 11, 11), None),     # three axes, pair split off the 2-pair grid; D = 320: ragged feature tile
     (512, 4, 128, 4, (16, 32), (40, 24), 2),            # one rank of four
+    (384, 4, 64, 1, (2, 4, 48), (1, 15, 16), None),     # an axis of one pair: the rotation table is read from global memory
+    (12288, 4, 64, 1, (12288,), (32,), None),           # a table (3 MB) that does not fit LDS: global memory again
+    (608, 4, 128, 1, (19, 32), (63, 1), None),          # the fastest axis one pair wide
+    (416, 8, 64, 1, (13, 32), (12, 20), None),          # two feature tiles, ragged third token tile
 ])
 def test_proj_fused_other_shapes(oracle, N, H, d, P, grid, pairs, rank):
     from synth import f32_to_bf16_bits
@@ -449,6 +453,27 @@ def test_proj_fused_other_shapes(oracle, N, H, d, P, grid, pairs, rank):
         inp[g_] = f32_to_bf16_bits((1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32))
     ids = np.arange(N) if rank is None else np.arange(rank * (N // P), (rank + 1) * (N // P))
     _fused_case(oracle, N, D, H, d, P, grid, pairs, inp, ids, rank=rank, what=f"{N}x{D}")
+
+
+@gpu
+@pytest.mark.parametrize("N,H,d,grid,pairs,tile_tokens", [
+    (9120, 24, 128, (48, 190), (32, 32), 224),          # 41 x 12 x 3 tiles of 224 tokens, the last row 160 tokens; table 63 KB in LDS
+    (20720, 47, 64, (37, 16, 35), (10, 11, 11), 256),   # 81 x 12 x 3 tiles of 256 tokens, ragged in tokens (240) and features (192)
+])
+def test_proj_fused_ragged_tiles_of_224_and_256_tokens(oracle, N, H, d, grid, pairs, tile_tokens):
+    """The two larger tile shapes of the fused call with a ragged last tile row (C3, C4 and C5 are whole multiples)."""
+    from synth import f32_to_bf16_bits
+    D = H * d
+    assert cd.qkv_proj_plan(cd.Shape.make(N, D, H, d, 1), 3, whole_heads=True)["tile_tokens"] == tile_tokens
+    rng = np.random.default_rng(N)
+    inp = {"X": f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32))}
+    for w in ("Wq", "Wk", "Wv"):
+        inp[w] = f32_to_bf16_bits(rng.standard_normal((D, D), dtype=np.float32) * np.float32(D ** -0.5))
+    for g_ in ("gamma_q", "gamma_k"):
+        inp[g_] = f32_to_bf16_bits((1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32))
+    last = N // tile_tokens * tile_tokens
+    ids = np.unique(np.concatenate([np.arange(0, 40), np.arange(last - 24, N), rng.integers(0, N, 200)]))
+    _fused_case(oracle, N, D, H, d, 1, grid, pairs, inp, ids, what=f"{N}x{D}")
 
 
 @gpu
