@@ -14,21 +14,24 @@ constexpr int kThreads = 256;
 struct PermuteArgs {
     uint32_t Ns, P, D8, d8, row8, chunk8;
     uint32_t N;           // tokens in total
-    uint32_t first;       // token-major walk: first token of the range; head-major walk: first head of the range
+    uint32_t first;       // walk over x_seq: first token of the range; walk over x_hs: first head of the range
     uint32_t n_vec;       // vectors this launch moves
     int recv_major;
+    uint32_t rank_begin, rank_count;     // the launch's ranks (buffer walks)
 };
 
 __device__ __forceinline__ uint32_t slot_of(uint32_t sender, uint32_t receiver, uint32_t P, int recv_major) {
     return recv_major ? receiver * P + sender : sender * P + receiver;
 }
 
-// Walks the sequence-parallel tensor [N][H][d] linearly over the token range of the launch, one vector per thread
-// (small workgroups measured fastest on cold data and disturb a concurrent projection least).
-// TO_BUF: x_seq -> exchange buffer (first all-to-all, sender = token owner r, receiver = head owner p);
-// else:   exchange buffer -> x_seq (second all-to-all, sender = head owner p, receiver = token owner r).
-template <bool NT_LD, bool NT_ST, bool TO_BUF>
-__global__ void __launch_bounds__(kThreads) seq_side_kernel(const vec16* __restrict__ in, vec16* __restrict__ out, PermuteArgs a) {
+// Every kernel walks its OUTPUT linearly, one 16-byte vector per thread (small workgroups measured fastest on cold
+// data and disturb a concurrent projection least): stores that run linearly through memory and loads that gather
+// 512- or 256-byte pieces are faster than the other way round (cold, 57 MB tensors: 20 against 21.5 us).
+
+// Exchange buffer -> sequence-parallel tensor [N][H][d] (second all-to-all: sender = head owner p, receiver = token
+// owner r), linearly over the token range of the launch.
+template <bool NT_LD, bool NT_ST>
+__global__ void __launch_bounds__(kThreads) seq_from_buf_kernel(const vec16* __restrict__ in, vec16* __restrict__ out, PermuteArgs a) {
     const uint32_t g = blockIdx.x * kThreads + threadIdx.x;
     if (g >= a.n_vec) return;
     const uint32_t tl = g / a.D8;            // token within the range
@@ -39,16 +42,14 @@ __global__ void __launch_bounds__(kThreads) seq_side_kernel(const vec16* __restr
     const uint32_t p = v / a.row8;           // head owner
     const uint32_t c = v - p * a.row8;       // (hl, i) within the chunk row
     const size_t seq_at = (size_t)n * a.D8 + v;
-    const size_t buf_at = (size_t)(TO_BUF ? slot_of(r, p, a.P, a.recv_major) : slot_of(p, r, a.P, a.recv_major)) * a.chunk8 +
-                          m * a.row8 + c;
-    st_vec<NT_ST>(out + (TO_BUF ? buf_at : seq_at), ld_vec<NT_LD>(in + (TO_BUF ? seq_at : buf_at)));
+    const size_t buf_at = (size_t)slot_of(p, r, a.P, a.recv_major) * a.chunk8 + m * a.row8 + c;
+    st_vec<NT_ST>(out + seq_at, ld_vec<NT_LD>(in + buf_at));
 }
 
-// Walks the head-parallel tensor [H][N][d] linearly over the head range of the launch.
-// TO_BUF: x_hs -> exchange buffer (second all-to-all, sender = head owner p, receiver = token owner r);
-// else:   exchange buffer -> x_hs (first all-to-all, sender = token owner r, receiver = head owner p).
-template <bool NT_LD, bool NT_ST, bool TO_BUF>
-__global__ void __launch_bounds__(kThreads) head_side_kernel(const vec16* __restrict__ in, vec16* __restrict__ out, PermuteArgs a) {
+// Exchange buffer -> head-parallel tensor [H][N][d] (first all-to-all: sender = token owner r, receiver = head owner
+// p), linearly over the head range of the launch.
+template <bool NT_LD, bool NT_ST>
+__global__ void __launch_bounds__(kThreads) heads_from_buf_kernel(const vec16* __restrict__ in, vec16* __restrict__ out, PermuteArgs a) {
     const uint32_t g = blockIdx.x * kThreads + threadIdx.x;
     if (g >= a.n_vec) return;
     const uint32_t head8 = a.N * a.d8;       // vectors per head slab
@@ -63,9 +64,41 @@ __global__ void __launch_bounds__(kThreads) head_side_kernel(const vec16* __rest
     const uint32_t r = n / a.Ns;             // token owner
     const uint32_t m = n - r * a.Ns;
     const size_t hs_at = (size_t)a.first * head8 + g;
-    const size_t buf_at = (size_t)(TO_BUF ? slot_of(p, r, a.P, a.recv_major) : slot_of(r, p, a.P, a.recv_major)) * a.chunk8 +
-                          m * a.row8 + hl * a.d8 + i8;
-    st_vec<NT_ST>(out + (TO_BUF ? buf_at : hs_at), ld_vec<NT_LD>(in + (TO_BUF ? hs_at : buf_at)));
+    const size_t buf_at = (size_t)slot_of(r, p, a.P, a.recv_major) * a.chunk8 + m * a.row8 + hl * a.d8 + i8;
+    st_vec<NT_ST>(out + hs_at, ld_vec<NT_LD>(in + buf_at));
+}
+
+// The packing directions: thread g of the launch is vector g of the chunks the launch's ranks send, in buffer order.
+// Sequence-parallel tensor -> exchange buffer (first all-to-all): the senders are the token owners r of the rank range.
+template <bool NT_LD, bool NT_ST>
+__global__ void __launch_bounds__(kThreads) buf_from_seq_kernel(const vec16* __restrict__ in, vec16* __restrict__ out, PermuteArgs a) {
+    const uint32_t g = blockIdx.x * kThreads + threadIdx.x;
+    if (g >= a.n_vec) return;
+    const uint32_t ch = g / a.chunk8, rem = g - ch * a.chunk8;       // chunk of the launch, vector inside it
+    // send-major: chunks (r, p) with p fastest; receive-major: (p, r) with r fastest
+    const uint32_t r = a.rank_begin + (a.recv_major ? ch % a.rank_count : ch / a.P);
+    const uint32_t p = a.recv_major ? ch / a.rank_count : ch % a.P;
+    const uint32_t m = rem / a.row8, c = rem - m * a.row8;
+    const size_t seq_at = (size_t)(r * a.Ns + m) * a.D8 + p * a.row8 + c;
+    const size_t buf_at = (size_t)slot_of(r, p, a.P, a.recv_major) * a.chunk8 + rem;
+    st_vec<NT_ST>(out + buf_at, ld_vec<NT_LD>(in + seq_at));
+}
+
+// Head-parallel tensor -> exchange buffer (second all-to-all): the senders are the head owners p of the rank range.
+template <bool NT_LD, bool NT_ST>
+__global__ void __launch_bounds__(kThreads) buf_from_heads_kernel(const vec16* __restrict__ in, vec16* __restrict__ out, PermuteArgs a) {
+    const uint32_t g = blockIdx.x * kThreads + threadIdx.x;
+    if (g >= a.n_vec) return;
+    const uint32_t ch = g / a.chunk8, rem = g - ch * a.chunk8;
+    // send-major: chunks (p, r) with r fastest; receive-major: (r, p) with p fastest
+    const uint32_t p = a.rank_begin + (a.recv_major ? ch % a.rank_count : ch / a.P);
+    const uint32_t r = a.recv_major ? ch / a.rank_count : ch % a.P;
+    const uint32_t m = rem / a.row8, c = rem - m * a.row8;           // token within the rank; (hl, i) within the chunk row
+    const uint32_t hl = c / a.d8, i8 = c - hl * a.d8;
+    const uint32_t Hp = a.row8 / a.d8;
+    const size_t hs_at = ((size_t)(p * Hp + hl) * a.N + r * a.Ns + m) * a.d8 + i8;
+    const size_t buf_at = (size_t)slot_of(p, r, a.P, a.recv_major) * a.chunk8 + rem;
+    st_vec<NT_ST>(out + buf_at, ld_vec<NT_LD>(in + hs_at));
 }
 
 static int check_permute(const cocodiff_shape* s, const void* in, const void* out, int slot_order, const char* who) {
@@ -92,10 +125,12 @@ static PermuteArgs make_args(const cocodiff_shape* s, int slot_order) {
     a.first = 0;
     a.n_vec = 0;
     a.recv_major = slot_order == COCODIFF_RECV_MAJOR;
+    a.rank_begin = (uint32_t)s->rank_begin;
+    a.rank_count = (uint32_t)s->rank_count;
     return a;
 }
 
-// Token-major walk over the ranks of the shape's range (they are token owners).
+// Between the sequence-parallel tensor and the buffer; the ranks of the shape's range are token owners.
 template <bool TO_BUF>
 static int launch_seq_side(const cocodiff_shape* shape, const void* in, void* out, int slot_order, void* stream, const char* who) {
     int rc = check_permute(shape, in, out, slot_order, who);
@@ -105,13 +140,17 @@ static int launch_seq_side(const cocodiff_shape* shape, const void* in, void* ou
     a.n_vec = (uint32_t)shape->rank_count * a.Ns * a.D8;
     const dim3 grid((a.n_vec + kThreads - 1) / kThreads), block(kThreads);
     with_policy(stream_loads((size_t)a.n_vec * 32), stream_stores((size_t)a.n_vec * 32), [&](auto L, auto S) {
-        hipLaunchKernelGGL((seq_side_kernel<decltype(L)::value, decltype(S)::value, TO_BUF>), grid, block, 0, as_stream(stream),
-                           (const vec16*)in, (vec16*)out, a);
+        if (TO_BUF)      // (the same vectors, counted along the buffer)
+            hipLaunchKernelGGL((buf_from_seq_kernel<decltype(L)::value, decltype(S)::value>), grid, block, 0, as_stream(stream),
+                               (const vec16*)in, (vec16*)out, a);
+        else
+            hipLaunchKernelGGL((seq_from_buf_kernel<decltype(L)::value, decltype(S)::value>), grid, block, 0, as_stream(stream),
+                               (const vec16*)in, (vec16*)out, a);
     });
     return check_launch(who);
 }
 
-// Head-major walk over the ranks of the shape's range (they are head owners).
+// Between the head-parallel tensor and the buffer; the ranks of the shape's range are head owners.
 template <bool TO_BUF>
 static int launch_head_side(const cocodiff_shape* shape, const void* in, void* out, int slot_order, void* stream, const char* who) {
     int rc = check_permute(shape, in, out, slot_order, who);
@@ -122,8 +161,12 @@ static int launch_head_side(const cocodiff_shape* shape, const void* in, void* o
     a.n_vec = (uint32_t)shape->rank_count * Hp * a.N * a.d8;
     const dim3 grid((a.n_vec + kThreads - 1) / kThreads), block(kThreads);
     with_policy(stream_loads((size_t)a.n_vec * 32), stream_stores((size_t)a.n_vec * 32), [&](auto L, auto S) {
-        hipLaunchKernelGGL((head_side_kernel<decltype(L)::value, decltype(S)::value, TO_BUF>), grid, block, 0, as_stream(stream),
-                           (const vec16*)in, (vec16*)out, a);
+        if (TO_BUF)
+            hipLaunchKernelGGL((buf_from_heads_kernel<decltype(L)::value, decltype(S)::value>), grid, block, 0, as_stream(stream),
+                               (const vec16*)in, (vec16*)out, a);
+        else
+            hipLaunchKernelGGL((heads_from_buf_kernel<decltype(L)::value, decltype(S)::value>), grid, block, 0, as_stream(stream),
+                               (const vec16*)in, (vec16*)out, a);
     });
     return check_launch(who);
 }
