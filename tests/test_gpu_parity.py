@@ -90,6 +90,32 @@ def test_per_rank_calls_equal_one_call(oracle, name):
         assert np.array_equal(to_host_bits(hs), x.transpose(1, 0, 2))
 
 
+@pytest.mark.parametrize("order", [0, 1])
+def test_pack_rank_ranges_of_several_ranks(oracle, order):
+    """A range of several sender ranks that starts past rank 0: its chunks equal the oracle's, every other chunk stays
+    as it was -- for the first all-to-all's pack (senders own tokens) and the second's (senders own heads)."""
+    cfg = CONFIGS["C2"]
+    P, first, count = cfg.P, 3, 4
+    rng = np.random.default_rng(31 + order)
+    x = rng.integers(0, 65535, size=(cfg.N, cfg.H, cfg.d), dtype=np.uint16)      # 0xFFFF is the fill value
+    y = np.ascontiguousarray(x.transpose(1, 0, 2))
+    # chunk slot of (sender s, receiver t)
+    slot = (lambda s_, t_: t_ * P + s_) if order == cd.RECV_MAJOR else (lambda s_, t_: s_ * P + t_)
+    sent = np.zeros(P * P, dtype=bool)
+    for s_ in range(first, first + count):
+        for t_ in range(P):
+            sent[slot(s_, t_)] = True
+    for call, src, want in ((cd.a2a_pack, x, oracle.a2a_pack(x, P, order)), (cd.a2a_pack_hs, y, oracle.a2a_pack_hs(y, P, order))):
+        buf = dev_empty((P * P, cfg.Ns, cfg.Hp, cfg.d))
+        buf.fill_(-1)
+        call(_shape(cfg, first, count), to_dev(src), buf, order)
+        _sync()
+        got = to_host_bits(buf).reshape(P * P, -1)
+        want = want.reshape(P * P, -1)
+        assert np.array_equal(got[sent], want[sent]), call.__name__
+        assert np.all(got[~sent] == 0xFFFF), f"{call.__name__}: chunks of other senders were written"
+
+
 @pytest.mark.parametrize("N,H,d,P", [(48, 3, 8, 3), (16, 1, 8, 1), (80, 5, 24, 5), (272, 2, 200, 1), (32, 4, 512, 2)])
 def test_pack_unpack_odd_shapes(oracle, N, H, d, P):
     rng = np.random.default_rng(N + H + d)
