@@ -9,14 +9,15 @@ head-parallel Q (normalised, rotated), K (same) and V, and the selection's flags
   fused0     one stream:  qkv_proj_fused(V, Q, K in one launch, V's tiles first: every tensor to its exchange buffer and to its
                           head-parallel tensor, norm + RoPE of Q and K in the epilogue) -> vmajor_select(V)
   fused0v    one stream:  qkv_proj_fused(V) -> qkv_proj_fused(Q, K) -> vmajor_select(V)
+  fused0v2   two streams: main qkv_proj_fused(V) -> qkv_proj_fused(Q, K); side [after V's launch] vmajor_select(V); joined at the end
   fused1     one stream:  qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_select(V) -> a2a_unpack_norm_rope(Q, K)
   fused1qkv  one stream:  qkv_proj_pack(V, Q, K in one launch, V's tiles first) -> a2a_unpack_select -> a2a_unpack_norm_rope
   fused2     two streams: main qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K);
                           side [after V's projection] a2a_unpack_select(V); joined at the end of the step
   fused3     three streams: V, Q, K projected by three launches of qkv_proj_pack, each tensor's unpack under the next projection
-(in fused0 / fused0v the exchange buffers of Q and K carry normalised values -- norm + RoPE on the sending side, the paper's
+(in fused0 / fused0v / fused0v2 the exchange buffers of Q and K carry normalised values -- norm + RoPE on the sending side, the paper's
 order -- in the others the projection itself, normalised by the receiver's unpack).
-The default run times all six with the same --warmup / --steps (three times each, interleaved, after a clock
+The default run times all seven with the same --warmup / --steps (three times each, interleaved, after a clock
 ramp: see time_headline) and reports each; `value` is the fastest one measured in this run (named in config.schedule).  Also timed and reported beside it: the same step through the five
 stand-alone calls only ("vfirst", two streams; "serial", one), the single-GPU direct form that writes V straight
 into the head-parallel layout ("fused1_vdirect": no exchange buffer for V), a HIP-graph replay of the headline
@@ -40,7 +41,7 @@ METRIC = "tokens/s per layer (QKV+norm+RoPE+pack); pack/select GB/s vs HBM peak"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "qkv_gemm_hbm_traffic.txt")
-HEADLINE_CANDIDATES = ("fused0", "fused0v", "fused1", "fused1qkv", "fused2", "fused3")
+HEADLINE_CANDIDATES = ("fused0", "fused0v", "fused0v2", "fused1", "fused1qkv", "fused2", "fused3")
 
 
 def measured_traffic(workload: str, form: str, kernel_tile: str, launches_per_step: int):
@@ -170,7 +171,7 @@ class Workload:
         v_prev_host, _ = perturb_tiles(self.bits(self.hv), 1, T, cfg.n_changed, np.random.default_rng(cfg.index), cfg.noise_sigma)
         self.hv_prev = up(v_prev_host)
         del v_prev_host
-        self.schedules = {"fused0": self.step_fused0, "fused0v": self.step_fused0v, "fused1": self.step_fused1, "fused1qkv": self.step_fused1qkv, "fused2": self.step_fused2,
+        self.schedules = {"fused0": self.step_fused0, "fused0v": self.step_fused0v, "fused0v2": self.step_fused0v2, "fused1": self.step_fused1, "fused1qkv": self.step_fused1qkv, "fused2": self.step_fused2,
                           "fused2x": self.step_fused2x, "fused3": self.step_fused3, "fused3s": self.step_fused3s,
                           "fused1_vdirect": self.step_fused1_vdirect,
                           "vfirst": self.step_vfirst, "vfirst3": self.step_vfirst3, "serial": self.step_serial}
@@ -235,6 +236,17 @@ class Workload:
         self.proj(rec, st, lambda s: cd.qkv_proj_fused(sh, self.X, self.Wq, self.Wk, None, self.gq, self.gk, c.eps, self.rope,
                                                        self.bq, self.bk, None, self.ORDER, self.hq, self.hk, None, stream=s))
         self.select(st)
+
+    def step_fused0v2(self, rec=None):
+        """fused0v with V's selection on the side stream, under the Q and K launch."""
+        cd, sh, st, side, c = self.cd, self.sh, self.s_main, self.s_side, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj_fused(sh, self.X, None, None, self.Wv, None, None, c.eps, None,
+                                                       None, None, self.bv, self.ORDER, None, None, self.hv, stream=s))
+        self.fork(st, side)
+        self.proj(rec, st, lambda s: cd.qkv_proj_fused(sh, self.X, self.Wq, self.Wk, None, self.gq, self.gk, c.eps, self.rope,
+                                                       self.bq, self.bk, None, self.ORDER, self.hq, self.hk, None, stream=s))
+        self.select(side)
+        self.fork(side, st)
 
     def step_fused1(self, rec=None):
         cd, sh, st = self.cd, self.sh, self.s_main
@@ -535,6 +547,8 @@ def main() -> int:
             cd.qkv_proj_pack(w.sh, w.X, None, None, w.Wv, None, None, w.bv, w.ORDER)
             cd.qkv_proj_pack(w.sh, w.X, w.Wq, w.Wk, None, w.bq, w.bk, None, w.ORDER)
             cd.qkv_proj_pack(w.sh, w.X, w.Wq, w.Wk, w.Wv, w.bq, w.bk, w.bv, w.ORDER)
+            cd.qkv_proj_fused(w.sh, w.X, None, None, w.Wv, None, None, cfg.eps, None, None, None, w.bv, w.ORDER, None, None, w.hv)
+            cd.qkv_proj_fused(w.sh, w.X, w.Wq, w.Wk, None, w.gq, w.gk, cfg.eps, w.rope, w.bq, w.bk, None, w.ORDER, w.hq, w.hk, None)
             cd.qkv_proj_fused(w.sh, w.X, w.Wq, w.Wk, w.Wv, w.gq, w.gk, cfg.eps, w.rope, w.bq, w.bk, w.bv, w.ORDER, w.hq, w.hk, w.hv)
             w.unpack_select(None)
             w.select(None)
