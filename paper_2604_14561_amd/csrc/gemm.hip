@@ -15,7 +15,10 @@
 // the features x two along the tokens, two per SIMD, so one can multiply while the other waits for LDS, memory or
 // the barrier.  General kernel (any K that is a multiple of 8): global -> registers -> LDS, zero-filled K tail.
 // The epilogue rounds to bf16, transposes through the (now idle) LDS and writes 16-byte vectors: rows of [N][D],
-// row pieces straight into their chunks of the exchange buffer, or row pieces of the head-parallel tensor.
+// row pieces straight into their chunks of the exchange buffer, or row pieces of the head-parallel tensor -- or, in
+// the fused form (tiles 256 features wide, so that they hold whole heads), it first RMS-normalises and rotates Q and K
+// on the fp32 accumulators (paper Section II-B's norm and RoPE, one rounding in all) and writes both the chunks and
+// the head-parallel tensor.
 #include <initializer_list>
 #include <type_traits>
 
