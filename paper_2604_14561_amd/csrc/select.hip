@@ -242,18 +242,19 @@ __global__ void __launch_bounds__(THREADS) select_gather_kernel(const vec16* __r
     const uint32_t t = blockIdx.x;
     const bool mine = (tile_flag[t] & mask) != 0;
     const bool last = t + 1 == sh.NT;
-    if (user_flags && threadIdx.x == 0) user_flags[t] = mine ? 1 : 0;
-    if (!mine && !last) return;
+    const bool lead = blockIdx.y == 0;        // with several workgroups per tile (gridDim.y), the first one also writes the lists
+    if (user_flags && lead && threadIdx.x == 0) user_flags[t] = mine ? 1 : 0;
+    if (!mine && !(last && lead)) return;
     uint32_t before = 0;
     for (uint32_t u = threadIdx.x; u < t; u += THREADS) before += (tile_flag[u] & mask) != 0 ? 1u : 0u;
     const uint32_t slot = block_sum<THREADS>(before, wave_tot);
-    if (threadIdx.x == 0) {
+    if (lead && threadIdx.x == 0) {
         if (mine) idx[slot] = (int32_t)t;
         if (last) *n_active = (int32_t)(slot + (mine ? 1u : 0u));
     }
     if (!mine || !compact || slot >= cap_tiles) return;
     const uint32_t total = sh.S * sh.seg8;
-    for (uint32_t g0 = threadIdx.x; g0 < total; g0 += kSelUnroll * THREADS) {
+    for (uint32_t g0 = blockIdx.y * (kSelUnroll * THREADS) + threadIdx.x; g0 < total; g0 += gridDim.y * (kSelUnroll * THREADS)) {
         vec16 c[kSelUnroll];
         uint64_t dst[kSelUnroll];
 #pragma unroll
@@ -392,9 +393,18 @@ static int select_launch(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
     });
     rc = check_launch("select_flag_kernel");
     if (rc != COCODIFF_OK) return rc;
-    // gather pass: one workgroup per tile, a tile in as few passes as possible (kSelUnroll vectors per lane and pass)
-    const int threads = per_tile > 512 * kSelUnroll ? 1024 : per_tile > 256 * kSelUnroll ? 512 : 256;
+    // gather pass: one workgroup per tile, a tile in as few passes as possible (kSelUnroll vectors per lane and pass) --
+    // or, when there are too few tiles for the flagged ones to occupy the chip, several 256-lane workgroups per tile,
+    // each of which counts the tile's slot for itself
     const uint32_t cap = compact ? (uint32_t)cap_tiles : 0u;
+    constexpr uint32_t kSplitBelowTiles = 2048;     // measured: 27.4 -> 26.2 us at 576 tiles, 49.0 -> 48.4 at 1296, nothing at 6240
+    if (sh.NT <= kSplitBelowTiles && per_tile > 256 * kSelUnroll) {
+        const uint32_t parts = (uint32_t)((per_tile + 256 * kSelUnroll - 1) / (256 * kSelUnroll));
+        hipLaunchKernelGGL(select_gather_kernel<256>, dim3(sh.NT, parts < 8 ? parts : 8), dim3(256), 0, st, (const vec16*)v_cur,
+                           (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
+        return check_launch("select_gather_kernel");
+    }
+    const int threads = per_tile > 512 * kSelUnroll ? 1024 : per_tile > 256 * kSelUnroll ? 512 : 256;
     if (threads == 1024)
         hipLaunchKernelGGL(select_gather_kernel<1024>, dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur,
                            (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
