@@ -455,6 +455,43 @@ def test_proj_fused_other_shapes(oracle, N, H, d, P, grid, pairs, rank):
     _fused_case(oracle, N, D, H, d, P, grid, pairs, inp, ids, rank=rank, what=f"{N}x{D}")
 
 
+def _random_fused_shapes(count, seed):
+    """Seeded small shapes for the fused call: 1 to 3 grid axes of odd sizes (the last a multiple of 16 so that the token
+    count is), rotary pairs split unevenly over the axes (now and then an axis of one pair), heads of 64, 128 or 256."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        n_axes = int(rng.integers(1, 4))
+        d = int(rng.choice([64, 128, 256]))
+        H = int(rng.integers(3, 9)) if d < 256 else int(rng.integers(1, 4))
+        grid = tuple(int(rng.integers(1, 8)) for _ in range(n_axes - 1)) + (16 * int(rng.integers(1, 5)),)
+        N = int(np.prod(grid))
+        if N > 1536 or H * d < 192:
+            continue
+        cuts = np.sort(rng.choice(np.arange(1, d // 2), size=n_axes - 1, replace=False)) if n_axes > 1 else np.array([], dtype=int)
+        pairs = tuple(int(x) for x in np.diff(np.concatenate([[0], cuts, [d // 2]])))
+        if rng.random() < 0.25 and n_axes > 1:          # an axis of a single pair
+            pairs = (1,) + pairs[1:-1] + (pairs[-1] + pairs[0] - 1,) if n_axes > 2 else (1, d // 2 - 1)
+        P = int(rng.choice([p_ for p_ in (1, 2, 3, 4) if H % p_ == 0 and N % (16 * p_) == 0]))
+        out.append((N, H, d, P, grid, pairs))
+    return out
+
+
+@gpu
+@pytest.mark.parametrize("N,H,d,P,grid,pairs", _random_fused_shapes(10, 20260414))
+def test_proj_fused_random_small_shapes(oracle, N, H, d, P, grid, pairs):
+    from synth import f32_to_bf16_bits
+    assert sum(pairs) == d // 2 and int(np.prod(grid)) == N
+    D = H * d
+    rng = np.random.default_rng(N * 7 + d)
+    inp = {"X": f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32))}
+    for w in ("Wq", "Wk", "Wv"):
+        inp[w] = f32_to_bf16_bits(rng.standard_normal((D, D), dtype=np.float32) * np.float32(D ** -0.5))
+    for g_ in ("gamma_q", "gamma_k"):
+        inp[g_] = f32_to_bf16_bits((1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32))
+    _fused_case(oracle, N, D, H, d, P, grid, pairs, inp, np.arange(N), what=f"{N}x{D} grid {grid} pairs {pairs} P {P}")
+
+
 @gpu
 @pytest.mark.parametrize("N,H,d,grid,pairs,tile_tokens", [
     (9120, 24, 128, (48, 190), (32, 32), 224),          # 41 x 12 x 3 tiles of 224 tokens, the last row 160 tokens; table 63 KB in LDS
