@@ -8,6 +8,9 @@ head-parallel Q (normalised, rotated), K (same) and V, and the selection's flags
 
   fused0     one stream:  qkv_proj_fused(V, Q, K in one launch, V's tiles first: every tensor to its exchange buffer and to its
                           head-parallel tensor, norm + RoPE of Q and K in the epilogue) -> vmajor_select(V)
+  fused00    one stream:  qkv_proj_fused_select(V, Q, K in one launch: as fused0, and V compared with the previous step's V on its
+                          way out, so of the selection only the second pass is launched)
+  fused00v   one stream:  qkv_proj_fused_select(V) -> qkv_proj_fused(Q, K)
   fused0v    one stream:  qkv_proj_fused(V) -> qkv_proj_fused(Q, K) -> vmajor_select(V)
   fused0v2   two streams: main qkv_proj_fused(V) -> qkv_proj_fused(Q, K); side [after V's launch] vmajor_select(V); joined at the end
   fused1     one stream:  qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_select(V) -> a2a_unpack_norm_rope(Q, K)
@@ -15,9 +18,9 @@ head-parallel Q (normalised, rotated), K (same) and V, and the selection's flags
   fused2     two streams: main qkv_proj_pack(V) -> qkv_proj_pack(Q, K) -> a2a_unpack_norm_rope(Q, K);
                           side [after V's projection] a2a_unpack_select(V); joined at the end of the step
   fused3     three streams: V, Q, K projected by three launches of qkv_proj_pack, each tensor's unpack under the next projection
-(in fused0 / fused0v / fused0v2 the exchange buffers of Q and K carry normalised values -- norm + RoPE on the sending side, the paper's
+(in fused00 / fused00v / fused0 / fused0v / fused0v2 the exchange buffers of Q and K carry normalised values -- norm + RoPE on the sending side, the paper's
 order -- in the others the projection itself, normalised by the receiver's unpack).
-The default run times all seven with the same --warmup / --steps (three times each, interleaved, after a clock
+The default run times all nine with the same --warmup / --steps (three times each, interleaved, after a clock
 ramp: see time_headline) and reports each; `value` is the fastest one measured in this run (named in config.schedule).  Also timed and reported beside it: the same step through the five
 stand-alone calls only ("vfirst", two streams; "serial", one), the single-GPU direct form that writes V straight
 into the head-parallel layout ("fused1_vdirect": no exchange buffer for V), a HIP-graph replay of the headline
@@ -41,7 +44,7 @@ METRIC = "tokens/s per layer (QKV+norm+RoPE+pack); pack/select GB/s vs HBM peak"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "qkv_gemm_hbm_traffic.txt")
-HEADLINE_CANDIDATES = ("fused0", "fused0v", "fused0v2", "fused1", "fused1qkv", "fused2", "fused3")
+HEADLINE_CANDIDATES = ("fused00", "fused00v", "fused0", "fused0v", "fused0v2", "fused1", "fused1qkv", "fused2", "fused3")
 
 
 def measured_traffic(workload: str, form: str, kernel_tile: str, launches_per_step: int):
@@ -156,7 +159,8 @@ class Workload:
         self.hq, self.hk, self.hv = bf((H, N, d)), bf((H, N, d)), bf((H, N, d))
         self.NT = cfg.NT
         self.cap = self.NT
-        self.ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), cd.qkv_proj_fused_select_workspace_bytes(self.sh, T), 16),
+                              dtype=torch.uint8, device=dev)
         self.flags = torch.empty(self.NT, dtype=torch.int32, device=dev)
         self.idx = torch.empty(self.NT, dtype=torch.int32, device=dev)
         self.n_act = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -171,7 +175,7 @@ class Workload:
         v_prev_host, _ = perturb_tiles(self.bits(self.hv), 1, T, cfg.n_changed, np.random.default_rng(cfg.index), cfg.noise_sigma)
         self.hv_prev = up(v_prev_host)
         del v_prev_host
-        self.schedules = {"fused0": self.step_fused0, "fused0v": self.step_fused0v, "fused0v2": self.step_fused0v2, "fused1": self.step_fused1, "fused1qkv": self.step_fused1qkv, "fused2": self.step_fused2,
+        self.schedules = {"fused00": self.step_fused00, "fused00v": self.step_fused00v, "fused0": self.step_fused0, "fused0v": self.step_fused0v, "fused0v2": self.step_fused0v2, "fused1": self.step_fused1, "fused1qkv": self.step_fused1qkv, "fused2": self.step_fused2,
                           "fused2x": self.step_fused2x, "fused3": self.step_fused3, "fused3s": self.step_fused3s,
                           "fused1_vdirect": self.step_fused1_vdirect,
                           "vfirst": self.step_vfirst, "vfirst3": self.step_vfirst3, "serial": self.step_serial}
@@ -228,6 +232,22 @@ class Workload:
         self.proj(rec, st, lambda s: cd.qkv_proj_fused(sh, self.X, self.Wq, self.Wk, self.Wv, self.gq, self.gk, c.eps, self.rope,
                                                        self.bq, self.bk, self.bv, self.ORDER, self.hq, self.hk, self.hv, stream=s))
         self.select(st)
+
+    def step_fused00(self, rec=None):
+        cd, sh, st, c = self.cd, self.sh, self.s_main, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj_fused_select(sh, self.X, self.Wq, self.Wk, self.Wv, self.gq, self.gk, c.eps, self.rope,
+                                                              self.bq, self.bk, self.bv, self.ORDER, self.hq, self.hk, self.hv,
+                                                              self.hv_prev, c.tile_tokens, c.tau, self.flags, self.idx, self.n_act,
+                                                              self.compact, self.cap, self.ws, stream=s))
+
+    def step_fused00v(self, rec=None):
+        cd, sh, st, c = self.cd, self.sh, self.s_main, self.cfg
+        self.proj(rec, st, lambda s: cd.qkv_proj_fused_select(sh, self.X, None, None, self.Wv, None, None, c.eps, None,
+                                                              None, None, self.bv, self.ORDER, None, None, self.hv,
+                                                              self.hv_prev, c.tile_tokens, c.tau, self.flags, self.idx, self.n_act,
+                                                              self.compact, self.cap, self.ws, stream=s))
+        self.proj(rec, st, lambda s: cd.qkv_proj_fused(sh, self.X, self.Wq, self.Wk, None, self.gq, self.gk, c.eps, self.rope,
+                                                       self.bq, self.bk, None, self.ORDER, self.hq, self.hk, None, stream=s))
 
     def step_fused0v(self, rec=None):
         cd, sh, st, c = self.cd, self.sh, self.s_main, self.cfg

@@ -173,6 +173,29 @@ COCODIFF_API int cocodiff_qkv_proj_fused(const cocodiff_shape* shape, const coco
                                          cocodiff_bf16* q_hs, cocodiff_bf16* k_hs, cocodiff_bf16* v_hs, void* stream);
 
 /*
+ * cocodiff_qkv_proj_fused_select = cocodiff_qkv_proj_fused followed by cocodiff_vmajor_select on v_hs (head-parallel:
+ * S = H, W = d) against v_prev ([H][N][d], the previous step's V): with tile_tokens = 16 (the tile of Section III-D) the
+ * projection compares every vector of V with v_prev's as it writes it out, so the selection's first pass -- a read of
+ * both tensors -- does not run; the selection's second pass (list, count, compact copy) follows on the same stream.
+ * Bit-identical to the two calls in every output.  Other tile heights, or D above 4096, run as the two calls.
+ * wv, vbuf and v_hs are required (Q and K stay optional); the rank range of `shape` must be all P ranks (a tile's flag
+ * needs every head).  workspace: cocodiff_qkv_proj_fused_select_workspace_bytes(shape, tile_tokens) bytes (0 for bad
+ * arguments), 16-byte aligned; nothing in it needs clearing and nothing survives the call.  Other arguments and error
+ * behaviour as for the two calls.
+ */
+COCODIFF_API size_t cocodiff_qkv_proj_fused_select_workspace_bytes(const cocodiff_shape* shape, int32_t tile_tokens);
+COCODIFF_API int cocodiff_qkv_proj_fused_select(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                                const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                                const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                                const cocodiff_rope* rope,
+                                                cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, cocodiff_bf16* vbuf, int slot_order,
+                                                cocodiff_bf16* q_hs, cocodiff_bf16* k_hs, cocodiff_bf16* v_hs,
+                                                const cocodiff_bf16* v_prev, int32_t tile_tokens, float tau,
+                                                int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                                                cocodiff_bf16* compact, int32_t cap_tiles,
+                                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * cocodiff_a2a_unpack_select = cocodiff_a2a_unpack of V followed by cocodiff_vmajor_select on the unpacked tensor
  * (head-parallel: S = H, W = d): the selection's first pass reads the current values from the exchange buffer
  * vbuf, writes them to their place in v_hs [H][N][d] and compares them with v_prev on the way, so the unpacked

@@ -20,7 +20,8 @@ ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_CAPACITY, ERR_HIP = -1, -2, -3, -4, -5
 SEND_MAJOR, RECV_MAJOR = 0, 1
 
 EXPORTS = (
-    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qkv_proj_hs", "cocodiff_qkv_proj_fused", "cocodiff_qk_norm_rope_pack",
+    "cocodiff_qkv_proj", "cocodiff_qk_norm_rope", "cocodiff_qkv_proj_pack", "cocodiff_qkv_proj_hs", "cocodiff_qkv_proj_fused", "cocodiff_qkv_proj_fused_select",
+    "cocodiff_qkv_proj_fused_select_workspace_bytes", "cocodiff_qk_norm_rope_pack",
     "cocodiff_a2a_unpack_select", "cocodiff_a2a_unpack_norm_rope", "cocodiff_a2a_pack", "cocodiff_a2a_unpack",
     "cocodiff_vmajor_select", "cocodiff_vmajor_select_static", "cocodiff_vmajor_select_workspace_bytes", "cocodiff_vmajor_gather",
     "cocodiff_vmajor_scatter", "cocodiff_vmajor_token_metric", "cocodiff_vmajor_topk", "cocodiff_cache_active_count",
@@ -102,6 +103,11 @@ def lib() -> ctypes.CDLL:
         L.cocodiff_qkv_proj_plan.argtypes = [sp, i32, i32, vp, vp, vp, vp]
         L.cocodiff_qkv_proj_fused.argtypes = [sp, vp, vp, vp, vp, vp, vp, f32, rp, vp, vp, vp, ci, vp, vp, vp, vp]
         L.cocodiff_qkv_proj_fused.restype = ci
+        L.cocodiff_qkv_proj_fused_select.argtypes = [sp, vp, vp, vp, vp, vp, vp, f32, rp, vp, vp, vp, ci, vp, vp, vp,
+                                                     vp, i32, f32, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.cocodiff_qkv_proj_fused_select.restype = ci
+        L.cocodiff_qkv_proj_fused_select_workspace_bytes.argtypes = [sp, i32]
+        L.cocodiff_qkv_proj_fused_select_workspace_bytes.restype = sz
         L.cocodiff_qkv_proj_plan.restype = ci
         L.cocodiff_version.restype = ctypes.c_char_p
         L.cocodiff_last_error.restype = ctypes.c_char_p
@@ -272,6 +278,20 @@ def qkv_proj_fused(shape: Shape, x, wq, wk, wv, gamma_q, gamma_k, eps: float, ro
     _check(lib().cocodiff_qkv_proj_fused(ctypes.byref(shape), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(gamma_q), _ptr(gamma_k),
                                          float(eps), ctypes.byref(rope) if rope is not None else None, _ptr(qbuf), _ptr(kbuf),
                                          _ptr(vbuf), int(slot_order), _ptr(q_hs), _ptr(k_hs), _ptr(v_hs), _stream(stream)))
+
+
+def qkv_proj_fused_select_workspace_bytes(shape: Shape, tile_tokens: int = 16) -> int:
+    return int(lib().cocodiff_qkv_proj_fused_select_workspace_bytes(ctypes.byref(shape), int(tile_tokens)))
+
+
+def qkv_proj_fused_select(shape: Shape, x, wq, wk, wv, gamma_q, gamma_k, eps: float, rope: Optional[Rope], qbuf, kbuf, vbuf,
+                          slot_order: int, q_hs, k_hs, v_hs, v_prev, tile_tokens: int, tau: float, flags, active_idx, n_active,
+                          compact, cap_tiles: int, workspace, stream=None) -> None:
+    _check(lib().cocodiff_qkv_proj_fused_select(
+        ctypes.byref(shape), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(gamma_q), _ptr(gamma_k), float(eps),
+        ctypes.byref(rope) if rope is not None else None, _ptr(qbuf), _ptr(kbuf), _ptr(vbuf), int(slot_order), _ptr(q_hs),
+        _ptr(k_hs), _ptr(v_hs), _ptr(v_prev), int(tile_tokens), float(tau), _ptr(flags), _ptr(active_idx), _ptr(n_active),
+        _ptr(compact), int(cap_tiles), _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 
 def qkv_proj_plan(shape: Shape, n_tensors: int, whole_heads: bool = False) -> dict:

@@ -64,6 +64,13 @@ struct GemmArgs {
     // 2 pairs + 2 floats apart (the two extra floats spread consecutive rows over the banks), and the four arrays describe
     // that copy; axis x is pairs [tab_cum[x], ...) of the caller's table and tab_magic[x] = ceil(2^32 / pairs[x])
     // divides a pair index by the row length.  tab_lds == 0: the arrays describe the caller's table in global memory.
+    // The fused call that also flags V for the selection (sel_prev != nullptr): the previous step's V in the head-parallel
+    // layout, the decision's thresholds, and the flag records: 16 bytes per 16-token tile, byte c written by the workgroup
+    // of V's feature tile c.  sel_tiles = N / 16.
+    const uint16_t* sel_prev;
+    uint8_t* sel_flag_bytes;
+    Thresholds sel_th;
+    uint32_t sel_tiles;
     uint32_t tab_lds, row_base[3], row_stride[3], row_span[3], row_end[3], row_step16[3], tab_cum[3], tab_magic[3];
 };
 
@@ -196,6 +203,79 @@ __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lan
                 m -= a.Ns;
                 yc += wrap_c;
             }
+        }
+    }
+}
+
+// store_rows for V in the fused call when the selection's flags are wanted too (paper Section III-D): every vector on
+// its way out is compared with the previous step's vector at the same place of the head-parallel layout (the decision
+// of the selection's flag pass: one streaming compare per element, the exact rule for suspects), and the wavefront
+// notes per 16-token tile -- two consecutive row groups -- whether anything changed, in `changed_lds`
+// ([wavefront][tile]: one byte-sized word each).  Both destinations must be given.
+// prev_rows: the lane's vectors of the previous step's V, fetched by load_prev_rows before the tile was staged (one
+// trip to memory for the whole tile, under the staging work, instead of one per group of rows).
+template <uint32_t ROWS>
+__device__ __forceinline__ void load_prev_rows(vec16 (&prev_rows)[ROWS / 8], uint32_t lane, size_t row0, uint32_t tok0, uint32_t feat0,
+                                               uint32_t M, uint32_t D, const GemmArgs& a) {
+    const uint32_t c16 = lane % 8u, rsub = lane / 8u;
+    const uint32_t feat = min(feat0 + c16 * 8u, D - 8u);
+    const bool live = feat0 + c16 * 8u < D;
+    const uint32_t tok = tok0 + rsub, n = (uint32_t)row0 + tok, v8 = feat >> 3;
+    const uint32_t h = v8 / a.d8, ch = v8 - h * a.d8;
+    const vec16* yp = reinterpret_cast<const vec16*>(a.sel_prev) + ((size_t)h * a.N_all + n) * a.d8 + ch;
+#pragma unroll
+    for (uint32_t it = 0; it < ROWS / 8; ++it)
+        if (live && tok + 8u * it < M) prev_rows[it] = ld_nt(yp + (size_t)(8u * it) * a.d8);
+}
+
+template <uint32_t ROWS>
+__device__ __forceinline__ void store_rows_select(const unsigned char* ep, uint32_t lane, uint32_t wave, uint16_t* __restrict__ Y,
+                                                  uint16_t* __restrict__ Y2, size_t row0, uint32_t tok0, uint32_t feat0, uint32_t M,
+                                                  uint32_t D, const GemmArgs& a, uint32_t* changed_lds, const vec16 (&prev_rows)[ROWS / 8]) {
+    constexpr uint32_t COLS = 8, ROWB = EpilogueRows<COLS>::ROWB, RPI = 8;
+    static_assert(EpilogueRows<COLS>::CP == 8 && ROWS % 16 == 0, "eight rows per read instruction, whole 16-token tiles");
+    const uint32_t c16 = lane % 8u, rsub = lane / 8u;
+    const uint32_t feat = min(feat0 + c16 * 8u, D - 8u);         // lanes past the last feature idle on a valid address
+    const bool live = feat0 + c16 * 8u < D;
+    uint32_t tok = tok0 + rsub;
+    const uint32_t n = (uint32_t)row0 + tok, v8 = feat >> 3;
+    const uint32_t r = n / a.Ns, p = v8 / a.row8, c = v8 - p * a.row8;
+    uint32_t m = n - r * a.Ns;
+    const size_t slot = a.recv_major ? (size_t)p * a.P + r : (size_t)r * a.P + p;
+    vec16* yc = reinterpret_cast<vec16*>(Y) + slot * a.chunk8 + (size_t)m * a.row8 + c;
+    const size_t step_c = (size_t)RPI * a.row8, wrap_c = a.recv_major ? 0 : (size_t)(a.P - 1u) * a.chunk8;
+    const uint32_t h = v8 / a.d8, ch = v8 - h * a.d8;
+    const size_t hs_at = ((size_t)h * a.N_all + n) * a.d8 + ch;
+    vec16* yh = reinterpret_cast<vec16*>(Y2) + hs_at;
+    const size_t step_h = (size_t)RPI * a.d8;
+    bool changed = false;
+#pragma unroll
+    for (uint32_t it = 0; it < ROWS / RPI; ++it) {
+        if (live && tok < M) {
+            const uint32_t row = RPI * it + rsub;
+            const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & 7u)) << 4));
+            const vec16 pv = prev_rows[it];
+            *yc = v;
+            *yh = v;
+            if (vec_suspect(v, pv, a.sel_th.tau_s)) {
+                bool tie = false;
+                bool chg = vec_changed(v, pv, a.sel_th.tau, a.sel_th.tau_tie, tie);
+                if (tie && !chg) chg = vec_changed_double(v, pv, a.sel_th.tau);
+                changed |= chg;
+            }
+        }
+        tok += RPI;
+        yh += step_h;
+        yc += step_c;
+        m += RPI;
+        if (m >= a.Ns) {
+            m -= a.Ns;
+            yc += wrap_c;
+        }
+        if (it & 1u) {        // rows 16 (it/2) .. +15 are done: one tile of the selection
+            const bool any = __ballot(changed) != 0;
+            if (lane == 0) changed_lds[wave * (ROWS / 16u) + it / 2u] = any ? 1u : 0u;
+            changed = false;
         }
     }
 }
@@ -614,6 +694,30 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
         }
     }
     unsigned char* ep = smem + wave * kEpilogueBytes;
+    if constexpr (LAYOUT == OUT_FUSED) {
+        if (a.sel_prev && tc.tensor == 0) {     // V (the first tensor of the launch), flagged on its way out
+            static_assert(WAVES * kEpilogueBytes + WAVES * NJ * 4 <= ring_lds_bytes(TM, TN), "room for the wavefronts' verdicts");
+            uint32_t* verdicts = reinterpret_cast<uint32_t*>(smem + WAVES * kEpilogueBytes);      // [wavefront][tile of 16 tokens]
+            vec16 prev_rows[NJ * 2];
+            load_prev_rows<NJ * 16>(prev_rows, lane, (size_t)a.row_begin, tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
+            stage_tile16<NI, NJ>(acc, ep, lane);
+            store_rows_select<NJ * 16>(ep, lane, wave, a.y[0], a.y2[0], (size_t)a.row_begin, tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M,
+                                       (uint32_t)a.D, a, verdicts, prev_rows);
+            __syncthreads();
+            // one lane per 16-token tile of the workgroup's 2 NJ: the verdicts of the WN wavefronts that share its tokens
+            const uint32_t sel = threadIdx.x;
+            if (sel < 2u * NJ) {
+                const uint32_t half = sel / NJ, j = sel - half * NJ;
+                uint32_t any = 0;
+#pragma unroll
+                for (uint32_t wf = 0; wf < (uint32_t)WN; ++wf) any |= verdicts[(half * WN + wf) * NJ + j];
+                const uint32_t tok = tc.m0 + sel * 16u;
+                if (tok < (uint32_t)a.M)
+                    a.sel_flag_bytes[(size_t)(((uint32_t)a.row_begin + tok) / 16u) * 16u + tc.f0 / (uint32_t)TN] = (uint8_t)any;
+            }
+            return;
+        }
+    }
     stage_tile16<NI, NJ>(acc, ep, lane);
     store_rows<NI * 2, NJ * 16, LAYOUT>(ep, lane, a.y[tc.tensor], LAYOUT == OUT_FUSED ? a.y2[tc.tensor] : nullptr, (size_t)a.row_begin,
                                         tc.m0 + wave_t, tc.f0 + wave_f, (uint32_t)a.M, (uint32_t)a.D, a);
@@ -785,6 +889,10 @@ struct FusedExtras {
     const cocodiff_bf16* gamma[2];     // gamma_q, gamma_k
     float eps;
     RopeDev rope;
+    // V flagged for the selection on its way out (cocodiff_qkv_proj_fused_select): previous-step V, threshold, flag records
+    const cocodiff_bf16* sel_prev;
+    uint8_t* sel_flag_bytes;
+    float sel_tau;
 };
 
 static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
@@ -850,6 +958,10 @@ static int proj_launch(const cocodiff_shape* shape, const cocodiff_bf16* x,
     a.eps = fused ? fused->eps : 0.f;
     a.rope = fused ? fused->rope : RopeDev{};
     a.tab_lds = 0;
+    a.sel_prev = fused ? fused->sel_prev : nullptr;
+    a.sel_flag_bytes = fused ? fused->sel_flag_bytes : nullptr;
+    a.sel_th = make_thresholds(fused ? fused->sel_tau : 0.f);
+    a.sel_tiles = (uint32_t)shape->N / 16u;
     const int32_t Ns = shape->N / shape->P;
     a.row_begin = shape->rank_begin * Ns;
     a.M = shape->rank_count * Ns;
@@ -969,6 +1081,79 @@ extern "C" int cocodiff_qkv_proj_fused(const cocodiff_shape* shape, const cocodi
         if (rc != COCODIFF_OK) return rc;
     }
     return proj_launch(shape, x, wq, wk, wv, qbuf, kbuf, vbuf, OUT_FUSED, slot_order, stream, &f);
+}
+
+// Flag records of the projection that flags V: 16 bytes per 16-token tile, one byte per 256-feature tile of V.
+static bool flags_in_projection(const cocodiff_shape* shape, int32_t tile_tokens) {
+    return tile_tokens == 16 && (shape->D + 255) / 256 <= 16;
+}
+
+extern "C" size_t cocodiff_qkv_proj_fused_select_workspace_bytes(const cocodiff_shape* shape, int32_t tile_tokens) {
+    if (check_shape(shape) != COCODIFF_OK || tile_tokens <= 0 || shape->N % tile_tokens) return 0;
+    if (flags_in_projection(shape, tile_tokens)) return (size_t)(shape->N / 16) * 16;
+    return cocodiff_vmajor_select_workspace_bytes(shape->H, shape->N, shape->d, tile_tokens);
+}
+
+extern "C" int cocodiff_qkv_proj_fused_select(const cocodiff_shape* shape, const cocodiff_bf16* x,
+                                              const cocodiff_bf16* wq, const cocodiff_bf16* wk, const cocodiff_bf16* wv,
+                                              const cocodiff_bf16* gamma_q, const cocodiff_bf16* gamma_k, float eps,
+                                              const cocodiff_rope* rope,
+                                              cocodiff_bf16* qbuf, cocodiff_bf16* kbuf, cocodiff_bf16* vbuf, int slot_order,
+                                              cocodiff_bf16* q_hs, cocodiff_bf16* k_hs, cocodiff_bf16* v_hs,
+                                              const cocodiff_bf16* v_prev, int32_t tile_tokens, float tau,
+                                              int32_t* flags, int32_t* active_idx, int32_t* n_active,
+                                              cocodiff_bf16* compact, int32_t cap_tiles,
+                                              void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != COCODIFF_OK) return rc;
+    if (shape->rank_begin != 0 || shape->rank_count != shape->P)
+        return fail(COCODIFF_ERR_SHAPE, "qkv_proj_fused_select: a tile's flag needs every head, so the rank range must be all P ranks");
+    if (!wv || !vbuf || !v_hs)
+        return fail(COCODIFF_ERR_NULL, "qkv_proj_fused_select: wv, vbuf and v_hs are required (the selection reads V in the head-parallel layout)");
+    if (!v_prev || !active_idx || !n_active || !workspace)
+        return fail(COCODIFF_ERR_NULL, "qkv_proj_fused_select: v_prev, active_idx, n_active and workspace are required");
+    if (!aligned16(v_prev) || !aligned16(workspace) || !aligned16(compact))
+        return fail(COCODIFF_ERR_ALIGN, "qkv_proj_fused_select: tensors and workspace must be 16-byte aligned");
+    if (tile_tokens <= 0 || shape->N % tile_tokens)
+        return fail(COCODIFF_ERR_SHAPE, "qkv_proj_fused_select: N (%d) must be a multiple of tile_tokens (%d)", shape->N, tile_tokens);
+    if (compact && cap_tiles < 1) return fail(COCODIFF_ERR_CAPACITY, "qkv_proj_fused_select: cap_tiles (%d) must be >= 1", cap_tiles);
+    const size_t need = cocodiff_qkv_proj_fused_select_workspace_bytes(shape, tile_tokens);
+    if (workspace_bytes < need)
+        return fail(COCODIFF_ERR_CAPACITY, "qkv_proj_fused_select: workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
+    if (!flags_in_projection(shape, tile_tokens)) {
+        // other tile heights, or more than 16 feature tiles: the two calls this one stands for
+        rc = cocodiff_qkv_proj_fused(shape, x, wq, wk, wv, gamma_q, gamma_k, eps, rope, qbuf, kbuf, vbuf, slot_order, q_hs, k_hs, v_hs, stream);
+        if (rc != COCODIFF_OK) return rc;
+        return cocodiff_vmajor_select(shape->H, shape->N, shape->d, tile_tokens, v_hs, v_prev, tau, flags, active_idx, n_active, compact,
+                                      cap_tiles, workspace, workspace_bytes, stream);
+    }
+    if (shape->d != 64 && shape->d != 128 && shape->d != 256)
+        return fail(COCODIFF_ERR_SHAPE, "qkv_proj_fused: d (%d) must be 64, 128 or 256 (a head row must fill whole wavefront tiles of 64 features)", shape->d);
+    FusedExtras f{};
+    f.hs[0] = q_hs;
+    f.hs[1] = k_hs;
+    f.hs[2] = v_hs;
+    f.gamma[0] = gamma_q;
+    f.gamma[1] = gamma_k;
+    f.eps = eps;
+    f.sel_prev = v_prev;
+    f.sel_flag_bytes = static_cast<uint8_t*>(workspace);
+    f.sel_tau = tau;
+    if (wq || wk) {
+        rc = fill_rope(shape, rope, "qkv_proj_fused_select", &f.rope);
+        if (rc != COCODIFF_OK) return rc;
+    }
+    rc = proj_launch(shape, x, wq, wk, wv, qbuf, kbuf, vbuf, OUT_FUSED, slot_order, stream, &f);
+    if (rc != COCODIFF_OK) return rc;
+    TileFlags tf;
+    tf.words_ptr = static_cast<const uint32_t*>(workspace);
+    tf.words = 4;
+    const uint32_t parts = (uint32_t)(shape->D + 255) / 256u;        // bytes of a record that the projection wrote
+    for (uint32_t w = 0; w < 4; ++w) {
+        const uint32_t n = parts > 4 * w ? (parts - 4 * w < 4 ? parts - 4 * w : 4u) : 0u;
+        tf.mask[w] = n >= 4 ? 0xffffffffu : (1u << (8 * n)) - 1u;
+    }
+    return select_finish_launch(shape->H, shape->N, shape->d, tile_tokens, v_hs, tf, flags, active_idx, n_active, compact, cap_tiles, stream);
 }
 
 extern "C" int cocodiff_qkv_proj_plan(const cocodiff_shape* shape, int32_t n_tensors, int32_t whole_heads, int32_t* tile_tokens,

@@ -112,4 +112,83 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
+
+// ---- the selection's decision (used by the flag pass and by the projection that flags V on its way out) ----------
+
+// The decision is NOT(|double(c) - double(p)| <= double(tau)).  The fp32 difference d = fl(c - p) decides it whenever
+// |d| != tau (rounding is monotonic and tau is an fp32 value: |x| <= tau gives |d| <= tau, |d| > tau gives |x| > tau);
+// only |d| == tau can hide a difference that exceeds tau by less than half an fp32 ulp, and only vectors with such a
+// tie and no change are compared again in double.
+//   vec_suspect: one compare per element for the streaming loop, NOT(|d| < tau_s): true for every change and every tie
+//                (tau_s = tau, or the smallest positive fp32 when tau is 0, so that equal values are no suspects);
+//   vec_changed: the fp32 decision plus a note of ties (tau_tie = tau, or NaN when tau is 0: a zero fp32 difference of
+//                two bf16 values is exactly zero).
+__device__ __forceinline__ bool vec_suspect(const vec16& c, const vec16& p, float tau_s) {
+    const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+    const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
+    bool suspect = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        suspect |= !(fabsf(bf16_lo(cw[i]) - bf16_lo(pw[i])) < tau_s);
+        suspect |= !(fabsf(bf16_hi(cw[i]) - bf16_hi(pw[i])) < tau_s);
+    }
+    return suspect;
+}
+
+__device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, float tau, float tau_tie, bool& tie) {
+    const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+    const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
+    bool changed = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float dl = fabsf(bf16_lo(cw[i]) - bf16_lo(pw[i]));
+        const float dh = fabsf(bf16_hi(cw[i]) - bf16_hi(pw[i]));
+        changed |= !(dl <= tau);
+        changed |= !(dh <= tau);
+        tie |= dl == tau_tie;
+        tie |= dh == tau_tie;
+    }
+    return changed;
+}
+
+__device__ __forceinline__ bool vec_changed_double(const vec16& c, const vec16& p, float tau) {
+    const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
+    const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
+    const double tau_d = (double)tau;
+    bool changed = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        changed |= !(fabs((double)bf16_lo(cw[i]) - (double)bf16_lo(pw[i])) <= tau_d);
+        changed |= !(fabs((double)bf16_hi(cw[i]) - (double)bf16_hi(pw[i])) <= tau_d);
+    }
+    return changed;
+}
+
+struct Thresholds {
+    float tau, tau_s, tau_tie;   // see vec_suspect / vec_changed
+};
+
+inline Thresholds make_thresholds(float tau) {
+    Thresholds th;
+    th.tau = tau;
+    th.tau_s = tau > 0.f ? tau : (tau == 0.f ? __builtin_bit_cast(float, 1u) : tau);
+    th.tau_tie = tau > 0.f ? tau : __builtin_nanf("");
+    return th;
+}
+
+// Flag records of the selection: `words` 32-bit words per tile (1 or 4), of which the bytes set in mask[] were
+// written, each by one workgroup of whichever pass produced the flags; a tile is active if any of them is non-zero.
+struct TileFlags {
+    const uint32_t* words_ptr;
+    uint32_t words;
+    uint32_t mask[4];
+};
+
+// Second pass of the selection on `stream`: list, count, optional per-tile flags and the compact copy of v_cur's
+// active tiles, from flag records some earlier kernel on the same stream wrote.  Arguments as cocodiff_vmajor_select
+// (validated there or by the caller).
+int select_finish_launch(int32_t S, int32_t N, int32_t W, int32_t tile_tokens, const cocodiff_bf16* v_cur, TileFlags tf,
+                         int32_t* flags, int32_t* active_idx, int32_t* n_active, cocodiff_bf16* compact, int32_t cap_tiles,
+                         void* stream);
+
 }  // namespace cocodiff

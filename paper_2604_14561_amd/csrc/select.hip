@@ -45,59 +45,6 @@ struct SelectShape {
     uint64_t slab8;         // vectors per slab = N*W/8
 };
 
-// The decision is NOT(|double(c) - double(p)| <= double(tau)).  The fp32 difference d = fl(c - p) decides it whenever
-// |d| != tau (rounding is monotonic and tau is an fp32 value: |x| <= tau gives |d| <= tau, |d| > tau gives |x| > tau);
-// only |d| == tau can hide a difference that exceeds tau by less than half an fp32 ulp, and only vectors with such a
-// tie and no change are compared again in double.
-//   vec_suspect: one compare per element for the streaming loop, NOT(|d| < tau_s): true for every change and every tie
-//                (tau_s = tau, or the smallest positive fp32 when tau is 0, so that equal values are no suspects);
-//   vec_changed: the fp32 decision plus a note of ties (tau_tie = tau, or NaN when tau is 0: a zero fp32 difference of
-//                two bf16 values is exactly zero).
-__device__ __forceinline__ bool vec_suspect(const vec16& c, const vec16& p, float tau_s) {
-    const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
-    const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
-    bool suspect = false;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        suspect |= !(fabsf(bf16_lo(cw[i]) - bf16_lo(pw[i])) < tau_s);
-        suspect |= !(fabsf(bf16_hi(cw[i]) - bf16_hi(pw[i])) < tau_s);
-    }
-    return suspect;
-}
-
-__device__ __forceinline__ bool vec_changed(const vec16& c, const vec16& p, float tau, float tau_tie, bool& tie) {
-    const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
-    const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
-    bool changed = false;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float dl = fabsf(bf16_lo(cw[i]) - bf16_lo(pw[i]));
-        const float dh = fabsf(bf16_hi(cw[i]) - bf16_hi(pw[i]));
-        changed |= !(dl <= tau);
-        changed |= !(dh <= tau);
-        tie |= dl == tau_tie;
-        tie |= dh == tau_tie;
-    }
-    return changed;
-}
-
-__device__ __forceinline__ bool vec_changed_double(const vec16& c, const vec16& p, float tau) {
-    const uint32_t cw[4] = {c.x, c.y, c.z, c.w};
-    const uint32_t pw[4] = {p.x, p.y, p.z, p.w};
-    const double tau_d = (double)tau;
-    bool changed = false;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        changed |= !(fabs((double)bf16_lo(cw[i]) - (double)bf16_lo(pw[i])) <= tau_d);
-        changed |= !(fabs((double)bf16_hi(cw[i]) - (double)bf16_hi(pw[i])) <= tau_d);
-    }
-    return changed;
-}
-
-struct Thresholds {
-    float tau, tau_s, tau_tie;   // see vec_suspect / vec_changed
-};
-
 // Where the current tensor comes from when the flag pass also does the receiver-side unpack of the first
 // all-to-all: the exchange buffer, chunk (sender r -> receiver p) = [Ns tokens][Hp heads][d].
 struct UnpackSource {
@@ -231,22 +178,29 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* wave_tot) {
     return tot;
 }
 
-// Workgroup t: if tile t is flagged (any of the bytes of its flag word that the flag pass wrote, `mask`), its
-// list slot is the number of flagged tiles before it.
-template <int THREADS>
-__global__ void __launch_bounds__(THREADS) select_gather_kernel(const vec16* __restrict__ cur, const uint32_t* __restrict__ tile_flag,
-                                                                    uint32_t mask, int32_t* __restrict__ user_flags,
+// Is tile t active by its flag record (WORDS words, the bytes in f.mask written by the pass before)?
+template <int WORDS>
+__device__ __forceinline__ bool tile_active(const TileFlags& f, uint32_t t) {
+    if (WORDS == 1) return (f.words_ptr[t] & f.mask[0]) != 0;
+    const uint4 w = reinterpret_cast<const uint4*>(f.words_ptr)[t];
+    return ((w.x & f.mask[0]) | (w.y & f.mask[1]) | (w.z & f.mask[2]) | (w.w & f.mask[3])) != 0;
+}
+
+// Workgroup t: if tile t is flagged, its list slot is the number of flagged tiles before it.
+template <int THREADS, int WORDS>
+__global__ void __launch_bounds__(THREADS) select_gather_kernel(const vec16* __restrict__ cur, TileFlags tf,
+                                                                    int32_t* __restrict__ user_flags,
                                                                     int32_t* __restrict__ idx, int32_t* __restrict__ n_active,
                                                                     vec16* __restrict__ compact, SelectShape sh, uint32_t cap_tiles) {
     __shared__ uint32_t wave_tot[THREADS / 64];
     const uint32_t t = blockIdx.x;
-    const bool mine = (tile_flag[t] & mask) != 0;
+    const bool mine = tile_active<WORDS>(tf, t);
     const bool last = t + 1 == sh.NT;
     const bool lead = blockIdx.y == 0;        // with several workgroups per tile (gridDim.y), the first one also writes the lists
     if (user_flags && lead && threadIdx.x == 0) user_flags[t] = mine ? 1 : 0;
     if (!mine && !(last && lead)) return;
     uint32_t before = 0;
-    for (uint32_t u = threadIdx.x; u < t; u += THREADS) before += (tile_flag[u] & mask) != 0 ? 1u : 0u;
+    for (uint32_t u = threadIdx.x; u < t; u += THREADS) before += tile_active<WORDS>(tf, u) ? 1u : 0u;
     const uint32_t slot = block_sum<THREADS>(before, wave_tot);
     if (lead && threadIdx.x == 0) {
         if (mine) idx[slot] = (int32_t)t;
@@ -320,6 +274,46 @@ static int select_shape(int32_t S, int32_t N, int32_t W, int32_t T, SelectShape*
     return COCODIFF_OK;
 }
 
+template <int WORDS>
+static void gather_launch(const SelectShape& sh, hipStream_t st, const cocodiff_bf16* v_cur, const TileFlags& tf, int32_t* flags,
+                          int32_t* active_idx, int32_t* n_active, cocodiff_bf16* compact, uint32_t cap) {
+    // one workgroup per tile, a tile in as few passes as possible (kSelUnroll vectors per lane and pass) -- or, when
+    // there are too few tiles for the flagged ones to occupy the chip, several 256-lane workgroups per tile, each of
+    // which counts the tile's slot for itself
+    const uint32_t per_tile = sh.S * sh.seg8;
+    constexpr uint32_t kSplitBelowTiles = 2048;     // measured: 27.4 -> 26.2 us at 576 tiles, 49.0 -> 48.4 at 1296, nothing at 6240
+    if (sh.NT <= kSplitBelowTiles && per_tile > 256 * kSelUnroll) {
+        const uint32_t parts = (uint32_t)((per_tile + 256 * kSelUnroll - 1) / (256 * kSelUnroll));
+        hipLaunchKernelGGL((select_gather_kernel<256, WORDS>), dim3(sh.NT, parts < 8 ? parts : 8), dim3(256), 0, st, (const vec16*)v_cur,
+                           tf, flags, active_idx, n_active, (vec16*)compact, sh, cap);
+        return;
+    }
+    const int threads = per_tile > 512 * kSelUnroll ? 1024 : per_tile > 256 * kSelUnroll ? 512 : 256;
+    if (threads == 1024)
+        hipLaunchKernelGGL((select_gather_kernel<1024, WORDS>), dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur, tf, flags,
+                           active_idx, n_active, (vec16*)compact, sh, cap);
+    else if (threads == 512)
+        hipLaunchKernelGGL((select_gather_kernel<512, WORDS>), dim3(sh.NT), dim3(512), 0, st, (const vec16*)v_cur, tf, flags,
+                           active_idx, n_active, (vec16*)compact, sh, cap);
+    else
+        hipLaunchKernelGGL((select_gather_kernel<256, WORDS>), dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur, tf, flags,
+                           active_idx, n_active, (vec16*)compact, sh, cap);
+}
+
+int select_finish_launch(int32_t S, int32_t N, int32_t W, int32_t tile_tokens, const cocodiff_bf16* v_cur, TileFlags tf,
+                         int32_t* flags, int32_t* active_idx, int32_t* n_active, cocodiff_bf16* compact, int32_t cap_tiles,
+                         void* stream) {
+    SelectShape sh;
+    int rc = select_shape(S, N, W, tile_tokens, &sh);
+    if (rc != COCODIFF_OK) return rc;
+    const uint32_t cap = compact ? (uint32_t)cap_tiles : 0u;
+    if (tf.words == 1)
+        gather_launch<1>(sh, as_stream(stream), v_cur, tf, flags, active_idx, n_active, compact, cap);
+    else
+        gather_launch<4>(sh, as_stream(stream), v_cur, tf, flags, active_idx, n_active, compact, cap);
+    return check_launch("select_gather_kernel");
+}
+
 }  // namespace cocodiff
 
 using namespace cocodiff;
@@ -366,9 +360,7 @@ static int select_launch(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
     fp.flag_bytes = (uint8_t*)tile_flag;
     fp.sh = sh;
     fp.share = share;
-    fp.th.tau = tau;
-    fp.th.tau_s = tau > 0.f ? tau : (tau == 0.f ? __builtin_bit_cast(float, 1u) : tau);
-    fp.th.tau_tie = tau > 0.f ? tau : __builtin_nanf("");
+    fp.th = make_thresholds(tau);
     fp.u = from_buf ? *from_buf : UnpackSource{};
     // the fast form: multiply-high division is exact while (largest dividend) * divisor < 2^32; 32-bit byte offsets
     // need every tensor below 4 GiB
@@ -393,28 +385,12 @@ static int select_launch(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,
     });
     rc = check_launch("select_flag_kernel");
     if (rc != COCODIFF_OK) return rc;
-    // gather pass: one workgroup per tile, a tile in as few passes as possible (kSelUnroll vectors per lane and pass) --
-    // or, when there are too few tiles for the flagged ones to occupy the chip, several 256-lane workgroups per tile,
-    // each of which counts the tile's slot for itself
-    const uint32_t cap = compact ? (uint32_t)cap_tiles : 0u;
-    constexpr uint32_t kSplitBelowTiles = 2048;     // measured: 27.4 -> 26.2 us at 576 tiles, 49.0 -> 48.4 at 1296, nothing at 6240
-    if (sh.NT <= kSplitBelowTiles && per_tile > 256 * kSelUnroll) {
-        const uint32_t parts = (uint32_t)((per_tile + 256 * kSelUnroll - 1) / (256 * kSelUnroll));
-        hipLaunchKernelGGL(select_gather_kernel<256>, dim3(sh.NT, parts < 8 ? parts : 8), dim3(256), 0, st, (const vec16*)v_cur,
-                           (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
-        return check_launch("select_gather_kernel");
-    }
-    const int threads = per_tile > 512 * kSelUnroll ? 1024 : per_tile > 256 * kSelUnroll ? 512 : 256;
-    if (threads == 1024)
-        hipLaunchKernelGGL(select_gather_kernel<1024>, dim3(sh.NT), dim3(1024), 0, st, (const vec16*)v_cur,
-                           (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
-    else if (threads == 512)
-        hipLaunchKernelGGL(select_gather_kernel<512>, dim3(sh.NT), dim3(512), 0, st, (const vec16*)v_cur,
-                           (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
-    else
-        hipLaunchKernelGGL(select_gather_kernel<256>, dim3(sh.NT), dim3(256), 0, st, (const vec16*)v_cur,
-                           (const uint32_t*)tile_flag, mask, flags, active_idx, n_active, (vec16*)compact, sh, cap);
-    return check_launch("select_gather_kernel");
+    TileFlags tf;
+    tf.words_ptr = tile_flag;
+    tf.words = 1;
+    tf.mask[0] = mask;
+    tf.mask[1] = tf.mask[2] = tf.mask[3] = 0;
+    return select_finish_launch(S, N, W, tile_tokens, v_cur, tf, flags, active_idx, n_active, compact, cap_tiles, stream);
 }
 
 extern "C" int cocodiff_vmajor_select(int32_t S, int32_t N, int32_t W, int32_t tile_tokens,

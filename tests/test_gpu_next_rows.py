@@ -683,6 +683,131 @@ def test_unpack_select_equals_unpack_then_select(oracle, name, order):
                              None, NT, ws)
 
 
+def _fused_select_case(oracle, N, D, H, d, P, grid, pairs, inp, T, tau, n_changed, order, cap=None, sparse=False, what=""):
+    """cocodiff_qkv_proj_fused_select against cocodiff_qkv_proj_fused followed by cocodiff_vmajor_select: every output
+    bit for bit; the selection also against the oracle on the GPU's V."""
+    import torch
+    from synth import perturb_tiles
+    sh = cd.Shape.make(N, D, H, d, P)
+    NT = N // T
+    cap = NT if cap is None else cap
+    table = torch.from_numpy(cd.rope_table(grid, pairs, 10000.0)).to("cuda:0")
+    rope = cd.Rope.make(grid, pairs, 10000.0, table.data_ptr())
+    X, Wq, Wk, Wv = (to_dev(inp[k_]) for k_ in ("X", "Wq", "Wk", "Wv"))
+    gq, gk = to_dev(inp["gamma_q"]), to_dev(inp["gamma_k"])
+    eps = 1e-6
+    # previous-step V: this step's V with some tiles perturbed
+    v0 = dev_empty((H, N, d))
+    cd.qkv_proj_hs(sh, X, None, None, Wv, None, None, v0)
+    _sync()
+    cur = to_host_bits(v0)
+    rng = np.random.default_rng(N + 3 * T)
+    if sparse:      # one element of one head differs per changed tile: the flag must come from a single lane
+        prev = cur.copy()
+        changed = np.sort(rng.permutation(NT)[:n_changed]).astype(np.int32)
+        for t_ in changed:
+            h_, n_, i_ = int(rng.integers(H)), int(t_) * T + int(rng.integers(T)), int(rng.integers(d))
+            prev[h_, n_, i_] ^= 0x4000        # flips the exponent's second bit: far apart
+    else:
+        prev, changed = perturb_tiles(cur, 1, T, n_changed, rng, 0.05)
+    prev_d = to_dev(prev)
+    outs = []
+    for one_call in (False, True):
+        bufs = [dev_empty((N * D,)) for _ in range(3)]
+        hss = [dev_empty((H, N, d)) for _ in range(3)]
+        flags, idx, n_act = dev_empty((NT,), "i32"), dev_empty((NT,), "i32"), dev_empty((1,), "i32")
+        compact = dev_empty((H, cap * T, d))
+        for t_ in bufs + hss + [flags, idx, compact]:
+            t_.fill_(-1)
+        if one_call:
+            ws = torch.empty(max(cd.qkv_proj_fused_select_workspace_bytes(sh, T), 16), dtype=torch.uint8, device="cuda:0")
+            ws.fill_(0xA5)                       # nothing in it needs clearing
+            cd.qkv_proj_fused_select(sh, X, Wq, Wk, Wv, gq, gk, eps, rope, bufs[0], bufs[1], bufs[2], order, hss[0], hss[1], hss[2],
+                                     prev_d, T, tau, flags, idx, n_act, compact, cap, ws)
+        else:
+            ws = torch.empty(max(cd.vmajor_select_workspace_bytes(H, N, d, T), 16), dtype=torch.uint8, device="cuda:0")
+            cd.qkv_proj_fused(sh, X, Wq, Wk, Wv, gq, gk, eps, rope, bufs[0], bufs[1], bufs[2], order, hss[0], hss[1], hss[2])
+            cd.vmajor_select(H, N, d, T, hss[2], prev_d, tau, flags, idx, n_act, compact, cap, ws)
+        _sync()
+        n = int(n_act.cpu()[0])
+        outs.append(([to_host_bits(t_) for t_ in bufs + hss], flags.cpu().numpy(), idx.cpu().numpy()[:min(n, NT)], n,
+                     to_host_bits(compact)[:, :min(n, cap) * T]))
+    a, b = outs
+    for k_ in range(6):
+        assert np.array_equal(a[0][k_], b[0][k_]), f"{what}: tensor {k_} differs between the two forms"
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2]) and a[3] == b[3], f"{what}: flags / list / count differ"
+    assert np.array_equal(a[4], b[4]), f"{what}: compact differs"
+    assert np.array_equal(b[0][5], cur)
+    o_flags, o_idx, o_n, o_comp = oracle.vmajor_select(cur, prev, tau, T)
+    assert b[3] == o_n and np.array_equal(b[2], o_idx[:o_n]) and np.array_equal(b[1], o_flags), f"{what}: selection differs from the oracle"
+    assert np.array_equal(b[4], o_comp[:, :min(o_n, cap) * T])
+    if tau > 0 and tau < 0.01:
+        assert o_n == len(changed) and np.array_equal(o_idx[:o_n], np.sort(changed))
+    return o_n
+
+
+@gpu
+@pytest.mark.parametrize("name,order", [("C1", 0), ("C2", 1), ("C3", 1), ("C4", 0), ("C5", 1)])
+def test_proj_fused_select_equals_the_two_calls(oracle, name, order):
+    from synth import make_layer_inputs
+    cfg = CONFIGS[name]
+    print(f"fused_select {name}", flush=True)
+    inp = make_layer_inputs(cfg)
+    n = _fused_select_case(oracle, cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, cfg.grid, cfg.pairs, inp, cfg.tile_tokens, cfg.tau, cfg.n_changed,
+                           order, what=name)
+    assert n == cfg.n_changed
+
+
+@gpu
+@pytest.mark.parametrize("N,H,d,P,grid,pairs,T,tau,n_changed,cap,sparse", [
+    (272, 4, 64, 1, (17, 16), (16, 16), 16, 1e-3, 5, None, False),       # ragged token tile (272 = 192 + 80)
+    (528, 3, 256, 1, (22, 24), (64, 64), 16, 1e-3, 33, 7, False),        # list longer than the compact buffer
+    (96, 5, 64, 1, (2, 4, 12), (10, 11, 11), 16, 1e-3, 6, None, False),  # D = 320: ragged feature tile, two flag bytes per tile
+    (512, 4, 128, 4, (16, 32), (40, 24), 16, 1e-3, 32, None, True),      # every tile changed, each in one element only
+    (512, 4, 128, 4, (16, 32), (40, 24), 16, 1e-3, 0, None, False),      # nothing changed
+    (512, 4, 128, 2, (16, 32), (40, 24), 16, 0.0, 9, None, True),        # threshold 0
+    (512, 4, 128, 2, (16, 32), (40, 24), 16, float("inf"), 9, None, False),   # nothing exceeds an infinite threshold
+    (512, 4, 128, 2, (16, 32), (40, 24), 16, float("nan"), 9, None, False),   # NaN: every tile is active
+    (512, 4, 128, 2, (16, 32), (40, 24), 32, 1e-3, 5, None, False),      # another tile height: runs as the two calls
+    (256, 72, 64, 1, (16, 16), (16, 16), 16, 1e-3, 4, None, True),       # D = 4608: more than 16 feature tiles, the two calls again
+])
+def test_proj_fused_select_other_shapes(oracle, N, H, d, P, grid, pairs, T, tau, n_changed, cap, sparse):
+    from synth import f32_to_bf16_bits
+    D = H * d
+    rng = np.random.default_rng(N + d + T)
+    inp = {"X": f32_to_bf16_bits(rng.standard_normal((N, D), dtype=np.float32))}
+    for w in ("Wq", "Wk", "Wv"):
+        inp[w] = f32_to_bf16_bits(rng.standard_normal((D, D), dtype=np.float32) * np.float32(D ** -0.5))
+    for g_ in ("gamma_q", "gamma_k"):
+        inp[g_] = f32_to_bf16_bits((1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32))
+    _fused_select_case(oracle, N, D, H, d, P, grid, pairs, inp, T, tau, n_changed, cd.RECV_MAJOR, cap=cap, sparse=sparse,
+                       what=f"{N}x{D} T={T} tau={tau}")
+
+
+@gpu
+def test_proj_fused_select_argument_errors():
+    import torch
+    cfg = CONFIGS["C1"]
+    sh = cd.Shape.make(cfg.N, cfg.D, cfg.H, cfg.d, cfg.P)
+    t = lambda *shape: dev_empty(shape)
+    X, W, g = t(cfg.N, cfg.D), t(cfg.D, cfg.D), t(cfg.d)
+    buf, hs = t(cfg.N * cfg.D), t(cfg.H, cfg.N, cfg.d)
+    table = torch.from_numpy(cd.rope_table(cfg.grid, cfg.pairs, cfg.theta)).to("cuda:0")
+    rope = cd.Rope.make(cfg.grid, cfg.pairs, cfg.theta, table.data_ptr())
+    idx, n_act = dev_empty((cfg.NT,), "i32"), dev_empty((1,), "i32")
+    ws = torch.empty(cd.qkv_proj_fused_select_workspace_bytes(sh, 16), dtype=torch.uint8, device="cuda:0")
+    assert ws.numel() == cfg.NT * 16
+    ok = dict(shape=sh, x=X, wq=None, wk=None, wv=W, gamma_q=None, gamma_k=None, eps=1e-6, rope=None, qbuf=None, kbuf=None, vbuf=buf,
+              slot_order=cd.SEND_MAJOR, q_hs=None, k_hs=None, v_hs=hs, v_prev=hs, tile_tokens=16, tau=0.1, flags=None, active_idx=idx,
+              n_active=n_act, compact=None, cap_tiles=0, workspace=ws)
+    cd.qkv_proj_fused_select(**ok)                                   # V alone, index-only: fine
+    for bad in (dict(wv=None), dict(v_hs=None), dict(vbuf=None), dict(v_prev=None), dict(active_idx=None), dict(tile_tokens=24),
+                dict(shape=cd.Shape.make(cfg.N, cfg.D, cfg.H, cfg.d, cfg.P, 0, 1)), dict(workspace=ws[:16]), dict(compact=hs, cap_tiles=0)):
+        with pytest.raises(cd.CocodiffError):
+            cd.qkv_proj_fused_select(**{**ok, **bad})
+    _sync()
+
+
 def test_cache_schedule_host_arithmetic(oracle):
     for n_tokens in (9216, 900, 99840, 7):
         for step in range(1, 51):
