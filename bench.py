@@ -50,7 +50,7 @@ HEADLINE_CANDIDATES = ("fused00", "fused00v", "fused0", "fused0v", "fused0v2", "
 def measured_traffic(workload: str, form: str, kernel_tile: str, launches_per_step: int):
     """Bytes per launch that crossed the L2 <-> memory-fabric boundary for the projection kernel, from the
     committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs of this script's --profile-projection mode);
-    None if the summary has no line for this workload, this kernel form ("plain" / "fused"), this tile shape and
+    None if the summary has no line for this workload, this kernel form ("plain" / "fused" / "fused_select"), this tile shape and
     this number of launches per step (a summary of another kernel form does not count)."""
     try:
         with open(TRAFFIC_FILE) as f:
@@ -511,9 +511,10 @@ def roofline_of(w, schedule, steps):
     flops_per_launch = 2.0 * cfg.N * (3 * cfg.D) * cfg.D / per_step
     achieved = flops_per_launch / us / 1e6
     fused = schedule.startswith("fused0")
+    form = "fused_select" if schedule.startswith("fused00") else "fused" if fused else "plain"
     tile = w.tile_name(3 if per_step == 1 else 2, fused)
     return {"kernel": "qkv_gemm_direct_kernel" + (" (norm + RoPE epilogue, two destinations)" if fused else ""), "tile": tile, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(cfg.name, "fused" if fused else "plain", tile, int(round(per_step))),
+            "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(cfg.name, form, tile, int(round(per_step))),
             "avg_launch_us": round(us, 2), "launches_per_step": round(per_step, 2), "event_steps": steps,
             "ms_per_step_instrumented": round(ms_instr, 4)}
 
@@ -532,6 +533,9 @@ def main() -> int:
                     help="profiling aid for rocprofv3 counter runs: N launches each of the projection with one, two and three "
                          "weights (exchange-buffer epilogue), of the fused form with three weights, of a2a_unpack_select and "
                          "vmajor_select, and of a 1000 MiB calibration copy, and nothing else")
+    ap.add_argument("--profile-fused-select", action="store_true",
+                    help="with --profile-projection: launch cocodiff_qkv_proj_fused_select instead (V alone, then V, Q and K), "
+                         "its selection pass and the calibration copy")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs all P logical ranks of the path on ONE GPU; "
@@ -563,7 +567,14 @@ def main() -> int:
         big = 1000 << 20
         src_big = torch.empty(big + (3 << 20), dtype=torch.uint8, device=dev)
         dst_big = torch.empty(big, dtype=torch.uint8, device=dev)
-        for _ in range(args.profile_projection):
+        c_ = cfg
+        for _ in range(args.profile_projection if args.profile_fused_select else 0):
+            cd.qkv_proj_fused_select(w.sh, w.X, None, None, w.Wv, None, None, c_.eps, None, None, None, w.bv, w.ORDER, None, None, w.hv,
+                                     w.hv_prev, c_.tile_tokens, c_.tau, w.flags, w.idx, w.n_act, w.compact, w.cap, w.ws)
+            cd.qkv_proj_fused_select(w.sh, w.X, w.Wq, w.Wk, w.Wv, w.gq, w.gk, c_.eps, w.rope, w.bq, w.bk, w.bv, w.ORDER, w.hq, w.hk, w.hv,
+                                     w.hv_prev, c_.tile_tokens, c_.tau, w.flags, w.idx, w.n_act, w.compact, w.cap, w.ws)
+            cd.util_copy(src_big, dst_big, big)
+        for _ in range(0 if args.profile_fused_select else args.profile_projection):
             cd.qkv_proj_pack(w.sh, w.X, None, None, w.Wv, None, None, w.bv, w.ORDER)
             cd.qkv_proj_pack(w.sh, w.X, w.Wq, w.Wk, None, w.bq, w.bk, None, w.ORDER)
             cd.qkv_proj_pack(w.sh, w.X, w.Wq, w.Wk, w.Wv, w.bq, w.bk, w.bv, w.ORDER)
