@@ -430,9 +430,13 @@ class Workload:
         rec.spans = []
         step_fn(rec)                               # counts the projection launches of a step
         rec.launches_per_step, rec.count = rec.count, 0
-        for _ in range(3):
-            step_fn()
-        torch.cuda.synchronize()
+        # the same clock ramp as in front of the headline timings: after even a few milliseconds of idling (the host
+        # summarising the previous measurement) the next tens of milliseconds run up to 10 % slow
+        t_ramp = time.perf_counter()
+        while time.perf_counter() - t_ramp < RAMP_SECONDS:
+            for _ in range(8):
+                step_fn()
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
             step_fn(rec)
