@@ -152,7 +152,13 @@ struct EpilogueRows {
 // of the exchange buffer Y, row m (Hp*d is a multiple of 8, so a 16-byte vector never straddles two chunks); RPI rows
 // further down is RPI chunk rows further, and into sender r+1's chunk where m passes Ns (Ns >= 16 >= RPI: once at most).
 // OUT_HEADS: they go to row n of head feature / d of Y = [H][N][d] (d is a multiple of 8).
-template <uint32_t COLS, uint32_t ROWS, int LAYOUT>
+// Cache policy of the stores: what a kernel of the same step reads next stays cached -- [N][D], the head-parallel V (the
+// selection reads it), and the exchange buffer of cocodiff_qkv_proj_pack (its unpack follows: with streaming stores the
+// steps through it were 2 - 3.5 % slower).  In the fused call nothing on this GPU reads the exchange buffers (they are
+// what the all-to-all would send) or, within the step, the head-parallel Q and K (NT_HEADS): streamed past the caches
+// they leave nothing dirty in L2 to be written back under the next round's loads (three-weight launch at 20736 tokens:
+// 970 -> 941 us).
+template <uint32_t COLS, uint32_t ROWS, int LAYOUT, bool NT_HEADS = false>
 __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lane, uint16_t* __restrict__ Y, uint16_t* __restrict__ Y2,
                                            size_t row0, uint32_t tok0, uint32_t feat0, uint32_t M, uint32_t D, const GemmArgs& a) {
     constexpr uint32_t CP = EpilogueRows<COLS>::CP, ROWB = EpilogueRows<COLS>::ROWB;
@@ -191,8 +197,8 @@ __device__ __forceinline__ void store_rows(const unsigned char* ep, uint32_t lan
         if (tok < M) {
             const uint32_t row = RPI * it + rsub;
             const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & (CP - 1u))) << 4));
-            if (to_chunks) *yc = v;
-            if (to_heads || LAYOUT == OUT_SEQ) *yh = v;
+            if (to_chunks) st_vec<LAYOUT == OUT_FUSED>(yc, v);
+            if (to_heads || LAYOUT == OUT_SEQ) st_vec<NT_HEADS>(yh, v);
         }
         tok += RPI;
         yh += step_h;
@@ -255,7 +261,7 @@ __device__ __forceinline__ void store_rows_select(const unsigned char* ep, uint3
             const uint32_t row = RPI * it + rsub;
             const vec16 v = *reinterpret_cast<const vec16*>(ep + row * ROWB + ((c16 ^ (row & 7u)) << 4));
             const vec16 pv = prev_rows[it];
-            *yc = v;
+            st_nt(yc, v);
             *yh = v;
             if (vec_suspect(v, pv, a.sel_th.tau_s)) {
                 bool tie = false;
@@ -448,9 +454,9 @@ __device__ __forceinline__ void norm_rope_store(f32x4 (&acc)[NI][NJ], unsigned c
         // a half is complete: out it goes (this wavefront's LDS accesses complete in order, so the next half may
         // overwrite the rows right away)
         if (j == JH - 1)
-            store_rows<NI * 2, JH * 16, OUT_FUSED>(ep, lane, Y, Y2, (size_t)a.row_begin, tok0, feat0, (uint32_t)a.M, (uint32_t)a.D, a);
+            store_rows<NI * 2, JH * 16, OUT_FUSED, true>(ep, lane, Y, Y2, (size_t)a.row_begin, tok0, feat0, (uint32_t)a.M, (uint32_t)a.D, a);
         if (j == NJ - 1 && NJ > JH)
-            store_rows<NI * 2, (NJ - JH) * 16, OUT_FUSED>(ep, lane, Y, Y2, (size_t)a.row_begin, tok0 + JH * 16u, feat0, (uint32_t)a.M,
+            store_rows<NI * 2, (NJ - JH) * 16, OUT_FUSED, true>(ep, lane, Y, Y2, (size_t)a.row_begin, tok0 + JH * 16u, feat0, (uint32_t)a.M,
                                                           (uint32_t)a.D, a);
     };
     float2 cs_a[NI][2], cs_b[NI][2];
