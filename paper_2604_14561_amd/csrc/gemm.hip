@@ -334,25 +334,44 @@ __device__ __forceinline__ void stage_tile16(const f32x4 (&acc)[NI][NJ], unsigne
 // The token tiles go through the staging rows in two halves (the first (NJ+1)/2, then the rest), which is what leaves
 // room for the table; a token tile's accumulators are dead once it is staged, so the whole thing fits the registers
 // the K loop had.
-// tok0 / feat0: the wavefront's first token within the launch's rows / first feature within its tensor.  Rows past the
+// tile_m0: the tile's first token within the launch's rows; tok0 / feat0: the wavefront's first token within the launch's
+// rows / first feature within its tensor.  Rows past the
 // launch's last token (ragged tile; never stored) rotate by some row of the table.
 template <int NI, int NJ, int WN, bool IN_LDS>
 __device__ __forceinline__ void norm_rope_store(f32x4 (&acc)[NI][NJ], unsigned char* ep, float* xch, float* tab, const GemmArgs& a,
                                                 const uint16_t* __restrict__ gamma, uint16_t* __restrict__ Y, uint16_t* __restrict__ Y2,
-                                                uint32_t lane, uint32_t wave, uint32_t tok0, uint32_t feat0) {
+                                                uint32_t lane, uint32_t wave, uint32_t tile_m0, uint32_t tok0, uint32_t feat0) {
     constexpr uint32_t WF = NI * 16;                 // features per wavefront
     constexpr int JH = (NJ + 1) / 2;                 // token tiles in the first half
     const uint32_t g4 = lane >> 4, tl = lane & 15u;
     if (IN_LDS) {
+        // Only the table rows the tile's tokens touch are copied (each to its usual place): along an axis the tile's
+        // consecutive tokens cover consecutive coordinates, `span` of them from `first` on, wrapping -- all rows of the
+        // fastest axis as a rule, two to four of the others: about half of the table.
         const float2* __restrict__ src = reinterpret_cast<const float2*>(a.rope.cs);
-        for (int x = 0; x < a.rope.n_axes; ++x) {
-            const uint32_t first = a.tab_cum[x], count = (uint32_t)a.rope.grid[x] * (uint32_t)a.rope.pairs[x];
+        uint32_t lo = (uint32_t)a.row_begin + tile_m0;
+        uint32_t hi = min(lo + 2u * NJ * 16u, (uint32_t)a.row_begin + (uint32_t)a.M) - 1u;
+        uint32_t first[3], span[3];
+#pragma unroll
+        for (int x = 2; x >= 0; --x) {
+            const uint32_t g = (uint32_t)a.rope.grid[x];      // absent axes: 1
+            first[x] = lo % g;
+            span[x] = min(hi - lo + 1u, g);
+            lo /= g;
+            hi /= g;
+        }
+#pragma unroll
+        for (int x = 0; x < 3; ++x) {
+            if (x >= a.rope.n_axes) continue;
+            const uint32_t g = (uint32_t)a.rope.grid[x], pr = (uint32_t)a.rope.pairs[x], count = span[x] * pr;
             float* dst = tab + a.row_base[x];
 #pragma unroll 4
             for (uint32_t e = wave * 64u + lane; e < count; e += 128u * WN) {
-                const uint32_t r = __umulhi(e, a.tab_magic[x]);             // e / pairs[x]
-                const uint32_t p = e - r * (uint32_t)a.rope.pairs[x];
-                *reinterpret_cast<float2*>(dst + r * a.row_stride[x] + 2u * p) = src[first + e];
+                const uint32_t k = __umulhi(e, a.tab_magic[x]);             // e / pairs[x]
+                const uint32_t p = e - k * pr;
+                uint32_t r = first[x] + k;
+                r -= r >= g ? g : 0u;
+                *reinterpret_cast<float2*>(dst + r * a.row_stride[x] + 2u * p) = src[a.tab_cum[x] + r * pr + p];
             }
         }
     }
@@ -692,10 +711,10 @@ __global__ void __launch_bounds__(128 * WN) qkv_gemm_direct_kernel(GemmArgs a) {
             float* xch = reinterpret_cast<float*>(smem + WAVES * kHalfBytes);
             if (a.tab_lds)
                 norm_rope_store<NI, NJ, WN, true>(acc, smem + wave * kHalfBytes, xch, xch + WAVES * NJ * 16, a, a.gamma[tc.tensor],
-                                                  a.y[tc.tensor], a.y2[tc.tensor], lane, wave, tc.m0 + wave_t, tc.f0 + wave_f);
+                                                  a.y[tc.tensor], a.y2[tc.tensor], lane, wave, tc.m0, tc.m0 + wave_t, tc.f0 + wave_f);
             else
                 norm_rope_store<NI, NJ, WN, false>(acc, smem + wave * kHalfBytes, xch, nullptr, a, a.gamma[tc.tensor], a.y[tc.tensor],
-                                                   a.y2[tc.tensor], lane, wave, tc.m0 + wave_t, tc.f0 + wave_f);
+                                                   a.y2[tc.tensor], lane, wave, tc.m0, tc.m0 + wave_t, tc.f0 + wave_f);
             return;
         }
     }
